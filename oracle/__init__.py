@@ -1,0 +1,2 @@
+"""CPU oracle for the GEMM hot path.  Test infrastructure only: nothing in the
+product package imports this."""
