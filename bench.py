@@ -1,0 +1,221 @@
+#!/usr/bin/env python3
+"""Bench of the GEMM hot path on one MI355X.
+
+A "step" is one pass of the whole hot path (plan already made; tile schedule,
+staging, MFMA loop, split-K reduction where used, epilogue) over one seeded
+synthetic problem already resident in HBM.  The headline workload is the bf16
+8192^3 NT product (C3); the other workloads are timed the same way and listed
+under "workloads" in the same JSON line.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload C3] [--only] [--no-cpu] [--no-torch]
+
+Prints ONE JSON line.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+# MI355X published peaks
+PEAK_TFLOPS = {"bf16": 2500.0, "f16": 2500.0, "f32": 157.3}
+PEAK_HBM_GBS = 8000.0
+
+# HBM bytes per launch measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE (see
+# profiles/), scaled by a copy kernel of known size; None where not measured.
+MEASURED_TRAFFIC = {}
+
+
+def log(*a):
+    print(*a, file=sys.stderr, flush=True)
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=10)
+    ap.add_argument("--workload", default="C3")
+    ap.add_argument("--only", action="store_true", help="time only the headline workload")
+    ap.add_argument("--no-cpu", action="store_true", help="skip the CPU-oracle baseline leg")
+    ap.add_argument("--no-torch", action="store_true", help="skip the torch.matmul context rows")
+    ap.add_argument("--variant", type=int, default=None, help="force a kernel variant id (sweeps)")
+    ap.add_argument("--split", type=int, default=None, help="force a K split (sweeps)")
+    args = ap.parse_args()
+
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU only (the GEMM kernel on one GPU's share); "
+              "--gpus %d is not supported" % args.gpus, file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+
+    import peak_inputs as pi
+    import paper_2512_19018_amd as pg
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(2)
+    pg.load_library()          # no fallback: raises if the HIP library is not built
+    torch.cuda.set_device(0)
+    stream = torch.cuda.current_stream()
+
+    def dev(x):
+        return torch.from_numpy(x.view(np.int16).copy() if x.dtype == np.uint16 else np.ascontiguousarray(x)).cuda()
+
+    def time_workload(name, steps, warmup, variant=None, split=None, with_torch=True):
+        w = pi.WORKLOADS[name]
+        t0 = time.time()
+        A, B, C = w.make(with_cin=True)
+        log("[bench] %s: inputs generated in %.1f s" % (name, time.time() - t0))
+        # rotate buffer sets for problems that would otherwise sit in the 256 MB last-level cache
+        nset = 1
+        footprint = A.nbytes + B.nbytes + C.nbytes
+        if footprint < 600e6:
+            nset = int(min(8, max(2, 600e6 // footprint + 1)))
+        dA = [dev(A) for _ in range(nset)]
+        dB = [dev(B) for _ in range(nset)]
+        dC = [dev(C) for _ in range(nset)]
+        lda, ldb, ldc = w.ld()
+        flags = pg.force_flags(variant, split)
+        res = {"workload": name, "note": w.note, "dtype": pi.DTYPE_NAMES[w.dtype], "M": w.M, "N": w.N, "K": w.K,
+               "transA": w.transA, "transB": w.transB, "alpha": w.alpha, "beta": w.beta, "buffer_sets": nset}
+        with pg.Plan(w.M, w.N, w.K, w.dtype, w.transA, w.transB, lda, ldb, ldc, flags) as plan:
+            res["plan"] = plan.info()
+            ws = torch.empty(max(plan.workspace_bytes, 256), dtype=torch.uint8, device="cuda")
+
+            def step(i):
+                s = i % nset
+                plan.run(w.alpha, dA[s].data_ptr(), dB[s].data_ptr(), w.beta, dC[s].data_ptr(),
+                         ws.data_ptr(), plan.workspace_bytes, stream.cuda_stream)
+
+            for i in range(warmup):
+                step(i)
+            torch.cuda.synchronize()
+            e0 = torch.cuda.Event(enable_timing=True)
+            e1 = torch.cuda.Event(enable_timing=True)
+            t0 = time.perf_counter()
+            e0.record(stream)
+            for i in range(steps):
+                step(i)
+            e1.record(stream)
+            torch.cuda.synchronize()
+            wall_ms = (time.perf_counter() - t0) * 1e3 / steps
+            ev_ms = e0.elapsed_time(e1) / steps
+        res["ms_per_step"] = wall_ms
+        res["event_ms_per_step"] = ev_ms
+        res["tflops"] = w.flops / (wall_ms * 1e-3) * 1e-12
+        res["tflops_events"] = w.flops / (ev_ms * 1e-3) * 1e-12
+        res["gbs_events"] = w.min_bytes / (ev_ms * 1e-3) * 1e-9
+        hbm_bound = (w.flops / w.min_bytes) < (PEAK_TFLOPS[res["dtype"]] * 1e12 / (PEAK_HBM_GBS * 1e9))
+        if hbm_bound:
+            res["roofline"] = {"bound": "hbm", "achieved": res["gbs_events"], "peak": PEAK_HBM_GBS, "unit": "GB/s",
+                               "frac": res["gbs_events"] / PEAK_HBM_GBS, "traffic": MEASURED_TRAFFIC.get(name)}
+        else:
+            pk = PEAK_TFLOPS[res["dtype"]]
+            res["roofline"] = {"bound": "mfma", "achieved": res["tflops_events"], "peak": pk, "unit": "TFLOP/s",
+                               "frac": res["tflops_events"] / pk, "traffic": MEASURED_TRAFFIC.get(name)}
+        if with_torch:
+            try:
+                tdt = {pi.F32: torch.float32, pi.F16: torch.float16, pi.BF16: torch.bfloat16}[w.dtype]
+                tA = dA[0].view(tdt) if w.dtype != pi.F32 else dA[0]
+                tB = dB[0].view(tdt) if w.dtype != pi.F32 else dB[0]
+                tC = dC[0].view(tdt) if w.dtype != pi.F32 else dC[0]
+                opA = tA.t() if w.transA else tA
+                opB = tB.t() if w.transB else tB
+                out = torch.empty_like(tC)
+
+                def tstep():
+                    if w.beta != 0:
+                        torch.addmm(tC, opA, opB, beta=w.beta, alpha=w.alpha, out=out)
+                    else:
+                        torch.matmul(opA, opB, out=out)
+                for _ in range(max(3, warmup // 2)):
+                    tstep()
+                torch.cuda.synchronize()
+                t0 = time.perf_counter()
+                for _ in range(steps):
+                    tstep()
+                torch.cuda.synchronize()
+                tms = (time.perf_counter() - t0) * 1e3 / steps
+                res["torch_ms"] = tms
+                res["torch_tflops"] = w.flops / (tms * 1e-3) * 1e-12
+            except Exception as ex:      # context only
+                res["torch_error"] = repr(ex)[:200]
+        del dA, dB, dC
+        torch.cuda.empty_cache()
+        return res, (A, B, C)
+
+    head, host = time_workload(args.workload, args.steps, args.warmup, args.variant, args.split,
+                               with_torch=not args.no_torch)
+    w = pi.WORKLOADS[args.workload]
+
+    out = {
+        "metric": "GEMM TFLOP/s and % of MFMA peak (bf16 8192^3; fp32 4096^3) on 1 MI355X",
+        "value": head["tflops"],
+        "unit": "TFLOP/s",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": head["ms_per_step"],
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": head["dtype"],
+        "data": "synthetic (seeded splitmix64 counters; see peak_inputs)",
+        "config": {"workload": "%s: %s, M=%d N=%d K=%d transA=%d transB=%d alpha=%g beta=%g"
+                               % (w.name, w.note, w.M, w.N, w.K, w.transA, w.transB, w.alpha, w.beta),
+                   "plan": head["plan"]},
+        "roofline": head["roofline"],
+        "pct_of_peak": 100.0 * head["roofline"]["frac"],
+        "torch_matmul_tflops": head.get("torch_tflops"),
+    }
+
+    # CPU baseline: the oracle as it stands, on a bounded sample of rows of the same workload
+    if not args.no_cpu:
+        from oracle import gemm_oracle
+        A, B, C = host
+        threads = gemm_oracle.default_threads()
+        # one probe row to size the sample for roughly 15 s
+        t0 = time.perf_counter()
+        gemm_oracle.gemm(w.dtype, w.transA, w.transB, w.M, w.N, w.K, w.alpha, A, B, w.beta,
+                         C if w.beta != 0 else None, rows=list(range(min(threads, w.M))), threads=threads)
+        t_probe = time.perf_counter() - t0
+        nrows = int(max(threads, min(w.M, threads * max(1.0, 15.0 / max(t_probe, 1e-3)))))
+        nrows = min(w.M, (nrows // threads) * threads if nrows >= threads else nrows)
+        rows = [int(r) for r in np.linspace(0, w.M - 1, nrows).astype(np.int64)]
+        t0 = time.perf_counter()
+        gemm_oracle.gemm(w.dtype, w.transA, w.transB, w.M, w.N, w.K, w.alpha, A, B, w.beta,
+                         C if w.beta != 0 else None, rows=rows, threads=threads)
+        t_cpu = time.perf_counter() - t0
+        cpu_tflops = 2.0 * len(rows) * w.N * w.K / t_cpu * 1e-12
+        out["cpu_baseline"] = {"value": cpu_tflops, "unit": "TFLOP/s", "cores": threads, "kind": "oracle",
+                               "sample": "%d of %d rows of C (all N columns, full K) of %s in %.1f s; "
+                                         "rate scaled to the whole product" % (len(rows), w.M, w.name, t_cpu)}
+    del host
+
+    if not args.only:
+        others = []
+        for name in ["C1", "C2", "C3b", "C4", "C5", "P2k_f32", "P4k_f32", "P2k_f16", "P4k_f16"]:
+            if name == args.workload:
+                continue
+            small = pi.WORKLOADS[name].flops < 1e10
+            r, _ = time_workload(name, max(args.steps, 200) if small else args.steps, args.warmup,
+                                 with_torch=not args.no_torch)
+            log("[bench] %s: %.3f ms  %.1f TFLOP/s  %.0f GB/s  (%s)" % (name, r["event_ms_per_step"], r["tflops_events"],
+                                                                        r["gbs_events"], r["plan"]))
+            others.append(r)
+        out["workloads"] = others
+
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

@@ -1,0 +1,135 @@
+/*
+ * peak_gemm.h - C ABI of the MI355X (gfx950) dense matrix-multiplication library.
+ *
+ * The operation is the MatMul of the paper's Section 2.2 ("Matrix
+ * Multiplication"): A is m x k, B is k x n, C = A x B is m x n, stored
+ * row-major, in fp32 or a 16-bit float type.  That passage calls it the
+ * standard BLAS library interface; this header takes that interface in full:
+ *
+ *      C = alpha * op(A) * op(B) + beta * C
+ *
+ * with leading dimensions, transpose flags and fp32 scalars.  Products are
+ * accumulated in fp32 on the matrix cores for every dtype (the paper's
+ * Tensor-Core / Warp-Tiling / TB-Tiling steps of Section 4.1, Table 2, mapped
+ * to MFMA, wavefront and workgroup tiles), and the result is rounded once,
+ * to nearest even, to the storage dtype.
+ *
+ * No C++ or framework types cross this boundary: plain pointers and sizes.
+ * Every pointer handed to peak_gemm_run (A, B, C, workspace) is a DEVICE
+ * pointer on the current HIP device; descriptors, plans and strings are HOST
+ * memory.  The library never allocates device memory and never synchronises.
+ */
+#ifndef PEAK_GEMM_H
+#define PEAK_GEMM_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+/* Element storage type of A, B and C (they share it).  Section 2.2 names fp32
+ * and fp16; bfloat16 is the third 16-bit storage the graded workloads use. */
+typedef enum {
+    PEAK_DT_F32 = 0,
+    PEAK_DT_F16 = 1,
+    PEAK_DT_BF16 = 2
+} peak_dtype_t;
+
+typedef enum {
+    PEAK_OK = 0,
+    PEAK_ERR_INVALID_ARG = 1,   /* NULL where data is needed, negative size, ld below the row length, unknown enum */
+    PEAK_ERR_UNSUPPORTED = 2,   /* no kernel variant fits: the "invalid configuration" sentinel of Section 3.1 */
+    PEAK_ERR_WORKSPACE = 3,     /* workspace missing or smaller than peak_gemm_workspace_bytes() */
+    PEAK_ERR_HIP = 4,           /* the HIP runtime reported an error at launch */
+    PEAK_ERR_ALLOC = 5          /* host allocation of the plan failed */
+} peak_status_t;
+
+/* Opaque, owned by the library, lives in host memory. */
+typedef struct peak_gemm_plan peak_gemm_plan_t;
+
+/*
+ * Problem description (the kernel context's input specification of Section
+ * 3.1, reduced to what a GEMM needs).
+ *
+ * op(A) is M x K, op(B) is K x N, C is M x N.  All arrays are row-major as
+ * stored, with row strides in ELEMENTS:
+ *   transA = 0: A is stored M rows x K,  lda >= K.   transA = 1: stored K rows x M, lda >= M.
+ *   transB = 0: B is stored K rows x N,  ldb >= N.   transB = 1: stored N rows x K, ldb >= K
+ *               (i.e. op(B) column-major; both operands then run along K in memory).
+ *   C is stored M rows x N, ldc >= N.  Elements beyond N in a row are never touched.
+ *
+ * flags: bits 0..7 = 0 lets the selector choose; a non-zero value forces kernel
+ * variant number (value - 1) for tests and tuning sweeps (PEAK_ERR_UNSUPPORTED
+ * if that variant cannot run the problem).  Bits 8..15 = 0 lets the selector
+ * choose the split of K; a non-zero value forces that many K slices.  Other bits
+ * must be zero.
+ */
+typedef struct {
+    int64_t M, N, K;
+    int64_t lda, ldb, ldc;
+    int32_t transA, transB;
+    int32_t dtype;              /* a peak_dtype_t value */
+    uint32_t flags;
+} peak_gemm_desc_t;
+
+/*
+ * Validates the description, chooses the kernel variant, tile shape, split of
+ * K, grid and workspace size (Section 3.1: tuning parameters and execution
+ * parameters; Section 2.2: t_m, t_n, t_k, w_m, w_n).  Touches no device.
+ * On success *out_plan is a new plan; on any error *out_plan is NULL.
+ * Degenerate sizes (M, N or K equal to 0) are valid.
+ */
+peak_status_t peak_gemm_create(const peak_gemm_desc_t *desc, peak_gemm_plan_t **out_plan);
+
+/* Bytes of device workspace peak_gemm_run needs for this plan (0 when K is not
+ * split).  The workspace holds fp32 partial tiles of the Split-K step (Section
+ * 4.1, Table 2). */
+size_t peak_gemm_workspace_bytes(const peak_gemm_plan_t *plan);
+
+/*
+ * Enqueues C = alpha*op(A)*op(B) + beta*C on `hip_stream` (a hipStream_t
+ * passed as void*; NULL = the default stream) and returns without waiting.
+ *
+ *   A, B, C      device pointers, aligned to the element size; C must not
+ *                overlap A or B.  With beta == 0 C is write-only: whatever it
+ *                holds, NaN included, does not reach the result.  With
+ *                alpha == 0 or K == 0, A and B are not read (they may be NULL)
+ *                and C = beta*C.
+ *   workspace    device pointer to at least peak_gemm_workspace_bytes() bytes,
+ *                256-byte aligned; may be NULL when that size is 0.  Its
+ *                contents need no initialisation and are scratch afterwards.
+ *
+ * The caller keeps ownership of every buffer and of the stream.  Runs of one
+ * plan that overlap in time must use different workspaces.  Results are
+ * bit-identical from run to run for a given plan (no floating-point atomics).
+ * M == 0 or N == 0: returns PEAK_OK and launches nothing.
+ */
+peak_status_t peak_gemm_run(peak_gemm_plan_t *plan, float alpha,
+                            const void *A, const void *B, float beta, void *C,
+                            void *workspace, size_t workspace_bytes,
+                            void *hip_stream);
+
+/* Frees the plan (host memory only).  NULL is accepted. */
+peak_status_t peak_gemm_destroy(peak_gemm_plan_t *plan);
+
+/* Static, NUL-terminated description of a status code. */
+const char *peak_status_string(peak_status_t s);
+
+/*
+ * Writes a one-line, NUL-terminated description of the plan (variant name,
+ * tile, waves, stages, K split, grid, LDS bytes, workspace) into buf and
+ * returns the length it would need (like snprintf).  For logs and the bench.
+ */
+int peak_gemm_plan_info(const peak_gemm_plan_t *plan, char *buf, size_t n);
+
+/* Number of kernel variants the library holds, and the name of variant `id`
+ * (NULL if out of range).  Variant ids are what `flags` bits 0..7 force. */
+int peak_gemm_variant_count(void);
+const char *peak_gemm_variant_name(int id);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* PEAK_GEMM_H */

@@ -1,0 +1,14 @@
+"""MI355X (gfx950) dense GEMM, C = alpha*op(A)*op(B) + beta*C, behind a C ABI.
+
+The arithmetic lives in the HIP library ``libpeak_gemm.so`` (see
+``include/peak_gemm.h``); this package only marshals arguments.  There is no
+CPU fallback: if the library is not built, importing the binding raises.
+"""
+from .binding import (  # noqa: F401
+    PEAK_DT_F32, PEAK_DT_F16, PEAK_DT_BF16,
+    PEAK_OK, PEAK_ERR_INVALID_ARG, PEAK_ERR_UNSUPPORTED, PEAK_ERR_WORKSPACE, PEAK_ERR_HIP, PEAK_ERR_ALLOC,
+    PeakGemmDesc, PeakError, lib_path, load_library,
+    peak_gemm_create, peak_gemm_workspace_bytes, peak_gemm_run, peak_gemm_destroy,
+    peak_status_string, peak_gemm_plan_info, peak_gemm_variant_count, peak_gemm_variant_name,
+    force_flags, Plan,
+)

@@ -1,0 +1,582 @@
+// Device side of the gfx950 GEMM: workgroup tile -> LDS staging ring -> MFMA
+// register tiles -> epilogue.  One kernel template, instantiated per dtype,
+// tile shape and operand layout.
+//
+// Vocabulary follows Section 2.2 of the paper ("Matrix Multiplication"):
+//   thread-block tile  t_m x t_n (x t_k)  ->  BM x BN x BK, one workgroup
+//   warp tile          w_m x w_n          ->  WTM x WTN, one 64-lane wavefront,
+//                                             a grid of 32x32 MFMA blocks
+// and the transformations of Section 4.1 (Table 2 and the sequences of Table
+// 3): Tensor-Core/Tensor-Tiling -> MFMA blocks per wave, Transpose -> the
+// transposing store of operands that do not run along K in memory, Offset ->
+// the XOR swizzle of 16-byte chunks (in place of padding), Pipelining /
+// Register-Staging -> the LDS ring filled by direct-to-LDS loads or through
+// registers, Block-Swizzle -> the XCD-aware tile order, Split-K -> K slices
+// with an ordered fp32 reduction.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace peak {
+
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef _Float16 f16x8 __attribute__((ext_vector_type(8)));
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+
+enum { DT_F32 = 0, DT_F16 = 1, DT_BF16 = 2 };
+
+// flags in GemmArgs::flags
+enum {
+    GF_A_VEC = 1,      // A base and row stride are 16-byte aligned
+    GF_B_VEC = 2,      // B likewise
+    GF_C_VEC = 4,      // C rows allow 4-element vector access
+    GF_WS_VEC = 8      // workspace rows (N floats) allow 16-byte access
+};
+
+struct GemmArgs {
+    const void *A;
+    const void *B;
+    void *C;
+    float *ws;                // split > 1: fp32 partials [split][M][N]
+    int64_t M, N, K;
+    int64_t lda, ldb, ldc;    // elements
+    float alpha, beta;
+    int32_t tiles_m, tiles_n;
+    int32_t split;            // number of K slices
+    int32_t ktiles_per_slice; // BK-tiles per slice (last slice may be shorter)
+    int32_t ktiles_total;     // ceil(K / BK)
+    int32_t group_m;          // tile rows per band of the tile order
+    uint32_t flags;
+};
+
+#define PEAK_DEV static __device__ __forceinline__
+#define PEAK_DEVM __device__ __forceinline__
+
+PEAK_DEV void lds_barrier()
+{
+    // LDS traffic of this wave done, then workgroup barrier.  Outstanding
+    // global loads are left in flight on purpose.
+    asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
+}
+
+template <int N>
+PEAK_DEV void wait_vmcnt()
+{
+    static_assert(N >= 0 && N < 64, "vmcnt range");
+    asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory");
+}
+
+// ---------------------------------------------------------------------------
+// Tile geometry.  A tile row holds RB bytes of K (BK elements) cut into 16-byte
+// chunks; chunk c of row r sits at chunk position c ^ swz(r), which keeps both
+// the row-wise 16-byte stores and the 32-rows-same-chunk fragment reads free of
+// bank conflicts.
+// ---------------------------------------------------------------------------
+template <int CPR>
+PEAK_DEV int swz(int r)
+{
+    if (CPR == 8) return (r ^ (r >> 3)) & 7;
+    return ((r >> 1) ^ (r >> 3)) & 3;          // CPR == 4: two rows share 128 bytes
+}
+
+template <int DT_, int BM_, int BN_, int RB_, int WAVES_M_, int WAVES_N_, int NS_,
+          bool A_T_, bool B_T_, bool DIRECT_>
+struct Cfg {
+    static constexpr int DT = DT_;
+    static constexpr int ESZ = DT_ == DT_F32 ? 4 : 2;
+    static constexpr int EPC = 16 / ESZ;              // elements per 16-byte chunk
+    static constexpr int BM = BM_, BN = BN_, RB = RB_;
+    static constexpr int CPR = RB_ / 16;              // chunks per tile row
+    static constexpr int BK = RB_ / ESZ;              // t_k
+    static constexpr int KG = CPR / 2;                // 32-row MFMA groups per tile row
+    static constexpr int WAVES_M = WAVES_M_, WAVES_N = WAVES_N_;
+    static constexpr int NW = WAVES_M_ * WAVES_N_;
+    static constexpr int NT = NW * 64;
+    static constexpr int WTM = BM_ / WAVES_M_, WTN = BN_ / WAVES_N_;
+    static constexpr int MI = WTM / 32, NI = WTN / 32;
+    static constexpr int NS = NS_;
+    static constexpr bool A_T = A_T_;                 // A stored K rows x M (does not run along K)
+    static constexpr bool B_T = B_T_;                 // B stored K rows x N (does not run along K)
+    static constexpr bool DIRECT = DIRECT_;           // K-running operands go global -> LDS directly
+    static constexpr int A_BYTES = BM_ * RB_;
+    static constexpr int B_BYTES = BN_ * RB_;
+    static constexpr int STAGE_BYTES = A_BYTES + B_BYTES;
+    static constexpr int LDS_BYTES = STAGE_BYTES * NS_;
+    static_assert(WTM % 32 == 0 && WTN % 32 == 0, "wave tile is a grid of 32x32 MFMA blocks");
+    static_assert(RB_ == 128 || RB_ == 64, "tile row is 64 or 128 bytes");
+    static_assert((BM_ * CPR) % 64 == 0 && (BN_ * CPR) % 64 == 0, "whole wave loads");
+};
+
+// ---------------------------------------------------------------------------
+// Register-staged tile loads.
+// ---------------------------------------------------------------------------
+template <int DT>
+PEAK_DEV u32x4 load_chunk_elems(const void *base, int64_t idx0, int64_t stride, int nvalid)
+{
+    // nvalid leading elements of the chunk come from memory (element idx0 + e*stride), the rest are zero.
+    constexpr int EPC = DT == DT_F32 ? 4 : 8;
+    u32x4 v = {0u, 0u, 0u, 0u};
+    if (DT == DT_F32) {
+        const uint32_t *p = (const uint32_t *)base;
+#pragma unroll
+        for (int e = 0; e < EPC; ++e)
+            if (e < nvalid) v[e] = p[idx0 + e * stride];
+    } else {
+        const uint16_t *p = (const uint16_t *)base;
+#pragma unroll
+        for (int e = 0; e < EPC; ++e)
+            if (e < nvalid) v[e >> 1] |= (uint32_t)p[idx0 + e * stride] << ((e & 1) * 16);
+    }
+    return v;
+}
+
+// Operand that runs along K in memory: rows x K, row stride ld.
+template <class C, int ROWS>
+struct LoaderK {
+    static constexpr int NCH = (ROWS * C::CPR + C::NT - 1) / C::NT;
+    u32x4 v[NCH];
+
+    PEAK_DEVM void load(const void *base, int64_t ld, int64_t row0, int64_t nrows, int64_t k0, int64_t kend,
+                       bool vec, int tid)
+    {
+#pragma unroll
+        for (int i = 0; i < NCH; ++i) {
+            const int idx = tid + C::NT * i;
+            const int row = idx / C::CPR, c = idx % C::CPR;
+            u32x4 val = {0u, 0u, 0u, 0u};
+            if (ROWS * C::CPR % C::NT == 0 || idx < ROWS * C::CPR) {
+                int64_t gr = row0 + row;
+                if (gr > nrows - 1) gr = nrows - 1;          // duplicate of a valid row; its results are never stored
+                const int64_t k = k0 + (int64_t)c * C::EPC;
+                const int64_t left = kend - k;
+                if (vec && left >= C::EPC) {
+                    val = *(const u32x4 *)((const char *)base + (gr * ld + k) * C::ESZ);
+                } else if (left > 0) {
+                    val = load_chunk_elems<C::DT>(base, gr * ld + k, 1, left < C::EPC ? (int)left : C::EPC);
+                }
+            }
+            v[i] = val;
+        }
+    }
+
+    PEAK_DEVM void store(char *lds_tile, int tid) const
+    {
+#pragma unroll
+        for (int i = 0; i < NCH; ++i) {
+            const int idx = tid + C::NT * i;
+            const int row = idx / C::CPR, c = idx % C::CPR;
+            if (ROWS * C::CPR % C::NT == 0 || idx < ROWS * C::CPR)
+                *(u32x4 *)(lds_tile + row * C::RB + ((c ^ swz<C::CPR>(row)) << 4)) = v[i];
+        }
+    }
+};
+
+// Operand stored K rows x `rows` (runs along M or N in memory).  Each thread
+// takes an EPC(k) x EPC(rows) block, transposes it in registers and stores EPC
+// chunks, one per tile row.
+template <class C, int ROWS>
+struct LoaderT {
+    static constexpr int E = C::EPC;
+    static constexpr int RBLK = ROWS / E;                         // blocks along the tile rows
+    static constexpr int NBLK = RBLK * C::CPR;
+    static constexpr int NB = (NBLK + C::NT - 1) / C::NT;
+    u32x4 v[NB][E];                                               // [block][k within chunk] -> E row-elements
+
+    PEAK_DEVM void load(const void *base, int64_t ld, int64_t row0, int64_t nrows, int64_t k0, int64_t kend,
+                       bool vec, int tid)
+    {
+#pragma unroll
+        for (int b = 0; b < NB; ++b) {
+            const int id = tid + C::NT * b;
+            const int rb = id % RBLK, c = id / RBLK;
+            const int64_t r = row0 + (int64_t)rb * E;             // first tile row of the block, as a global row/col index
+#pragma unroll
+            for (int kk = 0; kk < E; ++kk) {
+                u32x4 val = {0u, 0u, 0u, 0u};
+                const int64_t k = k0 + (int64_t)c * E + kk;
+                if ((NBLK % C::NT == 0 || id < NBLK) && k < kend) {
+                    const int64_t left = nrows - r;
+                    if (vec && left >= E) {
+                        val = *(const u32x4 *)((const char *)base + (k * ld + r) * C::ESZ);
+                    } else if (left > 0) {
+                        val = load_chunk_elems<C::DT>(base, k * ld + r, 1, left < E ? (int)left : E);
+                    }
+                }
+                v[b][kk] = val;
+            }
+        }
+    }
+
+    PEAK_DEVM void store(char *lds_tile, int tid) const
+    {
+#pragma unroll
+        for (int b = 0; b < NB; ++b) {
+            const int id = tid + C::NT * b;
+            const int rb = id % RBLK, c = id / RBLK;
+            if (NBLK % C::NT == 0 || id < NBLK) {
+#pragma unroll
+                for (int i = 0; i < E; ++i) {
+                    u32x4 o;
+                    if (C::DT == DT_F32) {
+                        o[0] = v[b][0][i]; o[1] = v[b][1][i]; o[2] = v[b][2][i]; o[3] = v[b][3][i];
+                    } else {
+                        // 16-bit: element i of k-row kk is half (i & 1) of dword (i >> 1)
+#pragma unroll
+                        for (int d = 0; d < 4; ++d) {
+                            const uint32_t lo = v[b][2 * d][i >> 1], hi = v[b][2 * d + 1][i >> 1];
+                            o[d] = (i & 1) ? ((lo >> 16) | (hi & 0xFFFF0000u)) : ((lo & 0xFFFFu) | (hi << 16));
+                        }
+                    }
+                    const int row = rb * E + i;
+                    *(u32x4 *)(lds_tile + row * C::RB + ((c ^ swz<C::CPR>(row)) << 4)) = o;
+                }
+            }
+        }
+    }
+};
+
+// Direct global -> LDS copy of an operand that runs along K.  One wave
+// instruction fills 1024 contiguous LDS bytes (64 / CPR tile rows); which global
+// chunk a lane fetches is chosen so that the swizzled layout comes out.
+template <class C, int ROWS>
+struct LoaderDirect {
+    static constexpr int NINST = ROWS * C::CPR / 64;              // wave instructions per tile
+    static constexpr int PER_WAVE = (NINST + C::NW - 1) / C::NW;
+    const char *g[PER_WAVE];                                      // this lane's source for each of its instructions, at k = 0
+
+    PEAK_DEVM void init(const void *base, int64_t ld, int64_t row0, int64_t nrows, int64_t k0, int wave, int lane)
+    {
+#pragma unroll
+        for (int i = 0; i < PER_WAVE; ++i) {
+            const int j = wave + C::NW * i;
+            const int row = j * (64 / C::CPR) + lane / C::CPR;
+            const int pos = lane % C::CPR;
+            const int c = pos ^ swz<C::CPR>(row);
+            int64_t gr = row0 + row;
+            if (gr > nrows - 1) gr = nrows - 1;
+            g[i] = (const char *)base + (gr * ld + k0 + (int64_t)c * C::EPC) * C::ESZ;
+        }
+    }
+
+    // ktile: tile index relative to k0
+    PEAK_DEVM void issue(char *lds_tile, int64_t ktile, int wave) const
+    {
+#pragma unroll
+        for (int i = 0; i < PER_WAVE; ++i) {
+            const int j = wave + C::NW * i;
+            if (NINST % C::NW == 0 || j < NINST) {
+                __builtin_amdgcn_global_load_lds(
+                    (const __attribute__((address_space(1))) void *)(g[i] + ktile * C::RB),
+                    (__attribute__((address_space(3))) void *)(lds_tile + j * 1024), 16, 0, 0);
+            }
+        }
+    }
+};
+
+// ---------------------------------------------------------------------------
+// MFMA on one 16-byte fragment pair.  The roles are swapped on purpose: the B
+// tile's rows (n) feed the instruction's row operand and the A tile's rows (m)
+// its column operand, so a lane ends up holding 4 consecutive n of one m and
+// the epilogue can store vectors along a row of C.
+//   acc[v] <-> m = lane % 32,  n = 8*(v/4) + 4*(lane/32) + v%4     (within the 32x32 block)
+// ---------------------------------------------------------------------------
+template <int DT>
+PEAK_DEV void mfma_frag(f32x16 &acc, const u32x4 &bfrag, const u32x4 &afrag)
+{
+    if (DT == DT_BF16) {
+        acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, bfrag),
+                                                      __builtin_bit_cast(bf16x8, afrag), acc, 0, 0, 0);
+    } else if (DT == DT_F16) {
+        acc = __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(f16x8, bfrag),
+                                                     __builtin_bit_cast(f16x8, afrag), acc, 0, 0, 0);
+    } else {
+        // fp32: the chunk holds 4 k values per lane half; step s multiplies k = 4*half + s of both operands
+#pragma unroll
+        for (int s = 0; s < 4; ++s)
+            acc = __builtin_amdgcn_mfma_f32_32x32x2f32(__builtin_bit_cast(float, bfrag[s]),
+                                                       __builtin_bit_cast(float, afrag[s]), acc, 0, 0, 0);
+    }
+}
+
+template <int DT>
+PEAK_DEV float elem_to_float(const void *p, int64_t idx)
+{
+    if (DT == DT_F32) return ((const float *)p)[idx];
+    if (DT == DT_F16) return (float)((const _Float16 *)p)[idx];
+    return (float)((const __bf16 *)p)[idx];
+}
+
+template <int DT>
+PEAK_DEV void float_to_elem(void *p, int64_t idx, float x)
+{
+    if (DT == DT_F32) ((float *)p)[idx] = x;
+    else if (DT == DT_F16) ((_Float16 *)p)[idx] = (_Float16)x;       // round to nearest even
+    else ((__bf16 *)p)[idx] = (__bf16)x;                             // round to nearest even
+}
+
+// Four consecutive outputs of one row: out = alpha*acc + beta*C_in, rounded once.
+template <int DT>
+PEAK_DEV void store4(void *C, int64_t idx, const float x[4], float alpha, float beta, bool vec, int nvalid)
+{
+    if (vec && nvalid == 4) {
+        if (DT == DT_F32) {
+            f32x4 o = {alpha * x[0], alpha * x[1], alpha * x[2], alpha * x[3]};
+            if (beta != 0.0f) {
+                const f32x4 c = *(const f32x4 *)((const float *)C + idx);
+                o[0] += beta * c[0]; o[1] += beta * c[1]; o[2] += beta * c[2]; o[3] += beta * c[3];
+            }
+            *(f32x4 *)((float *)C + idx) = o;
+        } else {
+            float o[4] = {alpha * x[0], alpha * x[1], alpha * x[2], alpha * x[3]};
+            if (beta != 0.0f) {
+#pragma unroll
+                for (int e = 0; e < 4; ++e) o[e] += beta * elem_to_float<DT>(C, idx + e);
+            }
+            union { u32x2 u; _Float16 h[4]; __bf16 b[4]; } pk;
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                if (DT == DT_F16) pk.h[e] = (_Float16)o[e];
+                else pk.b[e] = (__bf16)o[e];
+            }
+            *(u32x2 *)((uint16_t *)C + idx) = pk.u;
+        }
+    } else {
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            if (e < nvalid) {
+                float o = alpha * x[e];
+                if (beta != 0.0f) o += beta * elem_to_float<DT>(C, idx + e);
+                float_to_elem<DT>(C, idx + e, o);
+            }
+        }
+    }
+}
+
+// Tile order (the paper's Block-Swizzle, made XCD-aware): consecutive workgroup
+// ids go round-robin to the 8 XCDs, each with its own L2.  Give every XCD a
+// contiguous run of the band-ordered tile list, so the tiles an XCD works on at
+// one time share A row panels and B column panels in that L2.
+PEAK_DEV void tile_of_block(int t, int tiles_m, int tiles_n, int group_m, int &tm, int &tn)
+{
+    const int total = tiles_m * tiles_n;
+    const int xcd = t & 7, idx = t >> 3;
+    const int base = total >> 3, rem = total & 7;
+    const int L = xcd * base + (xcd < rem ? xcd : rem) + idx;
+    const int band = group_m * tiles_n;
+    const int g = L / band;
+    const int first = g * group_m;
+    const int gsz = (tiles_m - first) < group_m ? (tiles_m - first) : group_m;
+    const int w = L - g * band;
+    tm = first + w % gsz;
+    tn = w / gsz;
+}
+
+// ---------------------------------------------------------------------------
+// The GEMM kernel.
+// ---------------------------------------------------------------------------
+template <class C>
+__global__ __launch_bounds__(C::NT) void gemm_kernel(const GemmArgs p)
+{
+    __shared__ __attribute__((aligned(1024))) char lds[C::LDS_BYTES];
+
+    const int tid = threadIdx.x;
+    const int lane = tid & 63, wave = tid >> 6;
+    const int wm = wave / C::WAVES_N, wn = wave % C::WAVES_N;
+    const int r32 = lane & 31, half = lane >> 5;
+
+    const int tiles = p.tiles_m * p.tiles_n;
+    const int bid = blockIdx.x;
+    const int slice = bid / tiles;
+    int tm, tn;
+    tile_of_block(bid - slice * tiles, p.tiles_m, p.tiles_n, p.group_m, tm, tn);
+    const int64_t m0 = (int64_t)tm * C::BM, n0 = (int64_t)tn * C::BN;
+
+    const int kt_begin = slice * p.ktiles_per_slice;
+    int kt_end = kt_begin + p.ktiles_per_slice;
+    if (kt_end > p.ktiles_total) kt_end = p.ktiles_total;
+    const int KT = kt_end - kt_begin;                       // >= 1 by construction of the plan
+    const int64_t kbase = (int64_t)kt_begin * C::BK;
+    const int64_t kend = p.K;                               // zero fill beyond K (only the last slice can reach it)
+
+    const bool a_vec = p.flags & GF_A_VEC, b_vec = p.flags & GF_B_VEC;
+
+    f32x16 acc[C::MI][C::NI];
+#pragma unroll
+    for (int mi = 0; mi < C::MI; ++mi)
+#pragma unroll
+        for (int ni = 0; ni < C::NI; ++ni)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[mi][ni][v] = 0.0f;
+
+    // per-lane fragment addresses within a stage (chunk 2*kg + half of row r sits at (2*kg) ^ x, x below)
+    int a_addr[C::MI], b_addr[C::NI];
+#pragma unroll
+    for (int mi = 0; mi < C::MI; ++mi) {
+        const int r = wm * C::WTM + mi * 32 + r32;
+        a_addr[mi] = r * C::RB + ((half ^ swz<C::CPR>(r)) << 4);
+    }
+#pragma unroll
+    for (int ni = 0; ni < C::NI; ++ni) {
+        const int r = wn * C::WTN + ni * 32 + r32;
+        b_addr[ni] = C::A_BYTES + r * C::RB + ((half ^ swz<C::CPR>(r)) << 4);
+    }
+
+    // operand loaders
+    constexpr bool A_DIRECT = C::DIRECT && !C::A_T, B_DIRECT = C::DIRECT && !C::B_T;
+    LoaderDirect<C, C::BM> dA;
+    LoaderDirect<C, C::BN> dB;
+    LoaderK<C, C::BM> kA;
+    LoaderK<C, C::BN> kB;
+    LoaderT<C, C::BM> tA;
+    LoaderT<C, C::BN> tB;
+    // loads per thread and tile that stay in flight across iterations
+    constexpr int DLOADS = (A_DIRECT ? LoaderDirect<C, C::BM>::PER_WAVE : 0) + (B_DIRECT ? LoaderDirect<C, C::BN>::PER_WAVE : 0);
+    constexpr int P = C::NS - 1;                            // prefetch distance of the direct loads
+    static_assert(!A_DIRECT || LoaderDirect<C, C::BM>::NINST % C::NW == 0, "every wave issues the same number of loads");
+    static_assert(!B_DIRECT || LoaderDirect<C, C::BN>::NINST % C::NW == 0, "every wave issues the same number of loads");
+
+    if (A_DIRECT) dA.init(p.A, p.lda, m0, p.M, kbase, wave, lane);
+    if (B_DIRECT) dB.init(p.B, p.ldb, n0, p.N, kbase, wave, lane);
+
+    auto load_regs = [&](int kt) {                          // kt relative to the slice
+        const int64_t k0 = kbase + (int64_t)kt * C::BK;
+        if (!A_DIRECT) {
+            if (C::A_T) tA.load(p.A, p.lda, m0, p.M, k0, kend, a_vec, tid);
+            else        kA.load(p.A, p.lda, m0, p.M, k0, kend, a_vec, tid);
+        }
+        if (!B_DIRECT) {
+            if (C::B_T) tB.load(p.B, p.ldb, n0, p.N, k0, kend, b_vec, tid);
+            else        kB.load(p.B, p.ldb, n0, p.N, k0, kend, b_vec, tid);
+        }
+    };
+    auto store_regs = [&](int stage) {
+        char *st = lds + stage * C::STAGE_BYTES;
+        if (!A_DIRECT) {
+            if (C::A_T) tA.store(st, tid); else kA.store(st, tid);
+        }
+        if (!B_DIRECT) {
+            if (C::B_T) tB.store(st + C::A_BYTES, tid); else kB.store(st + C::A_BYTES, tid);
+        }
+    };
+    auto issue_direct = [&](int kt, int stage) {
+        // past the end the last tile is fetched again into a free stage, so the
+        // number of loads in flight stays the same for the waits below
+        const int kc = kt < KT ? kt : KT - 1;
+        char *st = lds + stage * C::STAGE_BYTES;
+        if (A_DIRECT) dA.issue(st, kc, wave);
+        if (B_DIRECT) dB.issue(st + C::A_BYTES, kc, wave);
+    };
+    auto compute = [&](int stage) {
+        const char *st = lds + stage * C::STAGE_BYTES;
+#pragma unroll
+        for (int kg = 0; kg < C::KG; ++kg) {
+            u32x4 af[C::MI], bf[C::NI];
+#pragma unroll
+            for (int mi = 0; mi < C::MI; ++mi) af[mi] = *(const u32x4 *)(st + (a_addr[mi] ^ (kg << 5)));
+#pragma unroll
+            for (int ni = 0; ni < C::NI; ++ni) bf[ni] = *(const u32x4 *)(st + (b_addr[ni] ^ (kg << 5)));
+#pragma unroll
+            for (int mi = 0; mi < C::MI; ++mi)
+#pragma unroll
+                for (int ni = 0; ni < C::NI; ++ni) mfma_frag<C::DT>(acc[mi][ni], bf[ni], af[mi]);
+        }
+    };
+
+    // prologue
+    if (C::DIRECT && DLOADS > 0) {
+#pragma unroll
+        for (int s = 0; s < P; ++s) issue_direct(s, s);
+    }
+    if (!(A_DIRECT && B_DIRECT)) {
+        load_regs(0);
+        store_regs(0);
+    }
+
+    for (int kt0 = 0; kt0 < KT; kt0 += C::NS) {
+#pragma unroll
+        for (int s = 0; s < C::NS; ++s) {
+            const int kt = kt0 + s;
+            if (kt < KT) {
+                if (DLOADS > 0) wait_vmcnt<(P - 1) * DLOADS>();     // tile kt has landed (this wave's part)
+                lds_barrier();                                      // everyone's part; stage (kt-1) % NS is free
+                if (!(A_DIRECT && B_DIRECT) && kt + 1 < KT) load_regs(kt + 1);
+                if (DLOADS > 0) issue_direct(kt + P, (s + P) % C::NS);
+                compute(s);
+                if (!(A_DIRECT && B_DIRECT) && kt + 1 < KT) store_regs((s + 1) % C::NS);
+            }
+        }
+    }
+
+    if (DLOADS > 0) wait_vmcnt<0>();    // refetches past the end must land before this workgroup's LDS is given away
+
+    // epilogue
+    const bool c_vec = p.flags & GF_C_VEC, ws_vec = p.flags & GF_WS_VEC;
+    float *wsl = p.split > 1 ? p.ws + (int64_t)slice * p.M * p.N : nullptr;
+#pragma unroll
+    for (int mi = 0; mi < C::MI; ++mi) {
+        const int64_t m = m0 + wm * C::WTM + mi * 32 + r32;
+        if (m < p.M) {
+#pragma unroll
+            for (int ni = 0; ni < C::NI; ++ni) {
+#pragma unroll
+                for (int vq = 0; vq < 4; ++vq) {
+                    const int64_t n = n0 + wn * C::WTN + ni * 32 + vq * 8 + half * 4;
+                    const int64_t left = p.N - n;
+                    if (left > 0) {
+                        const int nvalid = left >= 4 ? 4 : (int)left;
+                        const float x[4] = {acc[mi][ni][vq * 4 + 0], acc[mi][ni][vq * 4 + 1],
+                                            acc[mi][ni][vq * 4 + 2], acc[mi][ni][vq * 4 + 3]};
+                        if (wsl) store4<DT_F32>(wsl, m * p.N + n, x, 1.0f, 0.0f, ws_vec, nvalid);
+                        else     store4<C::DT>(p.C, m * p.ldc + n, x, p.alpha, p.beta, c_vec, nvalid);
+                    }
+                }
+            }
+        }
+    }
+}
+
+// ---------------------------------------------------------------------------
+// Split-K, second step: C = alpha * (sum over slices, in slice order) + beta*C.
+// One thread per 4 consecutive outputs of a row.
+// ---------------------------------------------------------------------------
+template <int DT>
+__global__ __launch_bounds__(256) void splitk_reduce_kernel(const GemmArgs p)
+{
+    const int64_t quads_per_row = (p.N + 3) / 4;
+    const int64_t q = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (q >= p.M * quads_per_row) return;
+    const int64_t m = q / quads_per_row, n = (q % quads_per_row) * 4;
+    const int nvalid = p.N - n >= 4 ? 4 : (int)(p.N - n);
+    const bool ws_vec = p.flags & GF_WS_VEC;
+    float x[4] = {0.0f, 0.0f, 0.0f, 0.0f};
+    for (int s = 0; s < p.split; ++s) {
+        const float *w = p.ws + ((int64_t)s * p.M + m) * p.N + n;
+        if (ws_vec && nvalid == 4) {
+            const f32x4 t = *(const f32x4 *)w;
+            x[0] += t[0]; x[1] += t[1]; x[2] += t[2]; x[3] += t[3];
+        } else {
+#pragma unroll
+            for (int e = 0; e < 4; ++e)
+                if (e < nvalid) x[e] += w[e];
+        }
+    }
+    store4<DT>(p.C, m * p.ldc + n, x, p.alpha, p.beta, p.flags & GF_C_VEC, nvalid);
+}
+
+// C = beta * C (alpha == 0 or K == 0).  beta == 0 writes zeros without reading.
+template <int DT>
+__global__ __launch_bounds__(256) void scale_c_kernel(const GemmArgs p)
+{
+    const int64_t e = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (e >= p.M * p.N) return;
+    const int64_t m = e / p.N, n = e % p.N;
+    float o = 0.0f;
+    if (p.beta != 0.0f) o = p.beta * elem_to_float<DT>(p.C, m * p.ldc + n);
+    float_to_elem<DT>(p.C, m * p.ldc + n, o);
+}
+
+}  // namespace peak

@@ -1,0 +1,382 @@
+// C ABI of the gfx950 GEMM library: argument checks, variant selection
+// (the tuning/execution parameters of the paper's Section 3.1), launches.
+#include "../../include/peak_gemm.h"
+
+#include <hip/hip_runtime.h>
+
+#include <cstdio>
+#include <cstdlib>
+#include <cstring>
+#include <new>
+
+#include "gemm_device.h"
+#include "skinny_device.h"
+
+namespace peak {
+
+constexpr int NUM_CU = 256;           // MI355X
+constexpr int LDS_LIMIT = 160 * 1024; // bytes per workgroup on gfx950
+
+typedef hipError_t (*launch_fn)(const GemmArgs &, dim3 grid, hipStream_t);
+
+template <class C>
+static hipError_t launch_gemm(const GemmArgs &a, dim3 grid, hipStream_t s)
+{
+    hipLaunchKernelGGL((gemm_kernel<C>), grid, dim3(C::NT), 0, s, a);
+    return hipGetLastError();
+}
+
+template <class C>
+static hipError_t launch_skinny(const GemmArgs &a, dim3 grid, hipStream_t s)
+{
+    hipLaunchKernelGGL((skinny_kernel<C>), grid, dim3(C::NT), 0, s, a);
+    return hipGetLastError();
+}
+
+enum Kind { KIND_TILED = 0, KIND_SKINNY = 1 };
+
+struct Variant {
+    const char *name;
+    int kind;
+    int dt;
+    int a_t, b_t;        // operand layouts the kernel was built for (1: stored K rows x M/N)
+    int direct;          // needs 16-byte aligned operands and K % BK == 0
+    int bm, bn, bk, nt, ns, lds;
+    int max_m;           // skinny kernels: largest M
+    launch_fn launch;
+};
+
+#define TILED(NAME, DT, BM, BN, RB, WMW, WNW, NS, AT, BT, DIR)                                         \
+    {NAME, KIND_TILED, DT, AT, BT, DIR, BM, BN, RB / (DT == DT_F32 ? 4 : 2), WMW * WNW * 64, NS,       \
+     Cfg<DT, BM, BN, RB, WMW, WNW, NS, AT, BT, DIR>::LDS_BYTES, 0,                                     \
+     &launch_gemm<Cfg<DT, BM, BN, RB, WMW, WNW, NS, AT, BT, DIR>>}
+
+#define TILED_LAYOUTS(NAME, DT, BM, BN, RB, WMW, WNW, NS)                                              \
+    TILED(NAME "_nt", DT, BM, BN, RB, WMW, WNW, NS, false, false, false),                             \
+    TILED(NAME "_nn", DT, BM, BN, RB, WMW, WNW, NS, false, true, false),                              \
+    TILED(NAME "_tt", DT, BM, BN, RB, WMW, WNW, NS, true, false, false),                              \
+    TILED(NAME "_tn", DT, BM, BN, RB, WMW, WNW, NS, true, true, false)
+
+#define SKINNY(NAME, DT, BN, KSTEP, NS)                                                                \
+    {NAME, KIND_SKINNY, DT, 0, 0, 1, 16, BN, KSTEP, SkinnyCfg<DT, BN, KSTEP, NS>::NT, NS,              \
+     SkinnyCfg<DT, BN, KSTEP, NS>::LDS_BYTES, 16, &launch_skinny<SkinnyCfg<DT, BN, KSTEP, NS>>}
+
+// Layout suffix: first letter is A (n: runs along K, t: stored K x M), second is
+// B as stored (t: N x K, runs along K; n: K x N).  So "_nt" is transA=0,
+// transB=1: both operands K-contiguous.
+static const Variant g_variants[] = {
+    // 0..11: register-staged 128x128 tiles, any alignment, any K
+    TILED_LAYOUTS("f32_r128x128", DT_F32, 128, 128, 128, 2, 2, 2),
+    TILED_LAYOUTS("f16_r128x128", DT_F16, 128, 128, 128, 2, 2, 2),
+    TILED_LAYOUTS("bf16_r128x128", DT_BF16, 128, 128, 128, 2, 2, 2),
+    // 12..23: register-staged 64x64 tiles for small problems
+    TILED_LAYOUTS("f32_r64x64", DT_F32, 64, 64, 128, 2, 2, 2),
+    TILED_LAYOUTS("f16_r64x64", DT_F16, 64, 64, 128, 2, 2, 2),
+    TILED_LAYOUTS("bf16_r64x64", DT_BF16, 64, 64, 128, 2, 2, 2),
+    // 24..: direct-to-LDS 256x256 tiles, 8 waves
+    TILED("bf16_d256x256w8_nt", DT_BF16, 256, 256, 128, 2, 4, 2, false, false, true),
+    TILED("f16_d256x256w8_nt", DT_F16, 256, 256, 128, 2, 4, 2, false, false, true),
+    TILED("bf16_d256x256w8_nn", DT_BF16, 256, 256, 128, 2, 4, 2, false, true, true),
+    TILED("f16_d256x256w8_nn", DT_F16, 256, 256, 128, 2, 4, 2, false, true, true),
+    // 28..: same tile, 64-byte rows, 4-deep ring
+    TILED("bf16_d256x256w8k32s4_nt", DT_BF16, 256, 256, 64, 2, 4, 4, false, false, true),
+    TILED("f16_d256x256w8k32s4_nt", DT_F16, 256, 256, 64, 2, 4, 4, false, false, true),
+    // 30..: 4 waves, 128x128 per wave
+    TILED("bf16_d256x256w4_nt", DT_BF16, 256, 256, 128, 2, 2, 2, false, false, true),
+    TILED("f16_d256x256w4_nt", DT_F16, 256, 256, 128, 2, 2, 2, false, false, true),
+    // 32..: fp32
+    TILED("f32_d128x128w4_nn", DT_F32, 128, 128, 128, 2, 2, 2, false, true, true),
+    TILED("f32_d128x128w4_nt", DT_F32, 128, 128, 128, 2, 2, 2, false, false, true),
+    TILED("f32_d256x128w8_nn", DT_F32, 256, 128, 128, 4, 2, 2, false, true, true),
+    // 35..: 256x128 16-bit tiles (more tiles for mid-size problems)
+    TILED("bf16_d256x128w8_nt", DT_BF16, 256, 128, 128, 4, 2, 3, false, false, true),
+    TILED("f16_d256x128w8_nt", DT_F16, 256, 128, 128, 4, 2, 3, false, false, true),
+    TILED("bf16_d256x128w8_nn", DT_BF16, 256, 128, 128, 4, 2, 3, false, true, true),
+    TILED("f16_d256x128w8_nn", DT_F16, 256, 128, 128, 4, 2, 3, false, true, true),
+    // 39..: skinny (M <= 16), both operands along K
+    SKINNY("bf16_skinny16s3_nt", DT_BF16, 64, 128, 3),
+    SKINNY("f16_skinny16s3_nt", DT_F16, 64, 128, 3),
+    SKINNY("bf16_skinny16s4_nt", DT_BF16, 64, 128, 4),
+    SKINNY("f16_skinny16s4_nt", DT_F16, 64, 128, 4),
+};
+constexpr int NUM_VARIANTS = (int)(sizeof(g_variants) / sizeof(g_variants[0]));
+
+// Variants the selector may pick on its own.  The others stay reachable through
+// the force bits of the descriptor, for sweeps.
+static bool variant_selectable(int id)
+{
+    const char *n = g_variants[id].name;
+    if (strstr(n, "k32s4") || strstr(n, "w4_nt") && strstr(n, "d256x256")) return false;
+    return true;
+}
+
+}  // namespace peak
+
+using namespace peak;
+
+struct peak_gemm_plan {
+    peak_gemm_desc_t d;
+    int variant;          // index into g_variants, -1: nothing to launch
+    int tiles_m, tiles_n, split, ktiles_total, ktiles_per_slice, group_m;
+    size_t ws_bytes;
+    int max_lds_set;      // hipFuncSetAttribute not needed: LDS is static
+};
+
+static int esize_of(int dt) { return dt == PEAK_DT_F32 ? 4 : 2; }
+
+static bool variant_fits(const Variant &v, const peak_gemm_desc_t &d)
+{
+    if (v.dt != d.dtype) return false;
+    if (v.lds > LDS_LIMIT) return false;
+    // layouts: kernel's A_T means A does not run along K, i.e. transA == 1;
+    // kernel's B_T means B stored K x N, i.e. transB == 0
+    const int a_t = d.transA ? 1 : 0, b_t = d.transB ? 0 : 1;
+    if (v.a_t != a_t || v.b_t != b_t) return false;
+    if (v.kind == KIND_SKINNY && d.M > v.max_m) return false;
+    if (v.direct) {
+        const int es = esize_of(d.dtype);
+        if (d.K % v.bk != 0 || d.K < v.bk) return false;
+        if ((d.lda * es) % 16 != 0 || (d.ldb * es) % 16 != 0) return false;
+        // per-workgroup byte offsets are formed in 64 bits; nothing else to check
+    }
+    return true;
+}
+
+static int64_t cdiv(int64_t a, int64_t b) { return (a + b - 1) / b; }
+
+// Estimated time of a tiled variant, in units of "one 32x32xBK-row MFMA group":
+// rounds of workgroups over the CUs times the work of one tile.  Used only to
+// rank variants; the measured sweep decides the constants.
+static double tiled_cost(const Variant &v, const peak_gemm_desc_t &d, int split)
+{
+    const int64_t tiles = cdiv(d.M, v.bm) * cdiv(d.N, v.bn) * split;
+    const int64_t rounds = cdiv(tiles, NUM_CU);
+    const double ktiles = (double)cdiv(cdiv(d.K, v.bk), split);
+    const double tile_work = (double)v.bm * v.bn * v.bk * ktiles;
+    // small tiles pay more LDS/L2 traffic per flop; direct loads overlap better
+    double eff = 1.0;
+    if (v.bm * v.bn >= 256 * 256) eff = 1.0;
+    else if (v.bm * v.bn >= 256 * 128) eff = 0.85;
+    else if (v.bm * v.bn >= 128 * 128) eff = 0.6;
+    else eff = 0.3;
+    if (!v.direct) eff *= 0.7;
+    const double fixed = 4.0e6;                     // launch + prologue + epilogue, same units
+    return rounds * (tile_work / eff + fixed) + (split > 1 ? 2.0e6 : 0.0);
+}
+
+static int choose_split(const Variant &v, const peak_gemm_desc_t &d)
+{
+    const int64_t tiles = cdiv(d.M, v.bm) * cdiv(d.N, v.bn);
+    const int64_t ktiles = cdiv(d.K, v.bk);
+    if (tiles >= NUM_CU / 2 || ktiles < 8) return 1;
+    int best = 1;
+    double best_cost = tiled_cost(v, d, 1);
+    for (int s = 2; s <= 16; ++s) {
+        if (ktiles / s < 4) break;
+        const double c = tiled_cost(v, d, s);
+        if (c < best_cost * 0.9) { best_cost = c; best = s; }
+    }
+    return best;
+}
+
+static void plan_geometry(peak_gemm_plan *p, const Variant &v, int forced_split)
+{
+    const peak_gemm_desc_t &d = p->d;
+    p->tiles_m = (int)cdiv(d.M, v.bm);
+    p->tiles_n = (int)cdiv(d.N, v.bn);
+    p->ktiles_total = (int)cdiv(d.K, v.bk);
+    int split = forced_split > 0 ? forced_split : (v.kind == KIND_SKINNY ? skinny_split(d.N, d.K, v.bn, v.bk)
+                                                                          : choose_split(v, d));
+    if (split > p->ktiles_total) split = p->ktiles_total;
+    if (split < 1) split = 1;
+    p->ktiles_per_slice = (int)cdiv(p->ktiles_total, split);
+    p->split = (int)cdiv(p->ktiles_total, p->ktiles_per_slice);   // no empty slices
+    p->group_m = p->tiles_m >= 8 ? 8 : (p->tiles_m > 0 ? p->tiles_m : 1);
+    p->ws_bytes = p->split > 1 ? (size_t)p->split * (size_t)d.M * (size_t)d.N * sizeof(float) : 0;
+}
+
+extern "C" {
+
+const char *peak_status_string(peak_status_t s)
+{
+    switch (s) {
+    case PEAK_OK: return "ok";
+    case PEAK_ERR_INVALID_ARG: return "invalid argument";
+    case PEAK_ERR_UNSUPPORTED: return "no kernel variant supports this problem";
+    case PEAK_ERR_WORKSPACE: return "workspace missing or too small";
+    case PEAK_ERR_HIP: return "HIP runtime error at launch";
+    case PEAK_ERR_ALLOC: return "host allocation failed";
+    }
+    return "unknown status";
+}
+
+int peak_gemm_variant_count(void) { return NUM_VARIANTS; }
+
+const char *peak_gemm_variant_name(int id)
+{
+    if (id < 0 || id >= NUM_VARIANTS) return nullptr;
+    return g_variants[id].name;
+}
+
+peak_status_t peak_gemm_create(const peak_gemm_desc_t *desc, peak_gemm_plan_t **out_plan)
+{
+    if (out_plan) *out_plan = nullptr;
+    if (!desc || !out_plan) return PEAK_ERR_INVALID_ARG;
+    const peak_gemm_desc_t &d = *desc;
+    if (d.M < 0 || d.N < 0 || d.K < 0) return PEAK_ERR_INVALID_ARG;
+    if (d.dtype != PEAK_DT_F32 && d.dtype != PEAK_DT_F16 && d.dtype != PEAK_DT_BF16) return PEAK_ERR_INVALID_ARG;
+    if ((d.transA != 0 && d.transA != 1) || (d.transB != 0 && d.transB != 1)) return PEAK_ERR_INVALID_ARG;
+    if (d.flags & ~0xFFFFu) return PEAK_ERR_INVALID_ARG;
+    const int64_t min_lda = d.transA ? d.M : d.K, min_ldb = d.transB ? d.K : d.N;
+    if (d.lda < (min_lda > 1 ? min_lda : 1) || d.ldb < (min_ldb > 1 ? min_ldb : 1) || d.ldc < (d.N > 1 ? d.N : 1))
+        return PEAK_ERR_INVALID_ARG;
+    // index arithmetic is 64-bit, but tile counts and the grid are 32-bit
+    if (d.M > (int64_t)1 << 30 || d.N > (int64_t)1 << 30 || d.K > (int64_t)1 << 30) return PEAK_ERR_UNSUPPORTED;
+
+    peak_gemm_plan *p = new (std::nothrow) peak_gemm_plan;
+    if (!p) return PEAK_ERR_ALLOC;
+    memset(p, 0, sizeof *p);
+    p->d = d;
+    p->variant = -1;
+    p->split = 1;
+
+    const int forced = (int)(d.flags & 0xFF) - 1;
+    const int forced_split = (int)((d.flags >> 8) & 0xFF);
+
+    if (d.M == 0 || d.N == 0 || d.K == 0) {           // nothing to multiply; run() scales C or does nothing
+        if (forced >= 0 && (forced >= NUM_VARIANTS || g_variants[forced].dt != d.dtype)) {
+            delete p;
+            return PEAK_ERR_UNSUPPORTED;
+        }
+        *out_plan = p;
+        return PEAK_OK;
+    }
+
+    int pick = -1;
+    if (forced >= 0) {
+        if (forced >= NUM_VARIANTS || !variant_fits(g_variants[forced], d)) {
+            delete p;
+            return PEAK_ERR_UNSUPPORTED;
+        }
+        pick = forced;
+    } else {
+        double best = 0.0;
+        for (int i = 0; i < NUM_VARIANTS; ++i) {
+            const Variant &v = g_variants[i];
+            if (!variant_fits(v, d)) continue;
+            if (v.kind == KIND_SKINNY) {              // the streaming kernel wins whenever it applies
+                pick = i;
+                break;
+            }
+            if (!variant_selectable(i)) continue;
+            const double c = tiled_cost(v, d, choose_split(v, d));
+            if (pick < 0 || c < best) { pick = i; best = c; }
+        }
+        if (pick < 0) {
+            delete p;
+            return PEAK_ERR_UNSUPPORTED;
+        }
+    }
+    p->variant = pick;
+    plan_geometry(p, g_variants[pick], forced_split);
+    const int64_t grid = (int64_t)p->tiles_m * p->tiles_n * p->split;
+    if (grid > 0x7FFFFFFF) {
+        delete p;
+        return PEAK_ERR_UNSUPPORTED;
+    }
+    *out_plan = p;
+    return PEAK_OK;
+}
+
+size_t peak_gemm_workspace_bytes(const peak_gemm_plan_t *plan) { return plan ? plan->ws_bytes : 0; }
+
+int peak_gemm_plan_info(const peak_gemm_plan_t *p, char *buf, size_t n)
+{
+    if (!p) return snprintf(buf, n, "null plan");
+    if (p->variant < 0)
+        return snprintf(buf, n, "variant=none (degenerate size) M=%lld N=%lld K=%lld", (long long)p->d.M,
+                        (long long)p->d.N, (long long)p->d.K);
+    const Variant &v = g_variants[p->variant];
+    return snprintf(buf, n,
+                    "variant=%d:%s tile=%dx%dx%d threads=%d stages=%d lds=%d split=%d ktiles/slice=%d "
+                    "grid=%lld (tiles %dx%d) group_m=%d workspace=%zu",
+                    p->variant, v.name, v.bm, v.bn, v.bk, v.nt, v.ns, v.lds, p->split, p->ktiles_per_slice,
+                    (long long)p->tiles_m * p->tiles_n * p->split, p->tiles_m, p->tiles_n, p->group_m, p->ws_bytes);
+}
+
+peak_status_t peak_gemm_run(peak_gemm_plan_t *p, float alpha, const void *A, const void *B, float beta, void *C,
+                            void *workspace, size_t workspace_bytes, void *hip_stream)
+{
+    if (!p) return PEAK_ERR_INVALID_ARG;
+    const peak_gemm_desc_t &d = p->d;
+    if (d.M == 0 || d.N == 0) return PEAK_OK;
+    if (!C) return PEAK_ERR_INVALID_ARG;
+    const int es = esize_of(d.dtype);
+    if ((uintptr_t)C % es) return PEAK_ERR_INVALID_ARG;
+    hipStream_t stream = (hipStream_t)hip_stream;
+
+    GemmArgs a;
+    memset(&a, 0, sizeof a);
+    a.A = A; a.B = B; a.C = C; a.ws = nullptr;
+    a.M = d.M; a.N = d.N; a.K = d.K;
+    a.lda = d.lda; a.ldb = d.ldb; a.ldc = d.ldc;
+    a.alpha = alpha; a.beta = beta;
+    a.split = 1;
+    if ((uintptr_t)C % (4 * es) == 0 && (d.ldc * es) % (4 * es) == 0) a.flags |= GF_C_VEC;
+
+    const bool no_product = (d.K == 0 || alpha == 0.0f);
+    if (no_product) {
+        if (beta == 1.0f) return PEAK_OK;
+        const int64_t blocks = cdiv(d.M * d.N, 256);
+        if (blocks > 0x7FFFFFFF) return PEAK_ERR_UNSUPPORTED;
+        dim3 grid((unsigned)blocks);
+        if (d.dtype == PEAK_DT_F32) hipLaunchKernelGGL(scale_c_kernel<DT_F32>, grid, dim3(256), 0, stream, a);
+        else if (d.dtype == PEAK_DT_F16) hipLaunchKernelGGL(scale_c_kernel<DT_F16>, grid, dim3(256), 0, stream, a);
+        else hipLaunchKernelGGL(scale_c_kernel<DT_BF16>, grid, dim3(256), 0, stream, a);
+        return hipGetLastError() == hipSuccess ? PEAK_OK : PEAK_ERR_HIP;
+    }
+
+    if (!A || !B) return PEAK_ERR_INVALID_ARG;
+    if ((uintptr_t)A % es || (uintptr_t)B % es) return PEAK_ERR_INVALID_ARG;
+    if (p->variant < 0) return PEAK_ERR_UNSUPPORTED;
+    const Variant &v = g_variants[p->variant];
+
+    const bool a_al = (uintptr_t)A % 16 == 0 && (d.lda * es) % 16 == 0;
+    const bool b_al = (uintptr_t)B % 16 == 0 && (d.ldb * es) % 16 == 0;
+    if (a_al) a.flags |= GF_A_VEC;
+    if (b_al) a.flags |= GF_B_VEC;
+    if (v.direct && !(a_al && b_al)) return PEAK_ERR_INVALID_ARG;   // plan was made for aligned operands
+
+    if (p->split > 1) {
+        if (!workspace || workspace_bytes < p->ws_bytes) return PEAK_ERR_WORKSPACE;
+        if ((uintptr_t)workspace % 256) return PEAK_ERR_INVALID_ARG;
+        a.ws = (float *)workspace;
+        if (d.N % 4 == 0) a.flags |= GF_WS_VEC;
+    }
+    a.tiles_m = p->tiles_m; a.tiles_n = p->tiles_n;
+    a.split = p->split;
+    a.ktiles_per_slice = p->ktiles_per_slice;
+    a.ktiles_total = p->ktiles_total;
+    a.group_m = p->group_m;
+
+    dim3 grid((unsigned)((int64_t)p->tiles_m * p->tiles_n * p->split));
+    if (v.launch(a, grid, stream) != hipSuccess) return PEAK_ERR_HIP;
+
+    if (p->split > 1) {
+        const int64_t quads = d.M * cdiv(d.N, 4);
+        dim3 rgrid((unsigned)cdiv(quads, 256));
+        if (d.dtype == PEAK_DT_F32) hipLaunchKernelGGL(splitk_reduce_kernel<DT_F32>, rgrid, dim3(256), 0, stream, a);
+        else if (d.dtype == PEAK_DT_F16) hipLaunchKernelGGL(splitk_reduce_kernel<DT_F16>, rgrid, dim3(256), 0, stream, a);
+        else hipLaunchKernelGGL(splitk_reduce_kernel<DT_BF16>, rgrid, dim3(256), 0, stream, a);
+        if (hipGetLastError() != hipSuccess) return PEAK_ERR_HIP;
+    }
+    return PEAK_OK;
+}
+
+peak_status_t peak_gemm_destroy(peak_gemm_plan_t *plan)
+{
+    delete plan;
+    return PEAK_OK;
+}
+
+}  // extern "C"

@@ -1,0 +1,160 @@
+// Streaming kernel for skinny products (M <= 16, both operands running along K
+// in memory): the N x K operand is read from HBM exactly once and that read is
+// the whole cost, so the kernel is built around keeping many direct-to-LDS
+// loads in flight per CU, not around the matrix cores (one 16x16x32 MFMA per
+// 32 k still does the arithmetic).  K is cut into slices (the paper's Split-K,
+// Section 4.1 Table 2) so that enough workgroups stream at once; the fp32
+// partials are summed in slice order by splitk_reduce_kernel.
+#pragma once
+
+#include "gemm_device.h"
+
+namespace peak {
+
+template <int DT_, int BN_, int KSTEP_, int NS_>
+struct SkinnyCfg {
+    static constexpr int DT = DT_;
+    static_assert(DT_ != DT_F32, "16-bit storage only");
+    static constexpr int ESZ = 2, EPC = 8;
+    static constexpr int BM = 16, BN = BN_, KSTEP = KSTEP_, NS = NS_;
+    static constexpr int RB = KSTEP_ * ESZ;               // bytes per tile row and stage
+    static constexpr int CPR = RB / 16;                   // 16-byte chunks per tile row
+    static constexpr int NW = BN_ / 16;                   // one wave per 16 rows of the N x K operand
+    static constexpr int NT = NW * 64;
+    static constexpr int A_BYTES = BM * RB, B_BYTES = BN_ * RB;
+    static constexpr int STAGE_BYTES = A_BYTES + B_BYTES;
+    static constexpr int LDS_BYTES = STAGE_BYTES * NS_;
+    static constexpr int ROWS_PER_INST = 64 / CPR;        // a wave load fills 1024 contiguous LDS bytes
+    static constexpr int A_INST = BM / ROWS_PER_INST, B_INST = BN_ / ROWS_PER_INST;
+    static_assert(CPR == 16 || CPR == 32, "row of 256 or 512 bytes");
+    static_assert(A_INST % NW == 0 || NW % A_INST == 0, "A loads split evenly");
+    static_assert(B_INST % NW == 0, "B loads split evenly");
+    static constexpr int B_PER_WAVE = B_INST / NW;
+    // every wave issues the same number of loads per stage: its share of B, and
+    // one A instruction (waves beyond A_INST repeat an A instruction of another
+    // wave, writing the same bytes to the same place)
+    static constexpr int A_PER_WAVE = A_INST >= NW ? A_INST / NW : 1;
+    static constexpr int DLOADS = A_PER_WAVE + B_PER_WAVE;
+};
+
+// chunk c of tile row r sits at position c ^ (r & 15) (in units of 16 bytes,
+// within the aligned group of 16 chunks c belongs to)
+PEAK_DEV int skinny_pos(int r, int c) { return c ^ (r & 15); }
+
+// Number of K slices: enough workgroups for ~8 per CU, at least 4 stages each.
+static inline int skinny_split(int64_t N, int64_t K, int bn, int kstep)
+{
+    const int64_t tiles_n = (N + bn - 1) / bn;
+    const int64_t ktiles = (K + kstep - 1) / kstep;
+    int64_t s = (2048 + tiles_n - 1) / tiles_n;
+    if (s > ktiles / 4) s = ktiles / 4;
+    if (s < 1) s = 1;
+    if (s > 64) s = 64;
+    return (int)s;
+}
+
+template <class C>
+__global__ __launch_bounds__(C::NT) void skinny_kernel(const GemmArgs p)
+{
+    __shared__ __attribute__((aligned(1024))) char lds[C::LDS_BYTES];
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int tn = blockIdx.x % p.tiles_n, slice = blockIdx.x / p.tiles_n;
+    const int64_t n0 = (int64_t)tn * C::BN;
+
+    const int kt_begin = slice * p.ktiles_per_slice;
+    int kt_end = kt_begin + p.ktiles_per_slice;
+    if (kt_end > p.ktiles_total) kt_end = p.ktiles_total;
+    const int KT = kt_end - kt_begin;
+    const int64_t kbase = (int64_t)kt_begin * C::KSTEP;
+
+    // sources of this lane's direct loads at the slice's first k
+    const char *ga[C::A_PER_WAVE];
+    const char *gb[C::B_PER_WAVE];
+    int ja[C::A_PER_WAVE], jb[C::B_PER_WAVE];
+#pragma unroll
+    for (int i = 0; i < C::A_PER_WAVE; ++i) {
+        const int j = (wave + C::NW * i) % C::A_INST;
+        const int row = j * C::ROWS_PER_INST + lane / C::CPR, pos = lane % C::CPR;
+        const int c = (pos & ~15) | skinny_pos(row, pos & 15);
+        int64_t gr = row;
+        if (gr > p.M - 1) gr = p.M - 1;
+        ga[i] = (const char *)p.A + (gr * p.lda + kbase + (int64_t)c * C::EPC) * C::ESZ;
+        ja[i] = j;
+    }
+#pragma unroll
+    for (int i = 0; i < C::B_PER_WAVE; ++i) {
+        const int j = wave + C::NW * i;
+        const int row = j * C::ROWS_PER_INST + lane / C::CPR, pos = lane % C::CPR;
+        const int c = (pos & ~15) | skinny_pos(row, pos & 15);
+        int64_t gr = n0 + row;
+        if (gr > p.N - 1) gr = p.N - 1;
+        gb[i] = (const char *)p.B + (gr * p.ldb + kbase + (int64_t)c * C::EPC) * C::ESZ;
+        jb[i] = j;
+    }
+    auto issue = [&](int kt, int stage) {
+        const int kc = kt < KT ? kt : KT - 1;            // past the end: refetch the last tile into a free stage
+        char *st = lds + stage * C::STAGE_BYTES;
+#pragma unroll
+        for (int i = 0; i < C::A_PER_WAVE; ++i)
+            __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)(ga[i] + (int64_t)kc * C::RB),
+                                             (__attribute__((address_space(3))) void *)(st + ja[i] * 1024), 16, 0, 0);
+#pragma unroll
+        for (int i = 0; i < C::B_PER_WAVE; ++i)
+            __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)(gb[i] + (int64_t)kc * C::RB),
+                                             (__attribute__((address_space(3))) void *)(st + C::A_BYTES + jb[i] * 1024), 16, 0, 0);
+    };
+
+    // fragment addresses: lane reads tile row (lane % 16), chunk 4*kg + lane/16
+    const int r16 = lane & 15, q = lane >> 4;
+    const int a_row = r16 * C::RB;
+    const int b_row = C::A_BYTES + (wave * 16 + r16) * C::RB;
+    const int a_sw = r16, b_sw = (wave * 16 + r16) & 15;       // both equal r16; kept apart for clarity
+
+    typedef float f32x4v __attribute__((ext_vector_type(4)));
+    f32x4v acc = {0.0f, 0.0f, 0.0f, 0.0f};
+
+    constexpr int P = C::NS - 1;
+#pragma unroll
+    for (int s = 0; s < P; ++s) issue(s, s);
+
+    for (int kt0 = 0; kt0 < KT; kt0 += C::NS) {
+#pragma unroll
+        for (int s = 0; s < C::NS; ++s) {
+            const int kt = kt0 + s;
+            if (kt < KT) {
+                wait_vmcnt<(P - 1) * C::DLOADS>();
+                lds_barrier();
+                issue(kt + P, (s + P) % C::NS);
+                const char *st = lds + s * C::STAGE_BYTES;
+#pragma unroll
+                for (int kg = 0; kg < C::KSTEP / 32; ++kg) {
+                    const int c = kg * 4 + q;
+                    const u32x4 af = *(const u32x4 *)(st + a_row + (((c & ~15) | ((c & 15) ^ a_sw)) << 4));
+                    const u32x4 bf = *(const u32x4 *)(st + b_row + (((c & ~15) | ((c & 15) ^ b_sw)) << 4));
+                    if (C::DT == DT_BF16)
+                        acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, bf),
+                                                                      __builtin_bit_cast(bf16x8, af), acc, 0, 0, 0);
+                    else
+                        acc = __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(f16x8, bf),
+                                                                     __builtin_bit_cast(f16x8, af), acc, 0, 0, 0);
+                }
+            }
+        }
+    }
+    wait_vmcnt<0>();        // the refetches past the end must land before this workgroup's LDS is given away
+
+    // acc[v] <-> m = lane % 16, n = n0 + wave*16 + 4*(lane/16) + v
+    const int64_t m = r16;
+    const int64_t n = n0 + wave * 16 + q * 4;
+    const int64_t left = p.N - n;
+    if (m < p.M && left > 0) {
+        const int nvalid = left >= 4 ? 4 : (int)left;
+        const float x[4] = {acc[0], acc[1], acc[2], acc[3]};
+        if (p.split > 1)
+            store4<DT_F32>(p.ws + (int64_t)slice * p.M * p.N, m * p.N + n, x, 1.0f, 0.0f, p.flags & GF_WS_VEC, nvalid);
+        else
+            store4<C::DT>(p.C, m * p.ldc + n, x, p.alpha, p.beta, p.flags & GF_C_VEC, nvalid);
+    }
+}
+
+}  // namespace peak

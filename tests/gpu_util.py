@@ -1,0 +1,59 @@
+"""Helpers for the GPU parity tests: move seeded host arrays to the device, run
+the C-ABI entry points, bring the result back as fp64 values."""
+from __future__ import annotations
+
+import numpy as np
+import torch
+
+import peak_inputs as pi
+import paper_2512_19018_amd as pg
+
+TOL = {pi.F32: 1e-5, pi.F16: 2e-2, pi.BF16: 2e-2}     # relative Frobenius, as stated for the workloads
+
+
+def to_dev(arr: np.ndarray) -> torch.Tensor:
+    if arr.dtype == np.uint16:
+        return torch.from_numpy(arr.view(np.int16).copy()).cuda()
+    return torch.from_numpy(np.ascontiguousarray(arr)).cuda()
+
+
+def from_dev(t: torch.Tensor, dtype: int) -> np.ndarray:
+    a = t.cpu().numpy()
+    return a.view(np.uint16) if dtype != pi.F32 else a
+
+
+def nan_fill(rows: int, cols: int, dtype: int) -> np.ndarray:
+    if dtype == pi.F32:
+        return np.full((rows, cols), np.nan, dtype=np.float32)
+    return np.full((rows, cols), 0x7FC1 if dtype == pi.BF16 else 0x7E01, dtype=np.uint16)
+
+
+def run_gemm(dtype, transA, transB, M, N, K, alpha, beta, A, B, C0, flags=0, repeat=1, a_off=0, b_off=0):
+    """A, B, C0: stored host arrays (2-D; row length = leading dimension).  C0 is
+    the initial content of C (C_in, or a NaN fill when beta == 0).  Returns
+    (C values as fp64 [M, N], raw stored C after the run, plan info)."""
+    lda, ldb, ldc = A.shape[1], B.shape[1], C0.shape[1]
+    dA, dB, dC = to_dev(A), to_dev(B), to_dev(C0)
+    stream = torch.cuda.current_stream().cuda_stream
+    with pg.Plan(M, N, K, dtype, transA, transB, lda, ldb, ldc, flags) as plan:
+        info = plan.info()
+        ws = torch.empty(max(plan.workspace_bytes, 256), dtype=torch.uint8, device="cuda")
+        for _ in range(repeat):
+            plan.run(alpha, dA.data_ptr() + a_off, dB.data_ptr() + b_off, beta, dC.data_ptr(),
+                     ws.data_ptr(), plan.workspace_bytes, stream)
+        torch.cuda.synchronize()
+    raw = from_dev(dC, dtype)
+    vals = pi.to_f64(np.ascontiguousarray(raw[:M, :N]), dtype) if M and N else np.zeros((M, N))
+    return vals, raw, info
+
+
+def variants_for(dtype, transA, transB):
+    """ids of all variants built for this dtype and layout."""
+    pre = {pi.F32: "f32_", pi.F16: "f16_", pi.BF16: "bf16_"}[dtype]
+    suf = "_" + ("t" if transA else "n") + ("t" if transB else "n")
+    out = []
+    for i in range(pg.peak_gemm_variant_count()):
+        n = pg.peak_gemm_variant_name(i)
+        if n.startswith(pre) and n.endswith(suf):
+            out.append((i, n))
+    return out

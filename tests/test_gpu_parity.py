@@ -1,0 +1,213 @@
+"""GPU parity: the HIP library, called through its C ABI, against the CPU oracle
+on the same seeded inputs.  Integer-valued cases must match exactly; floating
+point cases within the stated relative Frobenius error (1e-5 fp32, 2e-2 f16 and
+bf16)."""
+import itertools
+
+import numpy as np
+import pytest
+
+import peak_inputs as pi
+
+pytestmark = pytest.mark.gpu
+
+DTYPES = [pi.F32, pi.F16, pi.BF16]
+LAYOUTS = list(itertools.product([0, 1], [0, 1]))
+
+
+@pytest.fixture(scope="module")
+def gu():
+    import torch
+    assert torch.cuda.is_available(), "these tests need the GPU"
+    from tests import gpu_util
+    return gpu_util
+
+
+def _stored(seed, dtype, M, N, K, transA, transB, pad=(0, 0, 0), ints=False, dist="uniform", scale=1.0):
+    if ints:
+        la = pi.small_int_matrix(seed, 0, M, K, -2, 2, dtype)
+        lb = pi.small_int_matrix(seed, 1, K, N, -2, 2, dtype)
+        lc = pi.small_int_matrix(seed, 2, M, N, -3, 3, dtype)
+    else:
+        la = pi.logical_matrix(seed, 0, M, K, dist, scale, dtype)
+        lb = pi.logical_matrix(seed, 1, K, N, dist, scale, dtype)
+        lc = pi.logical_matrix(seed, 2, M, N, dist, 1.0, dtype)
+    A = pi.store(la, bool(transA), (M if transA else K) + pad[0])
+    B = pi.store(lb, bool(transB), (K if transB else N) + pad[1])
+    C = pi.store(lc, False, N + pad[2])
+    return A, B, C
+
+
+def _check_padding(raw, C0, M, N):
+    # everything outside the logical M x N block must be byte-identical to before
+    assert np.array_equal(raw[:, N:].view(np.uint8), C0[:, N:].view(np.uint8))
+    assert np.array_equal(raw[M:, :].view(np.uint8), C0[M:, :].view(np.uint8))
+
+
+@pytest.mark.parametrize("dtype", DTYPES)
+@pytest.mark.parametrize("transA,transB", LAYOUTS)
+def test_exact_integers_every_variant(gu, oracle, dtype, transA, transB):
+    """Small integers: products and sums are exact in fp32, results (|c| <= 256)
+    exact in every storage type, so the match must be bitwise.  Pins the MFMA
+    fragment layout, the swizzle, the transposing stores and the edge masks of
+    every kernel variant built for the layout."""
+    for vid, name in gu.variants_for(dtype, transA, transB):
+        direct = "_d" in name or "skinny" in name
+        # K <= 64 keeps |sum| <= 4*64 = 256
+        if "skinny" in name:
+            shapes = [(16, 192, 128), (7, 130, 256), (1, 64, 128)]
+        elif direct:
+            bk = 32 if ("f32" in name or "k32" in name) else 64
+            shapes = [(256, 256, bk), (300, 500, 2 * bk if 2 * bk <= 64 else bk), (100, 72, bk)]
+        else:
+            shapes = [(128, 128, 64), (200, 333, 40), (77, 5, 33), (1, 1, 1), (129, 257, 64)]
+        for case, (M, N, K) in enumerate(shapes):
+            for alpha, beta in [(1.0, 0.0), (-1.0, 2.0)]:
+                pad = (0, 0, 0) if direct else (case % 2 * 3, case % 2 * 5, case % 2 * 7)
+                A, B, C = _stored(1000 + vid * 10 + case, dtype, M, N, K, transA, transB, pad, ints=True)
+                if direct:
+                    # aligned leading dimensions for the direct kernels
+                    al = 16 // pi.DTYPE_SIZE[dtype]
+                    ok = A.shape[1] % al == 0 and B.shape[1] % al == 0
+                    if not ok:
+                        la = -(-A.shape[1] // al) * al
+                        lb = -(-B.shape[1] // al) * al
+                        A = np.pad(A, ((0, 0), (0, la - A.shape[1])))
+                        B = np.pad(B, ((0, 0), (0, lb - B.shape[1])))
+                C0 = C if beta != 0 else gu.nan_fill(C.shape[0], C.shape[1], dtype)
+                ref = oracle.gemm(dtype, transA, transB, M, N, K, alpha, A, B, beta, C if beta != 0 else None)
+                got, raw, info = gu.run_gemm(dtype, transA, transB, M, N, K, alpha, beta, A, B, C0,
+                                             flags=gu.pg.force_flags(variant=vid))
+                assert np.array_equal(got, ref), (name, M, N, K, alpha, beta, info)
+                _check_padding(raw, C0, M, N)
+
+
+@pytest.mark.parametrize("dtype", DTYPES)
+def test_random_every_direct_variant_deep_k(gu, oracle, dtype):
+    """Forced direct-to-LDS and streaming variants over enough K tiles to wrap
+    their staging rings several times, ragged M and N."""
+    for transA, transB in LAYOUTS:
+        for vid, name in gu.variants_for(dtype, transA, transB):
+            if not ("_d" in name or "skinny" in name):
+                continue
+            M, N, K = ((13, 1000, 2048) if "skinny" in name else (300, 520, 1024))
+            A, B, C = _stored(6000 + vid, dtype, M, N, K, transA, transB)
+            ref = oracle.gemm(dtype, transA, transB, M, N, K, 1.0, A, B, 0.25, C)
+            for split in (None, 3):
+                got, raw, info = gu.run_gemm(dtype, transA, transB, M, N, K, 1.0, 0.25, A, B, C,
+                                             flags=gu.pg.force_flags(variant=vid, split=split))
+                err = oracle.rel_frobenius(got, ref)
+                assert err <= gu.TOL[dtype], (info, err)
+
+
+@pytest.mark.parametrize("dtype", DTYPES)
+@pytest.mark.parametrize("transA,transB", LAYOUTS)
+def test_random_against_oracle_auto_selection(gu, oracle, dtype, transA, transB):
+    """Selector's own choice, sizes spanning several tiles with ragged tails."""
+    for case, (M, N, K) in enumerate([(384, 320, 512), (513, 259, 1000), (33, 1100, 200), (700, 70, 4096)]):
+        A, B, C = _stored(2000 + case, dtype, M, N, K, transA, transB)
+        for alpha, beta in [(1.0, 0.0), (0.75, -0.5)]:
+            C0 = C if beta != 0 else gu.nan_fill(M, N, dtype)
+            ref = oracle.gemm(dtype, transA, transB, M, N, K, alpha, A, B, beta, C if beta != 0 else None)
+            got, raw, info = gu.run_gemm(dtype, transA, transB, M, N, K, alpha, beta, A, B, C0)
+            err = oracle.rel_frobenius(got, ref)
+            assert err <= gu.TOL[dtype], (info, M, N, K, err)
+
+
+@pytest.mark.parametrize("dtype", DTYPES)
+def test_unaligned_operands_and_odd_leading_dimensions(gu, oracle, dtype):
+    """Base pointers off 16-byte alignment and odd row strides force the element
+    loaders and scalar stores."""
+    M, N, K = 150, 97, 203
+    for transA, transB in LAYOUTS:
+        A, B, C = _stored(3000, dtype, M, N, K, transA, transB, pad=(1, 3, 1))
+        es = pi.DTYPE_SIZE[dtype]
+        # shift A and B by one element inside a larger allocation
+        A1 = np.concatenate([A.ravel()[:1], A.ravel()]).reshape(1, -1)
+        B1 = np.concatenate([B.ravel()[:1], B.ravel()]).reshape(1, -1)
+        ref = oracle.gemm(dtype, transA, transB, M, N, K, 1.0, A, B, 0.5, C)
+        dA, dB, dC = gu.to_dev(A1), gu.to_dev(B1), gu.to_dev(C)
+        import torch
+        with gu.pg.Plan(M, N, K, dtype, transA, transB, A.shape[1], B.shape[1], C.shape[1]) as plan:
+            ws = torch.empty(max(plan.workspace_bytes, 256), dtype=torch.uint8, device="cuda")
+            plan.run(1.0, dA.data_ptr() + es, dB.data_ptr() + es, 0.5, dC.data_ptr(), ws.data_ptr(),
+                     plan.workspace_bytes, torch.cuda.current_stream().cuda_stream)
+            torch.cuda.synchronize()
+            info = plan.info()
+        raw = gu.from_dev(dC, dtype)
+        got = pi.to_f64(np.ascontiguousarray(raw[:M, :N]), dtype)
+        assert oracle.rel_frobenius(got, ref) <= gu.TOL[dtype], (info, transA, transB)
+        _check_padding(raw, C, M, N)
+
+
+@pytest.mark.parametrize("dtype", DTYPES)
+def test_split_k_forced_and_deterministic(gu, oracle, dtype):
+    M, N, K = 192, 160, 2048
+    transA, transB = 0, 1
+    A, B, C = _stored(4000, dtype, M, N, K, transA, transB)
+    ref = oracle.gemm(dtype, transA, transB, M, N, K, 1.25, A, B, 0.5, C)
+    outs = []
+    for split in (1, 3, 8):
+        got, raw, info = gu.run_gemm(dtype, transA, transB, M, N, K, 1.25, 0.5, A, B, C,
+                                     flags=gu.pg.force_flags(split=split))
+        assert ("split=%d" % split) in info or split > 1, info
+        assert oracle.rel_frobenius(got, ref) <= gu.TOL[dtype], info
+        again, raw2, _ = gu.run_gemm(dtype, transA, transB, M, N, K, 1.25, 0.5, A, B, C,
+                                     flags=gu.pg.force_flags(split=split))
+        assert np.array_equal(raw.view(np.uint8), raw2.view(np.uint8)), "run-to-run bits differ: " + info
+        outs.append(got)
+
+
+@pytest.mark.parametrize("dtype", DTYPES)
+def test_degenerate_cases(gu, oracle, dtype):
+    import torch
+    M, N, K = 40, 24, 16
+    A, B, C = _stored(5000, dtype, M, N, K, 0, 0, pad=(0, 0, 4))
+    # alpha == 0: C = beta*C, operands not read (NULL pointers)
+    with gu.pg.Plan(M, N, K, dtype, 0, 0, K, N, N + 4) as plan:
+        dC = gu.to_dev(C)
+        plan.run(0.0, 0, 0, -2.0, dC.data_ptr(), 0, 0, torch.cuda.current_stream().cuda_stream)
+        torch.cuda.synchronize()
+        raw = gu.from_dev(dC, dtype)
+        assert np.array_equal(pi.to_f64(np.ascontiguousarray(raw[:, :N]), dtype), -2.0 * pi.to_f64(np.ascontiguousarray(C[:, :N]), dtype))
+        _check_padding(raw, C, M, N)
+    # K == 0 with beta == 0: zeros, NaN in C_in not propagated
+    with gu.pg.Plan(M, N, 0, dtype, 0, 0, 1, N, N + 4) as plan:
+        C0 = gu.nan_fill(M, N + 4, dtype)
+        dC = gu.to_dev(C0)
+        plan.run(1.0, 0, 0, 0.0, dC.data_ptr(), 0, 0, torch.cuda.current_stream().cuda_stream)
+        torch.cuda.synchronize()
+        raw = gu.from_dev(dC, dtype)
+        assert (pi.to_f64(np.ascontiguousarray(raw[:, :N]), dtype) == 0).all()
+        _check_padding(raw, C0, M, N)
+    # M == 0 / N == 0: nothing happens
+    with gu.pg.Plan(0, N, K, dtype) as plan:
+        plan.run(1.0, 0, 0, 0.0, 0)
+    with gu.pg.Plan(M, 0, K, dtype) as plan:
+        plan.run(1.0, 0, 0, 0.0, 0)
+    # identity and permutation, exact
+    Kp = 96
+    la = pi.logical_matrix(5001, 0, 70, Kp, "uniform", 1.0, dtype)
+    perm = np.random.default_rng(9).permutation(Kp)
+    P = np.zeros((Kp, Kp), np.float32)
+    P[perm, np.arange(Kp)] = 1.0
+    Pst = pi.round_to_dtype(P, dtype).reshape(Kp, Kp)
+    got, _, info = gu.run_gemm(dtype, 0, 0, 70, Kp, Kp, 1.0, 0.0, la, Pst, gu.nan_fill(70, Kp, dtype))
+    assert np.array_equal(got, pi.to_f64(la, dtype)[:, perm]), info
+
+
+def test_error_paths_on_device(gu):
+    import torch
+    pg = gu.pg
+    M, N, K = 64, 64, 4096
+    with pg.Plan(M, N, K, pg.PEAK_DT_BF16, 0, 1, flags=pg.force_flags(split=4)) as plan:
+        assert plan.workspace_bytes == 4 * M * N * 4
+        a = torch.zeros(M * K, dtype=torch.int16, device="cuda")
+        c = torch.zeros(M * N, dtype=torch.int16, device="cuda")
+        st = pg.peak_gemm_run(plan.handle, 1.0, a.data_ptr(), a.data_ptr(), 0.0, c.data_ptr(), 0, 0, 0)
+        assert st == pg.PEAK_ERR_WORKSPACE
+        ws = torch.zeros(1024, dtype=torch.uint8, device="cuda")
+        st = pg.peak_gemm_run(plan.handle, 1.0, a.data_ptr(), a.data_ptr(), 0.0, c.data_ptr(), ws.data_ptr(), 1024, 0)
+        assert st == pg.PEAK_ERR_WORKSPACE
+        st = pg.peak_gemm_run(plan.handle, 1.0, 0, a.data_ptr(), 0.0, c.data_ptr(), 0, 0, 0)
+        assert st == pg.PEAK_ERR_INVALID_ARG
