@@ -295,10 +295,11 @@ PEAK_DEV void mfma_frag(f32x16 &acc, const u32x4 &bfrag, const u32x4 &afrag)
                                                      __builtin_bit_cast(f16x8, afrag), acc, 0, 0, 0);
     } else {
         // fp32: the chunk holds 4 k values per lane half; step s multiplies k = 4*half + s of both operands
-#pragma unroll
-        for (int s = 0; s < 4; ++s)
-            acc = __builtin_amdgcn_mfma_f32_32x32x2f32(__builtin_bit_cast(float, bfrag[s]),
-                                                       __builtin_bit_cast(float, afrag[s]), acc, 0, 0, 0);
+        const f32x4 bq = __builtin_bit_cast(f32x4, bfrag), aq = __builtin_bit_cast(f32x4, afrag);
+        acc = __builtin_amdgcn_mfma_f32_32x32x2f32(bq[0], aq[0], acc, 0, 0, 0);
+        acc = __builtin_amdgcn_mfma_f32_32x32x2f32(bq[1], aq[1], acc, 0, 0, 0);
+        acc = __builtin_amdgcn_mfma_f32_32x32x2f32(bq[2], aq[2], acc, 0, 0, 0);
+        acc = __builtin_amdgcn_mfma_f32_32x32x2f32(bq[3], aq[3], acc, 0, 0, 0);
     }
 }
 
