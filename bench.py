@@ -47,6 +47,10 @@ def main():
     ap.add_argument("--no-torch", action="store_true", help="skip the torch.matmul context rows")
     ap.add_argument("--variant", type=int, default=None, help="force a kernel variant id (sweeps)")
     ap.add_argument("--split", type=int, default=None, help="force a K split (sweeps)")
+    ap.add_argument("--fast-inputs", action="store_true",
+                    help="sweeps only: random device-generated inputs instead of the seeded host generator")
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="run a plain 1 GiB device copy instead (to scale FETCH_SIZE / WRITE_SIZE under rocprofv3)")
     args = ap.parse_args()
 
     if args.gpus != 1:
@@ -67,13 +71,35 @@ def main():
     torch.cuda.set_device(0)
     stream = torch.cuda.current_stream()
 
+    if args.copy_calibration:
+        n = 1 << 30
+        src = torch.full((n,), 3, dtype=torch.uint8, device="cuda")
+        dst = torch.empty_like(src)
+        for _ in range(args.steps):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        print(json.dumps({"copy_calibration_bytes_read": n, "copy_calibration_bytes_written": n, "launches": args.steps}))
+        return
+
     def dev(x):
         return torch.from_numpy(x.view(np.int16).copy() if x.dtype == np.uint16 else np.ascontiguousarray(x)).cuda()
 
     def time_workload(name, steps, warmup, variant=None, split=None, with_torch=True):
         w = pi.WORKLOADS[name]
         t0 = time.time()
-        A, B, C = w.make(with_cin=True)
+        if args.fast_inputs:
+            tdt0 = {pi.F32: torch.float32, pi.F16: torch.float16, pi.BF16: torch.bfloat16}[w.dtype]
+
+            def rnd(r, c):
+                t = (torch.randn(r, c, device="cuda") * w.scale).to(tdt0)
+                t = t.view(torch.int16) if w.dtype != pi.F32 else t
+                a = t.cpu().numpy()
+                return a.view(np.uint16) if w.dtype != pi.F32 else a
+            A = rnd(*( (w.K, w.M) if w.transA else (w.M, w.K) ))
+            B = rnd(*( (w.N, w.K) if w.transB else (w.K, w.N) ))
+            C = rnd(w.M, w.N)
+        else:
+            A, B, C = w.make(with_cin=True)
         log("[bench] %s: inputs generated in %.1f s" % (name, time.time() - t0))
         # rotate buffer sets for problems that would otherwise sit in the 256 MB last-level cache
         nset = 1

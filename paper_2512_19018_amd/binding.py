@@ -31,7 +31,8 @@ class PeakError(RuntimeError):
 
 
 def lib_path() -> str:
-    return os.path.join(_HERE, "libpeak_gemm.so")
+    """Path of the HIP library; PEAK_GEMM_LIB overrides it (to try another build)."""
+    return os.environ.get("PEAK_GEMM_LIB") or os.path.join(_HERE, "libpeak_gemm.so")
 
 
 def load_library():

@@ -50,24 +50,48 @@ struct GemmArgs {
     int32_t ktiles_per_slice; // BK-tiles per slice (last slice may be shorter)
     int32_t ktiles_total;     // ceil(K / BK)
     int32_t group_m;          // tile rows per band of the tile order
+    int32_t rot_m, rot_n;     // K rotation per tile row / tile column within an XCD's patch of tiles
     uint32_t flags;
 };
 
 #define PEAK_DEV static __device__ __forceinline__
 #define PEAK_DEVM __device__ __forceinline__
 
+// compile-time integer and loop (for template arguments inside lambdas)
+template <int V>
+struct IC { static constexpr int value = V; };
+template <int N, int I = 0, class F>
+PEAK_DEV void static_for(F &&f)
+{
+    if constexpr (I < N) {
+        f(IC<I>{});
+        static_for<N, I + 1>(f);
+    }
+}
+
+// s_waitcnt immediate (gfx9 encoding): vmcnt in bits 3:0 and 15:14, expcnt 6:4, lgkmcnt 11:8.
+constexpr int waitcnt_imm(int vmcnt, int lgkmcnt) { return ((vmcnt >> 4) & 3) << 14 | (vmcnt & 15) | 0x70 | (lgkmcnt & 15) << 8; }
+
 PEAK_DEV void lds_barrier()
 {
     // LDS traffic of this wave done, then workgroup barrier.  Outstanding
-    // global loads are left in flight on purpose.
-    asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
+    // global loads are left in flight on purpose (no fence: a fence would wait
+    // for them).  The empty asm statements keep the compiler from moving LDS
+    // accesses across; the wait is a builtin so that the compiler's own
+    // wait-count bookkeeping sees it.
+    asm volatile("" ::: "memory");
+    __builtin_amdgcn_s_waitcnt(waitcnt_imm(63, 0));
+    __builtin_amdgcn_s_barrier();
+    asm volatile("" ::: "memory");
 }
 
 template <int N>
 PEAK_DEV void wait_vmcnt()
 {
     static_assert(N >= 0 && N < 64, "vmcnt range");
-    asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory");
+    asm volatile("" ::: "memory");
+    __builtin_amdgcn_s_waitcnt(waitcnt_imm(N, 15));
+    asm volatile("" ::: "memory");
 }
 
 // ---------------------------------------------------------------------------
@@ -106,6 +130,7 @@ struct Cfg {
     static constexpr int B_BYTES = BN_ * RB_;
     static constexpr int STAGE_BYTES = A_BYTES + B_BYTES;
     static constexpr int LDS_BYTES = STAGE_BYTES * NS_;
+    static constexpr bool PIPE = NS_ >= 3;            // run-ahead main loop (see gemm_kernel)
     static_assert(WTM % 32 == 0 && WTN % 32 == 0, "wave tile is a grid of 32x32 MFMA blocks");
     static_assert(RB_ == 128 || RB_ == 64, "tile row is 64 or 128 bytes");
     static_assert((BM_ * CPR) % 64 == 0 && (BN_ * CPR) % 64 == 0, "whole wave loads");
@@ -239,39 +264,51 @@ struct LoaderT {
     }
 };
 
-// Direct global -> LDS copy of an operand that runs along K.  One wave
-// instruction fills 1024 contiguous LDS bytes (64 / CPR tile rows); which global
-// chunk a lane fetches is chosen so that the swizzled layout comes out.
+// Direct global -> LDS copy of an operand that runs along K, with buffer loads
+// (buffer_load_dwordx4 ... lds).  One wave instruction fills 1024 contiguous LDS
+// bytes (64 / CPR tile rows); which global chunk a lane fetches is chosen so that
+// the swizzled layout comes out.  The buffer descriptor covers exactly this
+// workgroup's panel, so a lane can never touch memory outside the operand; the
+// step along K goes into the scalar offset.
 template <class C, int ROWS>
 struct LoaderDirect {
     static constexpr int NINST = ROWS * C::CPR / 64;              // wave instructions per tile
     static constexpr int PER_WAVE = (NINST + C::NW - 1) / C::NW;
-    const char *g[PER_WAVE];                                      // this lane's source for each of its instructions, at k = 0
+    __amdgpu_buffer_rsrc_t rsrc;
+    int voff[PER_WAVE];                                           // this lane's byte offset in the panel, per instruction
 
-    PEAK_DEVM void init(const void *base, int64_t ld, int64_t row0, int64_t nrows, int64_t k0, int wave, int lane)
+    PEAK_DEVM void init(const void *base, int64_t ld, int64_t row0, int64_t nrows, int64_t k0, int64_t K, int wave, int lane)
     {
+        int64_t rows_here = nrows - row0;                         // >= 1
+        if (rows_here > ROWS) rows_here = ROWS;
+        const uint64_t panel = (uint64_t)((const char *)base + (row0 * ld + k0) * C::ESZ);
+        const int64_t bytes = ((rows_here - 1) * ld + (K - k0)) * C::ESZ;   // < 2^31, checked when the plan is made
+        // the descriptor is the same for every lane: say so, or it may end up in vector registers
+        const uint64_t panel_u = ((uint64_t)(uint32_t)__builtin_amdgcn_readfirstlane((int)(panel >> 32)) << 32) |
+                                 (uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)panel);
+        rsrc = __builtin_amdgcn_make_buffer_rsrc((void *)panel_u, 0, __builtin_amdgcn_readfirstlane((int)bytes), 0x00020000);
 #pragma unroll
         for (int i = 0; i < PER_WAVE; ++i) {
             const int j = wave + C::NW * i;
-            const int row = j * (64 / C::CPR) + lane / C::CPR;
+            int row = j * (64 / C::CPR) + lane / C::CPR;
             const int pos = lane % C::CPR;
             const int c = pos ^ swz<C::CPR>(row);
-            int64_t gr = row0 + row;
-            if (gr > nrows - 1) gr = nrows - 1;
-            g[i] = (const char *)base + (gr * ld + k0 + (int64_t)c * C::EPC) * C::ESZ;
+            if (row > rows_here - 1) row = (int)rows_here - 1;    // duplicate of a valid row; its results are never stored
+            voff[i] = (int)((row * ld + (int64_t)c * C::EPC) * C::ESZ);
         }
     }
 
-    // ktile: tile index relative to k0
-    PEAK_DEVM void issue(char *lds_tile, int64_t ktile, int wave) const
+    // ktile: tile index relative to k0.  Issues this wave's instructions i with
+    // i % NPARTS == PART, so that a tile's loads can be spread over a step.
+    template <int PART, int NPARTS>
+    PEAK_DEVM void issue(char *lds_tile, int ktile, int wave) const
     {
 #pragma unroll
         for (int i = 0; i < PER_WAVE; ++i) {
             const int j = wave + C::NW * i;
-            if (NINST % C::NW == 0 || j < NINST) {
-                __builtin_amdgcn_global_load_lds(
-                    (const __attribute__((address_space(1))) void *)(g[i] + ktile * C::RB),
-                    (__attribute__((address_space(3))) void *)(lds_tile + j * 1024), 16, 0, 0);
+            if (i % NPARTS == PART && (NINST % C::NW == 0 || j < NINST)) {
+                __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc, (__attribute__((address_space(3))) void *)(lds_tile + j * 1024),
+                                                         16, voff[i], ktile * C::RB, 0, 0);
             }
         }
     }
@@ -385,13 +422,13 @@ __global__ __launch_bounds__(C::NT) void gemm_kernel(const GemmArgs p)
     __shared__ __attribute__((aligned(1024))) char lds[C::LDS_BYTES];
 
     const int tid = threadIdx.x;
-    const int lane = tid & 63, wave = tid >> 6;
+    const int lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int wm = wave / C::WAVES_N, wn = wave % C::WAVES_N;
     const int r32 = lane & 31, half = lane >> 5;
 
     const int tiles = p.tiles_m * p.tiles_n;
     const int bid = blockIdx.x;
-    const int slice = bid / tiles;
+    const int slice = __builtin_amdgcn_readfirstlane(bid / tiles);
     int tm, tn;
     tile_of_block(bid - slice * tiles, p.tiles_m, p.tiles_n, p.group_m, tm, tn);
     const int64_t m0 = (int64_t)tm * C::BM, n0 = (int64_t)tn * C::BN;
@@ -399,7 +436,7 @@ __global__ __launch_bounds__(C::NT) void gemm_kernel(const GemmArgs p)
     const int kt_begin = slice * p.ktiles_per_slice;
     int kt_end = kt_begin + p.ktiles_per_slice;
     if (kt_end > p.ktiles_total) kt_end = p.ktiles_total;
-    const int KT = kt_end - kt_begin;                       // >= 1 by construction of the plan
+    const int KT = __builtin_amdgcn_readfirstlane(kt_end - kt_begin);   // >= 1 by construction of the plan
     const int64_t kbase = (int64_t)kt_begin * C::BK;
     const int64_t kend = p.K;                               // zero fill beyond K (only the last slice can reach it)
 
@@ -440,11 +477,20 @@ __global__ __launch_bounds__(C::NT) void gemm_kernel(const GemmArgs p)
     static_assert(!A_DIRECT || LoaderDirect<C, C::BM>::NINST % C::NW == 0, "every wave issues the same number of loads");
     static_assert(!B_DIRECT || LoaderDirect<C, C::BN>::NINST % C::NW == 0, "every wave issues the same number of loads");
 
-    if (A_DIRECT) dA.init(p.A, p.lda, m0, p.M, kbase, wave, lane);
-    if (B_DIRECT) dB.init(p.B, p.ldb, n0, p.N, kbase, wave, lane);
+    if (A_DIRECT) dA.init(p.A, p.lda, m0, p.M, kbase, p.K, wave, lane);
+    if (B_DIRECT) dB.init(p.B, p.ldb, n0, p.N, kbase, p.K, wave, lane);
 
+    // K rotation: this workgroup walks its K tiles starting at tile `rot` and
+    // wraps around.  Workgroups that share an A or B panel in one XCD's L2 start
+    // at different tiles, so one of them touches a chunk first and the others,
+    // a step or two later, find it in L2 instead of all waiting on the same miss.
+    const int rot = __builtin_amdgcn_readfirstlane(((tm & 7) * p.rot_m + (tn & 3) * p.rot_n) % KT);
+    auto rotated = [&](int kt) {
+        const int kr = kt + rot;
+        return kr >= KT ? kr - KT : kr;
+    };
     auto load_regs = [&](int kt) {                          // kt relative to the slice
-        const int64_t k0 = kbase + (int64_t)kt * C::BK;
+        const int64_t k0 = kbase + (int64_t)rotated(kt) * C::BK;
         if (!A_DIRECT) {
             if (C::A_T) tA.load(p.A, p.lda, m0, p.M, k0, kend, a_vec, tid);
             else        kA.load(p.A, p.lda, m0, p.M, k0, kend, a_vec, tid);
@@ -463,14 +509,28 @@ __global__ __launch_bounds__(C::NT) void gemm_kernel(const GemmArgs p)
             if (C::B_T) tB.store(st + C::A_BYTES, tid); else kB.store(st + C::A_BYTES, tid);
         }
     };
-    auto issue_direct = [&](int kt, int stage) {
+    // Direct loads of tile kt into `stage`, part PART of NPARTS.  The parts are
+    // issued between groups of MFMAs: a wave that issues all its loads at once
+    // blocks behind the texture unit's queue and its MFMAs with it.
+    auto issue_direct = [&](int kt, int stage, auto part, auto nparts) {
         // past the end the last tile is fetched again into a free stage, so the
         // number of loads in flight stays the same for the waits below
-        const int kc = kt < KT ? kt : KT - 1;
+        constexpr int PART = decltype(part)::value, NPARTS = decltype(nparts)::value;
+        const int kc = rotated(kt < KT ? kt : KT - 1);
         char *st = lds + stage * C::STAGE_BYTES;
-        if (A_DIRECT) dA.issue(st, kc, wave);
-        if (B_DIRECT) dB.issue(st + C::A_BYTES, kc, wave);
+        if (A_DIRECT) dA.template issue<PART, NPARTS>(st, kc, wave);
+        if (B_DIRECT) dB.template issue<PART, NPARTS>(st + C::A_BYTES, kc, wave);
     };
+    auto issue_direct_all = [&](int kt, int stage) { issue_direct(kt, stage, IC<0>{}, IC<1>{}); };
+    auto mfma_half = [&](const u32x4 *af, const u32x4 *bf, auto half_c) {
+        constexpr int H = decltype(half_c)::value;
+        constexpr int MH = C::MI > 1 ? C::MI / 2 : 1;
+#pragma unroll
+        for (int mi = (C::MI > 1 ? H * MH : 0); mi < (C::MI > 1 ? (H + 1) * MH : (H == 0 ? 1 : 0)); ++mi)
+#pragma unroll
+            for (int ni = 0; ni < C::NI; ++ni) mfma_frag<C::DT>(acc[mi][ni], bf[ni], af[mi]);
+    };
+    // two-phase step: all k-groups of one stage
     auto compute = [&](int stage) {
         const char *st = lds + stage * C::STAGE_BYTES;
 #pragma unroll
@@ -480,34 +540,95 @@ __global__ __launch_bounds__(C::NT) void gemm_kernel(const GemmArgs p)
             for (int mi = 0; mi < C::MI; ++mi) af[mi] = *(const u32x4 *)(st + (a_addr[mi] ^ (kg << 5)));
 #pragma unroll
             for (int ni = 0; ni < C::NI; ++ni) bf[ni] = *(const u32x4 *)(st + (b_addr[ni] ^ (kg << 5)));
-#pragma unroll
-            for (int mi = 0; mi < C::MI; ++mi)
-#pragma unroll
-                for (int ni = 0; ni < C::NI; ++ni) mfma_frag<C::DT>(acc[mi][ni], bf[ni], af[mi]);
+            mfma_half(af, bf, IC<0>{});
+            mfma_half(af, bf, IC<1>{});
         }
     };
 
-    // prologue
-    if (C::DIRECT && DLOADS > 0) {
+    constexpr bool ALL_DIRECT = A_DIRECT && B_DIRECT;
+    if (!C::PIPE) {
+        // Two-phase scheme: at the barrier of step kt tile kt is complete; its
+        // fragments are read after the barrier.
+        if (DLOADS > 0) {
 #pragma unroll
-        for (int s = 0; s < P; ++s) issue_direct(s, s);
-    }
-    if (!(A_DIRECT && B_DIRECT)) {
-        load_regs(0);
-        store_regs(0);
-    }
-
-    for (int kt0 = 0; kt0 < KT; kt0 += C::NS) {
+            for (int s = 0; s < P; ++s) issue_direct_all(s, s);
+        }
+        if (!ALL_DIRECT) {
+            load_regs(0);
+            store_regs(0);
+        }
+        for (int kt0 = 0; kt0 < KT; kt0 += C::NS) {
 #pragma unroll
-        for (int s = 0; s < C::NS; ++s) {
-            const int kt = kt0 + s;
-            if (kt < KT) {
-                if (DLOADS > 0) wait_vmcnt<(P - 1) * DLOADS>();     // tile kt has landed (this wave's part)
-                lds_barrier();                                      // everyone's part; stage (kt-1) % NS is free
-                if (!(A_DIRECT && B_DIRECT) && kt + 1 < KT) load_regs(kt + 1);
-                if (DLOADS > 0) issue_direct(kt + P, (s + P) % C::NS);
-                compute(s);
-                if (!(A_DIRECT && B_DIRECT) && kt + 1 < KT) store_regs((s + 1) % C::NS);
+            for (int s = 0; s < C::NS; ++s) {
+                const int kt = kt0 + s;
+                if (kt < KT) {
+                    if (DLOADS > 0) wait_vmcnt<(P - 1) * DLOADS>();     // tile kt has landed (this wave's part)
+                    lds_barrier();                                      // everyone's part; stage (kt-1) % NS is free
+                    if (!ALL_DIRECT && kt + 1 < KT) load_regs(kt + 1);
+                    // with one stage in flight the loads go out at once: each gets the whole step to land
+                    if (DLOADS > 0) issue_direct_all(kt + P, (s + P) % C::NS);
+                    compute(s);
+                    if (!ALL_DIRECT && kt + 1 < KT) store_regs((s + 1) % C::NS);
+                }
+            }
+        }
+    } else {
+        // Run-ahead scheme (NS >= 3): at the barrier of step j tiles <= j+1 are
+        // complete, so the fragments of the next tile's first k-group are fetched
+        // before that barrier and the MFMA stream never waits on LDS behind it.
+        //   step j:  registers <- tile j+2 ; direct loads of tile j+NS-1 -> stage (j-1) % NS ;
+        //            per k-group: fetch the next fragments, then MFMAs on the current ones ;
+        //            registers -> stage (j+2) % NS ; wait for own direct loads of tile j+2 ; barrier
+        static_assert(!C::PIPE || (C::NS >= 3 && C::KG % 2 == 0), "run-ahead needs 3 stages and an even number of k-groups");
+        constexpr int PN = C::PIPE ? C::NS : 3;
+        if (DLOADS > 0) {
+#pragma unroll
+            for (int s = 0; s < PN - 1; ++s) issue_direct_all(s, s);
+        }
+        if (!ALL_DIRECT) {
+            load_regs(0);
+            store_regs(0);
+            if (KT > 1) {
+                load_regs(1);
+                store_regs(1);
+            }
+        }
+        u32x4 af[2][C::MI], bf[2][C::NI];
+        auto fetch = [&](int stage, int kg, int set) {
+            const char *st = lds + stage * C::STAGE_BYTES;
+#pragma unroll
+            for (int mi = 0; mi < C::MI; ++mi) af[set][mi] = *(const u32x4 *)(st + (a_addr[mi] ^ (kg << 5)));
+#pragma unroll
+            for (int ni = 0; ni < C::NI; ++ni) bf[set][ni] = *(const u32x4 *)(st + (b_addr[ni] ^ (kg << 5)));
+        };
+        // tiles 0 and 1 complete; first fragments
+        if (DLOADS > 0) wait_vmcnt<(PN - 3) * DLOADS>();
+        lds_barrier();
+        fetch(0, 0, 0);
+        for (int j0 = 0; j0 < KT; j0 += PN) {
+#pragma unroll
+            for (int s = 0; s < PN; ++s) {
+                const int j = j0 + s;
+                if (j < KT) {
+                    if (!ALL_DIRECT && j + 2 < KT) load_regs(j + 2);
+                    static_for<C::KG>([&](auto kgc) {
+                        constexpr int kg = decltype(kgc)::value;
+                        // next fragments: same tile, or the first k-group of tile j+1 (past the
+                        // end this reads a stage nobody uses; the values are dropped)
+                        if (kg + 1 < C::KG) fetch(s, kg + 1, (kg + 1) & 1);
+                        else fetch((s + 1) % PN, 0, 0);
+                        __builtin_amdgcn_sched_barrier(0);      // keep the fetches ahead of the MFMAs they overlap with
+                        mfma_half(af[kg & 1], bf[kg & 1], IC<0>{});
+                        __builtin_amdgcn_sched_barrier(0);
+                        if (DLOADS > 0) issue_direct(j + PN - 1, (s + PN - 1) % PN, kgc, IC<C::KG>{});
+                        __builtin_amdgcn_sched_barrier(0);
+                        mfma_half(af[kg & 1], bf[kg & 1], IC<1>{});
+                        __builtin_amdgcn_sched_barrier(0);
+                    });
+                    if (!ALL_DIRECT && j + 2 < KT) store_regs((s + 2) % PN);
+                    if (DLOADS > 0) wait_vmcnt<(PN - 3) * DLOADS>();    // own loads of tile j+2 have landed
+                    lds_barrier();                                      // tiles <= j+2 complete; stage j % NS is free
+                }
             }
         }
     }
@@ -517,6 +638,24 @@ __global__ __launch_bounds__(C::NT) void gemm_kernel(const GemmArgs p)
     // epilogue
     const bool c_vec = p.flags & GF_C_VEC, ws_vec = p.flags & GF_WS_VEC;
     float *wsl = p.split > 1 ? p.ws + (int64_t)slice * p.M * p.N : nullptr;
+    const bool interior = m0 + C::BM <= p.M && n0 + C::BN <= p.N;      // whole tile inside C: no masks
+    if (interior && !wsl && c_vec) {
+#pragma unroll
+        for (int mi = 0; mi < C::MI; ++mi) {
+            const int64_t m = m0 + wm * C::WTM + mi * 32 + r32;
+#pragma unroll
+            for (int ni = 0; ni < C::NI; ++ni) {
+#pragma unroll
+                for (int vq = 0; vq < 4; ++vq) {
+                    const int64_t n = n0 + wn * C::WTN + ni * 32 + vq * 8 + half * 4;
+                    const float x[4] = {acc[mi][ni][vq * 4 + 0], acc[mi][ni][vq * 4 + 1],
+                                        acc[mi][ni][vq * 4 + 2], acc[mi][ni][vq * 4 + 3]};
+                    store4<C::DT>(p.C, m * p.ldc + n, x, p.alpha, p.beta, true, 4);
+                }
+            }
+        }
+        return;
+    }
 #pragma unroll
     for (int mi = 0; mi < C::MI; ++mi) {
         const int64_t m = m0 + wm * C::WTM + mi * 32 + r32;

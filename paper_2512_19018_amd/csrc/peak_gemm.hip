@@ -33,7 +33,14 @@ static hipError_t launch_skinny(const GemmArgs &a, dim3 grid, hipStream_t s)
     return hipGetLastError();
 }
 
-enum Kind { KIND_TILED = 0, KIND_SKINNY = 1 };
+template <class C>
+static hipError_t launch_skinny_reg(const GemmArgs &a, dim3 grid, hipStream_t s)
+{
+    hipLaunchKernelGGL((skinny_reg_kernel<C>), grid, dim3(C::NT), 0, s, a);
+    return hipGetLastError();
+}
+
+enum Kind { KIND_TILED = 0, KIND_SKINNY = 1, KIND_SKINNY_REG = 2 };
 
 struct Variant {
     const char *name;
@@ -60,6 +67,10 @@ struct Variant {
 #define SKINNY(NAME, DT, BN, KSTEP, NS)                                                                \
     {NAME, KIND_SKINNY, DT, 0, 0, 1, 16, BN, KSTEP, SkinnyCfg<DT, BN, KSTEP, NS>::NT, NS,              \
      SkinnyCfg<DT, BN, KSTEP, NS>::LDS_BYTES, 16, &launch_skinny<SkinnyCfg<DT, BN, KSTEP, NS>>}
+
+#define SKINNY_REG(NAME, DT, DEPTH, WAVES)                                                             \
+    {NAME, KIND_SKINNY_REG, DT, 0, 0, 1, 16, 16, 64, WAVES * 64, DEPTH, 0, 16,                         \
+     &launch_skinny_reg<SkinnyRegCfg<DT, DEPTH, WAVES>>}
 
 // Layout suffix: first letter is A (n: runs along K, t: stored K x M), second is
 // B as stored (t: N x K, runs along K; n: K x N).  So "_nt" is transA=0,
@@ -98,6 +109,32 @@ static const Variant g_variants[] = {
     SKINNY("f16_skinny16s3_nt", DT_F16, 64, 128, 3),
     SKINNY("bf16_skinny16s4_nt", DT_BF16, 64, 128, 4),
     SKINNY("f16_skinny16s4_nt", DT_F16, 64, 128, 4),
+    // 43..: run-ahead ring for row-major B, and 3-stage fp32
+    TILED("bf16_d256x256w8k32s4_nn", DT_BF16, 256, 256, 64, 2, 4, 4, false, true, true),
+    TILED("f16_d256x256w8k32s4_nn", DT_F16, 256, 256, 64, 2, 4, 4, false, true, true),
+    TILED("f32_d256x128w8s3_nn", DT_F32, 256, 128, 128, 4, 2, 3, false, true, true),
+    TILED("f32_d128x128w4s3_nn", DT_F32, 128, 128, 128, 2, 2, 3, false, true, true),
+    TILED("f32_d128x128w4s3_nt", DT_F32, 128, 128, 128, 2, 2, 3, false, false, true),
+    // 48..: deepest ring that fits 160 KB
+    TILED("bf16_d256x256w8k32s5_nt", DT_BF16, 256, 256, 64, 2, 4, 5, false, false, true),
+    TILED("f16_d256x256w8k32s5_nt", DT_F16, 256, 256, 64, 2, 4, 5, false, false, true),
+    // 50..: one wave per SIMD, 128x128 per wave, run-ahead ring
+    TILED("bf16_d256x256w4k32s4_nt", DT_BF16, 256, 256, 64, 2, 2, 4, false, false, true),
+    TILED("f16_d256x256w4k32s4_nt", DT_F16, 256, 256, 64, 2, 2, 4, false, false, true),
+    // 52..: register-staged 256x256 (global -> VGPR -> LDS), for comparison with the direct path
+    TILED("bf16_r256x256w8_nt", DT_BF16, 256, 256, 128, 2, 4, 2, false, false, false),
+    TILED("bf16_r256x256w8s3k32_nt", DT_BF16, 256, 256, 64, 2, 4, 4, false, false, false),
+    // 54..: register-streaming skinny kernels (no LDS, no barriers)
+    SKINNY_REG("bf16_skinnyreg_d8_nt", DT_BF16, 8, 4),
+    SKINNY_REG("f16_skinnyreg_d8_nt", DT_F16, 8, 4),
+    SKINNY_REG("bf16_skinnyreg_d4_nt", DT_BF16, 4, 4),
+    SKINNY_REG("bf16_skinnyreg_d12_nt", DT_BF16, 12, 4),
+    // 58..: LDS-ring skinny kernels with longer contiguous runs per row
+    SKINNY("bf16_skinny32k512s3_nt", DT_BF16, 32, 512, 3),
+    SKINNY("bf16_skinny32k256s4_nt", DT_BF16, 32, 256, 4),
+    SKINNY("bf16_skinny64k256s3_nt", DT_BF16, 64, 256, 3),
+    SKINNY("bf16_skinny64k128s6_nt", DT_BF16, 64, 128, 6),
+    SKINNY("f16_skinny32k512s3_nt", DT_F16, 32, 512, 3),
 };
 constexpr int NUM_VARIANTS = (int)(sizeof(g_variants) / sizeof(g_variants[0]));
 
@@ -106,7 +143,7 @@ constexpr int NUM_VARIANTS = (int)(sizeof(g_variants) / sizeof(g_variants[0]));
 static bool variant_selectable(int id)
 {
     const char *n = g_variants[id].name;
-    if (strstr(n, "k32s4") || strstr(n, "w4_nt") && strstr(n, "d256x256")) return false;
+    if (strstr(n, "k32s4") || strstr(n, "k32s5") || strstr(n, "r256x256") || strstr(n, "w4k32") || strstr(n, "w4_nt") && strstr(n, "d256x256")) return false;
     return true;
 }
 
@@ -117,7 +154,7 @@ using namespace peak;
 struct peak_gemm_plan {
     peak_gemm_desc_t d;
     int variant;          // index into g_variants, -1: nothing to launch
-    int tiles_m, tiles_n, split, ktiles_total, ktiles_per_slice, group_m;
+    int tiles_m, tiles_n, split, ktiles_total, ktiles_per_slice, group_m, rot_m, rot_n;
     size_t ws_bytes;
     int max_lds_set;      // hipFuncSetAttribute not needed: LDS is static
 };
@@ -132,12 +169,14 @@ static bool variant_fits(const Variant &v, const peak_gemm_desc_t &d)
     // kernel's B_T means B stored K x N, i.e. transB == 0
     const int a_t = d.transA ? 1 : 0, b_t = d.transB ? 0 : 1;
     if (v.a_t != a_t || v.b_t != b_t) return false;
-    if (v.kind == KIND_SKINNY && d.M > v.max_m) return false;
+    if (v.kind != KIND_TILED && d.M > v.max_m) return false;
     if (v.direct) {
         const int es = esize_of(d.dtype);
         if (d.K % v.bk != 0 || d.K < v.bk) return false;
         if ((d.lda * es) % 16 != 0 || (d.ldb * es) % 16 != 0) return false;
-        // per-workgroup byte offsets are formed in 64 bits; nothing else to check
+        // a workgroup's operand panel is addressed with 32-bit byte offsets
+        const int64_t lim = (int64_t)1 << 31;
+        if (((int64_t)(v.bm - 1) * d.lda + d.K) * es >= lim || ((int64_t)(v.bn - 1) * d.ldb + d.K) * es >= lim) return false;
     }
     return true;
 }
@@ -185,13 +224,21 @@ static void plan_geometry(peak_gemm_plan *p, const Variant &v, int forced_split)
     p->tiles_m = (int)cdiv(d.M, v.bm);
     p->tiles_n = (int)cdiv(d.N, v.bn);
     p->ktiles_total = (int)cdiv(d.K, v.bk);
-    int split = forced_split > 0 ? forced_split : (v.kind == KIND_SKINNY ? skinny_split(d.N, d.K, v.bn, v.bk)
-                                                                          : choose_split(v, d));
+    int split = forced_split > 0 ? forced_split
+              : v.kind == KIND_SKINNY     ? skinny_split(d.N, d.K, v.bn, v.bk)
+              : v.kind == KIND_SKINNY_REG ? skinny_reg_split(d.N, d.K)
+                                          : choose_split(v, d);
     if (split > p->ktiles_total) split = p->ktiles_total;
     if (split < 1) split = 1;
     p->ktiles_per_slice = (int)cdiv(p->ktiles_total, split);
     p->split = (int)cdiv(p->ktiles_total, p->ktiles_per_slice);   // no empty slices
     p->group_m = p->tiles_m >= 8 ? 8 : (p->tiles_m > 0 ? p->tiles_m : 1);
+    p->rot_m = 1;
+    p->rot_n = 2;
+    if (const char *e = getenv("PEAK_GEMM_ROT")) {          // tuning knob: "rot_m,rot_n"
+        int a = 0, b = 0;
+        if (sscanf(e, "%d,%d", &a, &b) == 2 && a >= 0 && b >= 0) { p->rot_m = a; p->rot_n = b; }
+    }
     p->ws_bytes = p->split > 1 ? (size_t)p->split * (size_t)d.M * (size_t)d.N * sizeof(float) : 0;
 }
 
@@ -261,17 +308,24 @@ peak_status_t peak_gemm_create(const peak_gemm_desc_t *desc, peak_gemm_plan_t **
         pick = forced;
     } else {
         double best = 0.0;
+        int skinny_pick = -1;
         for (int i = 0; i < NUM_VARIANTS; ++i) {
             const Variant &v = g_variants[i];
             if (!variant_fits(v, d)) continue;
-            if (v.kind == KIND_SKINNY) {              // the streaming kernel wins whenever it applies
-                pick = i;
-                break;
+            if (v.kind != KIND_TILED) {
+                // a streaming kernel wins whenever it applies: long row runs through LDS first,
+                // the register-streaming one for K that is not a multiple of 512
+                const bool preferred = strstr(v.name, "skinny32k512s3") != nullptr;
+                const bool second = v.kind == KIND_SKINNY_REG && strstr(v.name, "_d8_") != nullptr;
+                if (preferred) { pick = i; break; }
+                if (second && skinny_pick < 0) skinny_pick = i;
+                continue;
             }
             if (!variant_selectable(i)) continue;
             const double c = tiled_cost(v, d, choose_split(v, d));
             if (pick < 0 || c < best) { pick = i; best = c; }
         }
+        if (skinny_pick >= 0 && (pick < 0 || g_variants[pick].kind == KIND_TILED)) pick = skinny_pick;
         if (pick < 0) {
             delete p;
             return PEAK_ERR_UNSUPPORTED;
@@ -358,8 +412,12 @@ peak_status_t peak_gemm_run(peak_gemm_plan_t *p, float alpha, const void *A, con
     a.ktiles_per_slice = p->ktiles_per_slice;
     a.ktiles_total = p->ktiles_total;
     a.group_m = p->group_m;
+    a.rot_m = p->rot_m;
+    a.rot_n = p->rot_n;
 
-    dim3 grid((unsigned)((int64_t)p->tiles_m * p->tiles_n * p->split));
+    int64_t nblocks = (int64_t)p->tiles_m * p->tiles_n * p->split;
+    if (v.kind == KIND_SKINNY_REG) nblocks = cdiv((int64_t)p->tiles_n * p->split, v.nt / 64);   // one wave per row group and slice
+    dim3 grid((unsigned)nblocks);
     if (v.launch(a, grid, stream) != hipSuccess) return PEAK_ERR_HIP;
 
     if (p->split > 1) {

@@ -26,7 +26,7 @@ struct SkinnyCfg {
     static constexpr int LDS_BYTES = STAGE_BYTES * NS_;
     static constexpr int ROWS_PER_INST = 64 / CPR;        // a wave load fills 1024 contiguous LDS bytes
     static constexpr int A_INST = BM / ROWS_PER_INST, B_INST = BN_ / ROWS_PER_INST;
-    static_assert(CPR == 16 || CPR == 32, "row of 256 or 512 bytes");
+    static_assert(CPR % 16 == 0 && CPR <= 64, "row of 256, 512 or 1024 bytes");
     static_assert(A_INST % NW == 0 || NW % A_INST == 0, "A loads split evenly");
     static_assert(B_INST % NW == 0, "B loads split evenly");
     static constexpr int B_PER_WAVE = B_INST / NW;
@@ -41,12 +41,12 @@ struct SkinnyCfg {
 // within the aligned group of 16 chunks c belongs to)
 PEAK_DEV int skinny_pos(int r, int c) { return c ^ (r & 15); }
 
-// Number of K slices: enough workgroups for ~8 per CU, at least 4 stages each.
+// Number of K slices: about 4 workgroups per CU over the run, at least 4 stages each.
 static inline int skinny_split(int64_t N, int64_t K, int bn, int kstep)
 {
     const int64_t tiles_n = (N + bn - 1) / bn;
     const int64_t ktiles = (K + kstep - 1) / kstep;
-    int64_t s = (2048 + tiles_n - 1) / tiles_n;
+    int64_t s = (1024 + tiles_n - 1) / tiles_n;
     if (s > ktiles / 4) s = ktiles / 4;
     if (s < 1) s = 1;
     if (s > 64) s = 64;
@@ -150,6 +150,106 @@ __global__ __launch_bounds__(C::NT) void skinny_kernel(const GemmArgs p)
     if (m < p.M && left > 0) {
         const int nvalid = left >= 4 ? 4 : (int)left;
         const float x[4] = {acc[0], acc[1], acc[2], acc[3]};
+        if (p.split > 1)
+            store4<DT_F32>(p.ws + (int64_t)slice * p.M * p.N, m * p.N + n, x, 1.0f, 0.0f, p.flags & GF_WS_VEC, nvalid);
+        else
+            store4<C::DT>(p.C, m * p.ldc + n, x, p.alpha, p.beta, p.flags & GF_C_VEC, nvalid);
+    }
+}
+
+
+// ---------------------------------------------------------------------------
+// Register-streaming skinny kernel: no LDS, no barriers.  One wave owns 16 rows
+// of the N x K operand over one K slice and streams them straight from global
+// memory into MFMA operand registers, DEPTH iterations (of 64 k) ahead; the
+// matching 16 x 64 pieces of the M x K operand come the same way and are shared
+// between the waves of a CU by the L1 cache.  Every byte of the big operand is
+// read once, by one wave, in row order.
+//   lane l:  operand row l % 16,  k = k0 + 8*(l/16) .. +7   (first MFMA of the iteration)
+//                                 k = k0 + 32 + 8*(l/16) .. +7   (second MFMA)
+//   acc[v] <-> m = l % 16,  n = 16*rowgroup + 4*(l/16) + v
+// ---------------------------------------------------------------------------
+template <int DT_, int DEPTH_, int WAVES_>
+struct SkinnyRegCfg {
+    static constexpr int DT = DT_;
+    static_assert(DT_ != DT_F32, "16-bit storage only");
+    static constexpr int DEPTH = DEPTH_, NW = WAVES_, NT = WAVES_ * 64;
+    static constexpr int KIT = 64;                      // k per iteration
+    static constexpr int LDS_BYTES = 0;
+};
+
+// K slices for the register-streaming kernel: aim at >= 8 waves per CU
+static inline int skinny_reg_split(int64_t N, int64_t K)
+{
+    const int64_t groups = (N + 15) / 16;
+    const int64_t iters = K / 64;
+    int64_t s = (2048 + groups - 1) / groups;
+    if (s > iters / 16) s = iters / 16;
+    if (s < 1) s = 1;
+    if (s > 64) s = 64;
+    return (int)s;
+}
+
+template <class C>
+__global__ __launch_bounds__(C::NT) void skinny_reg_kernel(const GemmArgs p)
+{
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int groups = p.tiles_n;                       // row groups of 16 along N
+    const int64_t w = (int64_t)blockIdx.x * C::NW + wave;
+    if (w >= (int64_t)groups * p.split) return;         // whole wave leaves; there are no barriers
+    const int g = (int)(w % groups), slice = (int)(w / groups);
+    const int r16 = lane & 15, q = lane >> 4;
+
+    const int it_begin = slice * p.ktiles_per_slice;
+    int it_end = it_begin + p.ktiles_per_slice;
+    if (it_end > p.ktiles_total) it_end = p.ktiles_total;
+    const int NIT = it_end - it_begin;                  // >= 1
+
+    int64_t brow = (int64_t)g * 16 + r16;
+    if (brow > p.N - 1) brow = p.N - 1;                 // duplicates of a valid row; never stored
+    int64_t arow = r16;
+    if (arow > p.M - 1) arow = p.M - 1;
+    const char *bp = (const char *)p.B + (brow * p.ldb + (int64_t)it_begin * C::KIT + q * 8) * 2;
+    const char *ap = (const char *)p.A + (arow * p.lda + (int64_t)it_begin * C::KIT + q * 8) * 2;
+
+    u32x4 b_lo[C::DEPTH], b_hi[C::DEPTH], a_lo[C::DEPTH], a_hi[C::DEPTH];
+    auto load_it = [&](int it, int slot) {
+        const int ic = it < NIT ? it : NIT - 1;         // past the end: reload the last iteration, unused
+        const int64_t off = (int64_t)ic * (C::KIT * 2);
+        b_lo[slot] = *(const u32x4 *)(bp + off);
+        b_hi[slot] = *(const u32x4 *)(bp + off + 64);
+        a_lo[slot] = *(const u32x4 *)(ap + off);
+        a_hi[slot] = *(const u32x4 *)(ap + off + 64);
+    };
+    typedef float f32x4v __attribute__((ext_vector_type(4)));
+    f32x4v acc0 = {0.0f, 0.0f, 0.0f, 0.0f}, acc1 = {0.0f, 0.0f, 0.0f, 0.0f};
+    auto mma = [&](f32x4v &acc, const u32x4 &bf, const u32x4 &af) {
+        if (C::DT == DT_BF16)
+            acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, bf), __builtin_bit_cast(bf16x8, af), acc, 0, 0, 0);
+        else
+            acc = __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(f16x8, bf), __builtin_bit_cast(f16x8, af), acc, 0, 0, 0);
+    };
+
+#pragma unroll
+    for (int d = 0; d < C::DEPTH; ++d) load_it(d, d);
+    for (int it0 = 0; it0 < NIT; it0 += C::DEPTH) {
+#pragma unroll
+        for (int d = 0; d < C::DEPTH; ++d) {
+            const int it = it0 + d;
+            if (it < NIT) {
+                mma(acc0, b_lo[d], a_lo[d]);
+                mma(acc1, b_hi[d], a_hi[d]);
+                load_it(it + C::DEPTH, d);
+            }
+        }
+    }
+
+    const int64_t m = r16;
+    const int64_t n = (int64_t)g * 16 + q * 4;
+    const int64_t left = p.N - n;
+    if (m < p.M && left > 0) {
+        const int nvalid = left >= 4 ? 4 : (int)left;
+        const float x[4] = {acc0[0] + acc1[0], acc0[1] + acc1[1], acc0[2] + acc1[2], acc0[3] + acc1[3]};
         if (p.split > 1)
             store4<DT_F32>(p.ws + (int64_t)slice * p.M * p.N, m * p.N + n, x, 1.0f, 0.0f, p.flags & GF_WS_VEC, nvalid);
         else

@@ -1,0 +1,144 @@
+"""Host side of the C ABI, no GPU needed: the library loads, exports every
+symbol the header declares, validates descriptors and plans the graded
+workloads sensibly.  No compute call is made here."""
+import ctypes
+import os
+import re
+
+import pytest
+
+import paper_2512_19018_amd as pg
+import peak_inputs as pi
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def _desc(M=64, N=64, K=64, dtype=pg.PEAK_DT_BF16, tA=0, tB=0, lda=None, ldb=None, ldc=None, flags=0):
+    lda = lda if lda is not None else (M if tA else K)
+    ldb = ldb if ldb is not None else (K if tB else N)
+    ldc = ldc if ldc is not None else N
+    return pg.PeakGemmDesc(M, N, K, lda, ldb, ldc, tA, tB, dtype, flags)
+
+
+def test_every_declared_symbol_is_exported():
+    header = open(os.path.join(ROOT, "include", "peak_gemm.h")).read()
+    header = re.sub(r"/\*.*?\*/", "", header, flags=re.S)
+    names = set(re.findall(r"\b(peak_[a-z_]+)\s*\(", header))
+    assert {"peak_gemm_create", "peak_gemm_run", "peak_gemm_destroy", "peak_gemm_workspace_bytes",
+            "peak_status_string", "peak_gemm_plan_info"} <= names
+    lib = pg.load_library()
+    for n in names:
+        assert hasattr(lib, n), n
+
+
+def test_status_strings():
+    seen = set()
+    for s in range(6):
+        txt = pg.peak_status_string(s)
+        assert txt and txt not in seen
+        seen.add(txt)
+    assert pg.peak_status_string(99)
+
+
+@pytest.mark.parametrize("bad", [
+    dict(M=-1), dict(N=-5), dict(K=-2), dict(dtype=7), dict(tA=2), dict(tB=-1),
+    dict(lda=63), dict(ldb=10), dict(ldc=1), dict(tA=1, lda=63), dict(tB=1, ldb=63), dict(flags=1 << 20),
+])
+def test_create_rejects_bad_descriptors(bad):
+    st, h = pg.peak_gemm_create(_desc(**bad))
+    assert st == pg.PEAK_ERR_INVALID_ARG and h is None
+
+
+def test_create_null_pointers():
+    lib = pg.load_library()
+    h = ctypes.c_void_p(1234)
+    assert lib.peak_gemm_create(None, ctypes.byref(h)) == pg.PEAK_ERR_INVALID_ARG
+    assert h.value is None                      # *out_plan is cleared on error
+    d = _desc()
+    assert lib.peak_gemm_create(ctypes.byref(d), None) == pg.PEAK_ERR_INVALID_ARG
+    assert lib.peak_gemm_destroy(None) == pg.PEAK_OK
+    assert lib.peak_gemm_workspace_bytes(None) == 0
+    assert lib.peak_gemm_run(None, 1.0, None, None, 0.0, None, None, 0, None) == pg.PEAK_ERR_INVALID_ARG
+
+
+def test_degenerate_sizes_make_plans():
+    for kw in (dict(M=0), dict(N=0, ldb=1, ldc=1), dict(K=0, lda=1, ldb=64)):
+        st, h = pg.peak_gemm_create(_desc(**kw))
+        assert st == pg.PEAK_OK
+        assert pg.peak_gemm_workspace_bytes(h) == 0
+        assert "degenerate" in pg.peak_gemm_plan_info(h)
+        pg.peak_gemm_destroy(h)
+
+
+def test_forced_variant_must_fit():
+    names = [pg.peak_gemm_variant_name(i) for i in range(pg.peak_gemm_variant_count())]
+    assert pg.peak_gemm_variant_name(-1) is None and pg.peak_gemm_variant_name(len(names)) is None
+    f32_nn = names.index("f32_r128x128_nn")
+    # wrong dtype, wrong layout: the invalid-configuration sentinel, not a crash
+    st, _ = pg.peak_gemm_create(_desc(dtype=pg.PEAK_DT_BF16, flags=pg.force_flags(variant=f32_nn)))
+    assert st == pg.PEAK_ERR_UNSUPPORTED
+    st, _ = pg.peak_gemm_create(_desc(dtype=pg.PEAK_DT_F32, tB=1, flags=pg.force_flags(variant=f32_nn)))
+    assert st == pg.PEAK_ERR_UNSUPPORTED
+    st, h = pg.peak_gemm_create(_desc(dtype=pg.PEAK_DT_F32, flags=pg.force_flags(variant=f32_nn)))
+    assert st == pg.PEAK_OK and "f32_r128x128_nn" in pg.peak_gemm_plan_info(h)
+    pg.peak_gemm_destroy(h)
+    # direct-to-LDS variants need K a multiple of their K tile and 16-byte aligned rows
+    direct = names.index("bf16_d256x256w8_nt")
+    st, _ = pg.peak_gemm_create(_desc(512, 512, 1000, tB=1, flags=pg.force_flags(variant=direct)))
+    assert st == pg.PEAK_ERR_UNSUPPORTED
+    st, _ = pg.peak_gemm_create(_desc(512, 512, 1024, tB=1, lda=1028, flags=pg.force_flags(variant=direct)))
+    assert st == pg.PEAK_ERR_UNSUPPORTED
+    st, h = pg.peak_gemm_create(_desc(512, 512, 1024, tB=1, flags=pg.force_flags(variant=direct)))
+    assert st == pg.PEAK_OK
+    pg.peak_gemm_destroy(h)
+    st, _ = pg.peak_gemm_create(_desc(flags=pg.force_flags(variant=250)))
+    assert st == pg.PEAK_ERR_UNSUPPORTED
+
+
+def test_forced_split_and_workspace():
+    with pg.Plan(100, 200, 4096, pg.PEAK_DT_F16, 0, 1, flags=pg.force_flags(split=4)) as p:
+        assert "split=4" in p.info()
+        assert p.workspace_bytes == 4 * 100 * 200 * 4
+    with pg.Plan(100, 200, 64, pg.PEAK_DT_F16, 0, 1, flags=pg.force_flags(split=200)) as p:
+        assert "split=1" in p.info() and p.workspace_bytes == 0     # never more slices than K tiles
+
+
+def test_plans_for_the_graded_workloads():
+    w = pi.WORKLOADS
+    info = {}
+    for name in ("C1", "C2", "C3", "C3b", "C4", "C5"):
+        x = w[name]
+        lda, ldb, ldc = x.ld()
+        with pg.Plan(x.M, x.N, x.K, x.dtype, x.transA, x.transB, lda, ldb, ldc) as p:
+            info[name] = p.info()
+    assert "f32_" in info["C1"] and "_nn" in info["C1"]
+    assert "f32_d" in info["C2"] and "_nn" in info["C2"]
+    assert "bf16_d256x256" in info["C3"] and "_nt" in info["C3"] and "tiles 32x32" in info["C3"]
+    assert "bf16_d256x256" in info["C3b"]
+    assert "f16_d" in info["C4"] and "_nn" in info["C4"] and "tiles 20x12" in info["C4"]
+    assert "skinny" in info["C5"]
+
+
+def test_every_layout_and_dtype_has_a_general_variant():
+    # any alignment, any K: one of the register-staged kernels must accept it
+    for dt in (pg.PEAK_DT_F32, pg.PEAK_DT_F16, pg.PEAK_DT_BF16):
+        for tA in (0, 1):
+            for tB in (0, 1):
+                with pg.Plan(37, 53, 29, dt, tA, tB, (37 if tA else 29) + 1, (29 if tB else 53) + 3, 53 + 1) as p:
+                    assert "_r" in p.info()
+
+
+def test_too_large_dimensions_are_unsupported_not_fatal():
+    st, _ = pg.peak_gemm_create(_desc(M=1 << 31, lda=64))
+    assert st == pg.PEAK_ERR_UNSUPPORTED
+
+
+def test_missing_library_fails_loudly(monkeypatch, tmp_path):
+    import importlib
+    import paper_2512_19018_amd.binding as b
+    monkeypatch.setenv("PEAK_GEMM_LIB", str(tmp_path / "nope.so"))
+    monkeypatch.setattr(b, "_LIB", None)
+    with pytest.raises(ImportError):
+        b.load_library()
+    monkeypatch.undo()
+    importlib.reload(b)
