@@ -108,7 +108,7 @@ PEAK_DEV int swz(int r)
 }
 
 template <int DT_, int BM_, int BN_, int RB_, int WAVES_M_, int WAVES_N_, int NS_,
-          bool A_T_, bool B_T_, bool DIRECT_>
+          bool A_T_, bool B_T_, bool DIRECT_, int AX_ = 0>
 struct Cfg {
     static constexpr int DT = DT_;
     static constexpr int ESZ = DT_ == DT_F32 ? 4 : 2;
@@ -128,9 +128,13 @@ struct Cfg {
     static constexpr bool DIRECT = DIRECT_;           // K-running operands go global -> LDS directly
     static constexpr int A_BYTES = BM_ * RB_;
     static constexpr int B_BYTES = BN_ * RB_;
-    static constexpr int STAGE_BYTES = A_BYTES + B_BYTES;
-    static constexpr int LDS_BYTES = STAGE_BYTES * NS_;
-    static constexpr bool PIPE = NS_ >= 3;            // run-ahead main loop (see gemm_kernel)
+    // LDS: NSA stages of the A tile, then NSB stages of the B tile.  AX extra A
+    // stages let A's loads run one more step ahead than B's when LDS cannot hold
+    // another full stage of both (asymmetric ring, all-direct two-phase loop only).
+    static constexpr int NSA = NS_ + AX_, NSB = NS_;
+    static constexpr int LDS_BYTES = A_BYTES * NSA + B_BYTES * NSB;
+    static constexpr bool PIPE = NS_ >= 3 && AX_ == 0;   // run-ahead main loop (see gemm_kernel)
+    static_assert(AX_ == 0 || (NS_ == 2 && DIRECT_ && !A_T_ && !B_T_), "extra A stages: two-phase, both operands direct");
     static_assert(WTM % 32 == 0 && WTN % 32 == 0, "wave tile is a grid of 32x32 MFMA blocks");
     static_assert(RB_ == 128 || RB_ == 64, "tile row is 64 or 128 bytes");
     static_assert((BM_ * CPR) % 64 == 0 && (BN_ * CPR) % 64 == 0, "whole wave loads");
@@ -460,7 +464,7 @@ __global__ __launch_bounds__(C::NT) void gemm_kernel(const GemmArgs p)
 #pragma unroll
     for (int ni = 0; ni < C::NI; ++ni) {
         const int r = wn * C::WTN + ni * 32 + r32;
-        b_addr[ni] = C::A_BYTES + r * C::RB + ((half ^ swz<C::CPR>(r)) << 4);
+        b_addr[ni] = r * C::RB + ((half ^ swz<C::CPR>(r)) << 4);
     }
 
     // operand loaders
@@ -472,13 +476,18 @@ __global__ __launch_bounds__(C::NT) void gemm_kernel(const GemmArgs p)
     LoaderT<C, C::BM> tA;
     LoaderT<C, C::BN> tB;
     // loads per thread and tile that stay in flight across iterations
-    constexpr int DLOADS = (A_DIRECT ? LoaderDirect<C, C::BM>::PER_WAVE : 0) + (B_DIRECT ? LoaderDirect<C, C::BN>::PER_WAVE : 0);
+    constexpr int LA = A_DIRECT ? LoaderDirect<C, C::BM>::PER_WAVE : 0;
+    constexpr int LB = B_DIRECT ? LoaderDirect<C, C::BN>::PER_WAVE : 0;
+    constexpr int DLOADS = LA + LB;
     constexpr int P = C::NS - 1;                            // prefetch distance of the direct loads
     static_assert(!A_DIRECT || LoaderDirect<C, C::BM>::NINST % C::NW == 0, "every wave issues the same number of loads");
     static_assert(!B_DIRECT || LoaderDirect<C, C::BN>::NINST % C::NW == 0, "every wave issues the same number of loads");
 
     if (A_DIRECT) dA.init(p.A, p.lda, m0, p.M, kbase, p.K, wave, lane);
     if (B_DIRECT) dB.init(p.B, p.ldb, n0, p.N, kbase, p.K, wave, lane);
+
+    auto a_stage = [&](int s) { return lds + s * C::A_BYTES; };
+    auto b_stage = [&](int s) { return lds + C::NSA * C::A_BYTES + s * C::B_BYTES; };
 
     // K rotation: this workgroup walks its K tiles starting at tile `rot` and
     // wraps around.  Workgroups that share an A or B panel in one XCD's L2 start
@@ -500,28 +509,29 @@ __global__ __launch_bounds__(C::NT) void gemm_kernel(const GemmArgs p)
             else        kB.load(p.B, p.ldb, n0, p.N, k0, kend, b_vec, tid);
         }
     };
-    auto store_regs = [&](int stage) {
-        char *st = lds + stage * C::STAGE_BYTES;
+    auto store_regs = [&](int sa, int sb) {
         if (!A_DIRECT) {
-            if (C::A_T) tA.store(st, tid); else kA.store(st, tid);
+            if (C::A_T) tA.store(a_stage(sa), tid); else kA.store(a_stage(sa), tid);
         }
         if (!B_DIRECT) {
-            if (C::B_T) tB.store(st + C::A_BYTES, tid); else kB.store(st + C::A_BYTES, tid);
+            if (C::B_T) tB.store(b_stage(sb), tid); else kB.store(b_stage(sb), tid);
         }
     };
-    // Direct loads of tile kt into `stage`, part PART of NPARTS.  The parts are
-    // issued between groups of MFMAs: a wave that issues all its loads at once
-    // blocks behind the texture unit's queue and its MFMAs with it.
-    auto issue_direct = [&](int kt, int stage, auto part, auto nparts) {
-        // past the end the last tile is fetched again into a free stage, so the
-        // number of loads in flight stays the same for the waits below
+    // Direct loads of tile kt, part PART of NPARTS (the parts of a tile can be
+    // issued between groups of MFMAs).  Past the end the last tile is fetched again
+    // into a free stage, so the number of loads in flight stays what the waits assume.
+    auto issue_a = [&](int kt, int sa, auto part, auto nparts) {
         constexpr int PART = decltype(part)::value, NPARTS = decltype(nparts)::value;
-        const int kc = rotated(kt < KT ? kt : KT - 1);
-        char *st = lds + stage * C::STAGE_BYTES;
-        if (A_DIRECT) dA.template issue<PART, NPARTS>(st, kc, wave);
-        if (B_DIRECT) dB.template issue<PART, NPARTS>(st + C::A_BYTES, kc, wave);
+        if (A_DIRECT) dA.template issue<PART, NPARTS>(a_stage(sa), rotated(kt < KT ? kt : KT - 1), wave);
     };
-    auto issue_direct_all = [&](int kt, int stage) { issue_direct(kt, stage, IC<0>{}, IC<1>{}); };
+    auto issue_b = [&](int kt, int sb, auto part, auto nparts) {
+        constexpr int PART = decltype(part)::value, NPARTS = decltype(nparts)::value;
+        if (B_DIRECT) dB.template issue<PART, NPARTS>(b_stage(sb), rotated(kt < KT ? kt : KT - 1), wave);
+    };
+    auto issue_direct_all = [&](int kt, int stage) {
+        issue_a(kt, stage, IC<0>{}, IC<1>{});
+        issue_b(kt, stage, IC<0>{}, IC<1>{});
+    };
     auto mfma_half = [&](const u32x4 *af, const u32x4 *bf, auto half_c) {
         constexpr int H = decltype(half_c)::value;
         constexpr int MH = C::MI > 1 ? C::MI / 2 : 1;
@@ -531,22 +541,48 @@ __global__ __launch_bounds__(C::NT) void gemm_kernel(const GemmArgs p)
             for (int ni = 0; ni < C::NI; ++ni) mfma_frag<C::DT>(acc[mi][ni], bf[ni], af[mi]);
     };
     // two-phase step: all k-groups of one stage
-    auto compute = [&](int stage) {
-        const char *st = lds + stage * C::STAGE_BYTES;
+    auto compute = [&](int sa, int sb) {
+        const char *sta = a_stage(sa), *stb = b_stage(sb);
 #pragma unroll
         for (int kg = 0; kg < C::KG; ++kg) {
             u32x4 af[C::MI], bf[C::NI];
 #pragma unroll
-            for (int mi = 0; mi < C::MI; ++mi) af[mi] = *(const u32x4 *)(st + (a_addr[mi] ^ (kg << 5)));
+            for (int mi = 0; mi < C::MI; ++mi) af[mi] = *(const u32x4 *)(sta + (a_addr[mi] ^ (kg << 5)));
 #pragma unroll
-            for (int ni = 0; ni < C::NI; ++ni) bf[ni] = *(const u32x4 *)(st + (b_addr[ni] ^ (kg << 5)));
+            for (int ni = 0; ni < C::NI; ++ni) bf[ni] = *(const u32x4 *)(stb + (b_addr[ni] ^ (kg << 5)));
             mfma_half(af, bf, IC<0>{});
             mfma_half(af, bf, IC<1>{});
         }
     };
 
     constexpr bool ALL_DIRECT = A_DIRECT && B_DIRECT;
-    if (!C::PIPE) {
+    if (C::NSA != C::NSB) {
+        // Two-phase scheme with A running further ahead than B (all direct).  Per
+        // step the order of issue is B(j+PB) then A(j+PA); at the barrier of step j
+        // tile j of both operands must be complete.
+        constexpr int PA = C::NSA - 1, PB = C::NSB - 1;
+        constexpr int U = C::NSA * C::NSB;                              // unroll: both stage indices static
+        constexpr int ALLOWED = (PA - 1) * (LA + LB) < LA + (PB - 1) * (LA + LB) ? (PA - 1) * (LA + LB)
+                                                                               : LA + (PB - 1) * (LA + LB);
+        static_for<PA>([&](auto vc) {                                   // virtual steps -PA .. -1
+            constexpr int sv = decltype(vc)::value - PA;
+            if (sv + PB >= 0) issue_b(sv + PB, (sv + PB) % C::NSB, IC<0>{}, IC<1>{});
+            issue_a(sv + PA, (sv + PA) % C::NSA, IC<0>{}, IC<1>{});
+        });
+        for (int j0 = 0; j0 < KT; j0 += U) {
+            static_for<U>([&](auto uc) {
+                constexpr int u = decltype(uc)::value;
+                const int j = j0 + u;
+                if (j < KT) {
+                    wait_vmcnt<ALLOWED>();
+                    lds_barrier();
+                    issue_b(j + PB, (u + PB) % C::NSB, IC<0>{}, IC<1>{});
+                    issue_a(j + PA, (u + PA) % C::NSA, IC<0>{}, IC<1>{});
+                    compute(u % C::NSA, u % C::NSB);
+                }
+            });
+        }
+    } else if (!C::PIPE) {
         // Two-phase scheme: at the barrier of step kt tile kt is complete; its
         // fragments are read after the barrier.
         if (DLOADS > 0) {
@@ -555,7 +591,7 @@ __global__ __launch_bounds__(C::NT) void gemm_kernel(const GemmArgs p)
         }
         if (!ALL_DIRECT) {
             load_regs(0);
-            store_regs(0);
+            store_regs(0, 0);
         }
         for (int kt0 = 0; kt0 < KT; kt0 += C::NS) {
 #pragma unroll
@@ -567,8 +603,8 @@ __global__ __launch_bounds__(C::NT) void gemm_kernel(const GemmArgs p)
                     if (!ALL_DIRECT && kt + 1 < KT) load_regs(kt + 1);
                     // with one stage in flight the loads go out at once: each gets the whole step to land
                     if (DLOADS > 0) issue_direct_all(kt + P, (s + P) % C::NS);
-                    compute(s);
-                    if (!ALL_DIRECT && kt + 1 < KT) store_regs((s + 1) % C::NS);
+                    compute(s, s);
+                    if (!ALL_DIRECT && kt + 1 < KT) store_regs((s + 1) % C::NS, (s + 1) % C::NS);
                 }
             }
         }
@@ -587,19 +623,21 @@ __global__ __launch_bounds__(C::NT) void gemm_kernel(const GemmArgs p)
         }
         if (!ALL_DIRECT) {
             load_regs(0);
-            store_regs(0);
+            store_regs(0, 0);
             if (KT > 1) {
                 load_regs(1);
-                store_regs(1);
+                store_regs(1, 1);
             }
         }
         u32x4 af[2][C::MI], bf[2][C::NI];
         auto fetch = [&](int stage, int kg, int set) {
-            const char *st = lds + stage * C::STAGE_BYTES;
+            // in the order the MFMAs of the next k-group consume them
+            const char *sta = a_stage(stage), *stb = b_stage(stage);
 #pragma unroll
-            for (int mi = 0; mi < C::MI; ++mi) af[set][mi] = *(const u32x4 *)(st + (a_addr[mi] ^ (kg << 5)));
-#pragma unroll
-            for (int ni = 0; ni < C::NI; ++ni) bf[set][ni] = *(const u32x4 *)(st + (b_addr[ni] ^ (kg << 5)));
+            for (int i = 0; i < (C::MI > C::NI ? C::MI : C::NI); ++i) {
+                if (i < C::NI) bf[set][i] = *(const u32x4 *)(stb + (b_addr[i] ^ (kg << 5)));
+                if (i < C::MI) af[set][i] = *(const u32x4 *)(sta + (a_addr[i] ^ (kg << 5)));
+            }
         };
         // tiles 0 and 1 complete; first fragments
         if (DLOADS > 0) wait_vmcnt<(PN - 3) * DLOADS>();
@@ -617,15 +655,28 @@ __global__ __launch_bounds__(C::NT) void gemm_kernel(const GemmArgs p)
                         // end this reads a stage nobody uses; the values are dropped)
                         if (kg + 1 < C::KG) fetch(s, kg + 1, (kg + 1) & 1);
                         else fetch((s + 1) % PN, 0, 0);
-                        __builtin_amdgcn_sched_barrier(0);      // keep the fetches ahead of the MFMAs they overlap with
+                        // this k-group's share of the loads of tile j+NS-1
+                        issue_a(j + PN - 1, (s + PN - 1) % PN, kgc, IC<C::KG>{});
+                        issue_b(j + PN - 1, (s + PN - 1) % PN, kgc, IC<C::KG>{});
                         mfma_half(af[kg & 1], bf[kg & 1], IC<0>{});
-                        __builtin_amdgcn_sched_barrier(0);
-                        if (DLOADS > 0) issue_direct(j + PN - 1, (s + PN - 1) % PN, kgc, IC<C::KG>{});
-                        __builtin_amdgcn_sched_barrier(0);
                         mfma_half(af[kg & 1], bf[kg & 1], IC<1>{});
+                        // Issue order inside the k-group: one LDS read or one global load after each
+                        // MFMA.  A run of memory instructions leaves the matrix pipe idle when the
+                        // other wave of the SIMD is in the same phase (or there is no other wave);
+                        // spread out, they issue in the shadow of the MFMA before them.
+                        constexpr int NMFMA = C::MI * C::NI * (C::DT == DT_F32 ? 4 : 1);
+                        constexpr int NDS = C::MI + C::NI;
+                        constexpr int NVM = (LA + C::KG - 1 - kg) / C::KG + (LB + C::KG - 1 - kg) / C::KG;
+                        constexpr int PER = C::DT == DT_F32 ? 4 : 1;       // MFMAs per slot
+                        static_for<NMFMA / PER>([&](auto ic) {
+                            constexpr int i = decltype(ic)::value;
+                            __builtin_amdgcn_sched_group_barrier(0x008, PER, 0);
+                            if constexpr (i < NDS) __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+                            else if constexpr (i - NDS < NVM) __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);
+                        });
                         __builtin_amdgcn_sched_barrier(0);
                     });
-                    if (!ALL_DIRECT && j + 2 < KT) store_regs((s + 2) % PN);
+                    if (!ALL_DIRECT && j + 2 < KT) store_regs((s + 2) % PN, (s + 2) % PN);
                     if (DLOADS > 0) wait_vmcnt<(PN - 3) * DLOADS>();    // own loads of tile j+2 have landed
                     lds_barrier();                                      // tiles <= j+2 complete; stage j % NS is free
                 }

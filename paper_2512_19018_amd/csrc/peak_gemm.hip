@@ -58,6 +58,11 @@ struct Variant {
      Cfg<DT, BM, BN, RB, WMW, WNW, NS, AT, BT, DIR>::LDS_BYTES, 0,                                     \
      &launch_gemm<Cfg<DT, BM, BN, RB, WMW, WNW, NS, AT, BT, DIR>>}
 
+#define TILED_AX(NAME, DT, BM, BN, RB, WMW, WNW, NS, AX)                                              \
+    {NAME, KIND_TILED, DT, 0, 0, 1, BM, BN, RB / (DT == DT_F32 ? 4 : 2), WMW * WNW * 64, NS,           \
+     Cfg<DT, BM, BN, RB, WMW, WNW, NS, false, false, true, AX>::LDS_BYTES, 0,                          \
+     &launch_gemm<Cfg<DT, BM, BN, RB, WMW, WNW, NS, false, false, true, AX>>}
+
 #define TILED_LAYOUTS(NAME, DT, BM, BN, RB, WMW, WNW, NS)                                              \
     TILED(NAME "_nt", DT, BM, BN, RB, WMW, WNW, NS, false, false, false),                             \
     TILED(NAME "_nn", DT, BM, BN, RB, WMW, WNW, NS, false, true, false),                              \
@@ -135,6 +140,9 @@ static const Variant g_variants[] = {
     SKINNY("bf16_skinny64k256s3_nt", DT_BF16, 64, 256, 3),
     SKINNY("bf16_skinny64k128s6_nt", DT_BF16, 64, 128, 6),
     SKINNY("f16_skinny32k512s3_nt", DT_F16, 32, 512, 3),
+    // 63..: two B stages, three A stages (160 KB): A's loads run two steps ahead
+    TILED_AX("bf16_d256x256w8a3_nt", DT_BF16, 256, 256, 128, 2, 4, 2, 1),
+    TILED_AX("f16_d256x256w8a3_nt", DT_F16, 256, 256, 128, 2, 4, 2, 1),
 };
 constexpr int NUM_VARIANTS = (int)(sizeof(g_variants) / sizeof(g_variants[0]));
 
@@ -143,7 +151,7 @@ constexpr int NUM_VARIANTS = (int)(sizeof(g_variants) / sizeof(g_variants[0]));
 static bool variant_selectable(int id)
 {
     const char *n = g_variants[id].name;
-    if (strstr(n, "k32s4") || strstr(n, "k32s5") || strstr(n, "r256x256") || strstr(n, "w4k32") || strstr(n, "w4_nt") && strstr(n, "d256x256")) return false;
+    if (strstr(n, "k32s4") || strstr(n, "k32s5") || strstr(n, "w8a3") || strstr(n, "r256x256") || strstr(n, "w4k32") || strstr(n, "w4_nt") && strstr(n, "d256x256")) return false;
     return true;
 }
 
@@ -199,6 +207,7 @@ static double tiled_cost(const Variant &v, const peak_gemm_desc_t &d, int split)
     else if (v.bm * v.bn >= 128 * 128) eff = 0.6;
     else eff = 0.3;
     if (!v.direct) eff *= 0.7;
+    if (v.dt == DT_F32 && v.ns == 3) eff *= 1.05;     // measured: the 3-stage fp32 ring is ahead of the 2-stage one
     const double fixed = 4.0e6;                     // launch + prologue + epilogue, same units
     return rounds * (tile_work / eff + fixed) + (split > 1 ? 2.0e6 : 0.0);
 }

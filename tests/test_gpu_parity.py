@@ -23,10 +23,10 @@ def gu():
     return gpu_util
 
 
-def _stored(seed, dtype, M, N, K, transA, transB, pad=(0, 0, 0), ints=False, dist="uniform", scale=1.0):
+def _stored(seed, dtype, M, N, K, transA, transB, pad=(0, 0, 0), ints=False, dist="uniform", scale=1.0, amp=2):
     if ints:
-        la = pi.small_int_matrix(seed, 0, M, K, -2, 2, dtype)
-        lb = pi.small_int_matrix(seed, 1, K, N, -2, 2, dtype)
+        la = pi.small_int_matrix(seed, 0, M, K, -amp, amp, dtype)
+        lb = pi.small_int_matrix(seed, 1, K, N, -amp, amp, dtype)
         lc = pi.small_int_matrix(seed, 2, M, N, -3, 3, dtype)
     else:
         la = pi.logical_matrix(seed, 0, M, K, dist, scale, dtype)
@@ -55,7 +55,10 @@ def test_exact_integers_every_variant(gu, oracle, dtype, transA, transB):
         direct = "_d" in name or "skinny" in name
         # K <= 64 keeps |sum| <= 4*64 = 256
         if "skinny" in name:
-            shapes = [(16, 192, 128), (7, 130, 256), (1, 64, 128)]
+            import re
+            m = re.search(r"k(\d+)s", name)
+            ks = int(m.group(1)) if m else (64 if "skinnyreg" in name else 128)
+            shapes = [(16, 192, ks), (7, 130, 2 * ks), (1, 64, ks)]
         elif direct:
             bk = 32 if ("f32" in name or "k32" in name) else 64
             shapes = [(256, 256, bk), (300, 500, 2 * bk if 2 * bk <= 64 else bk), (100, 72, bk)]
@@ -64,7 +67,8 @@ def test_exact_integers_every_variant(gu, oracle, dtype, transA, transB):
         for case, (M, N, K) in enumerate(shapes):
             for alpha, beta in [(1.0, 0.0), (-1.0, 2.0)]:
                 pad = (0, 0, 0) if direct else (case % 2 * 3, case % 2 * 5, case % 2 * 7)
-                A, B, C = _stored(1000 + vid * 10 + case, dtype, M, N, K, transA, transB, pad, ints=True)
+                A, B, C = _stored(1000 + vid * 10 + case, dtype, M, N, K, transA, transB, pad, ints=True,
+                                  amp=1 if K > 256 else 2)
                 if direct:
                     # aligned leading dimensions for the direct kernels
                     al = 16 // pi.DTYPE_SIZE[dtype]
@@ -90,7 +94,7 @@ def test_random_every_direct_variant_deep_k(gu, oracle, dtype):
         for vid, name in gu.variants_for(dtype, transA, transB):
             if not ("_d" in name or "skinny" in name):
                 continue
-            M, N, K = ((13, 1000, 2048) if "skinny" in name else (300, 520, 1024))
+            M, N, K = ((13, 1000, 4096) if "skinny" in name else (300, 520, 1024))
             A, B, C = _stored(6000 + vid, dtype, M, N, K, transA, transB)
             ref = oracle.gemm(dtype, transA, transB, M, N, K, 1.0, A, B, 0.25, C)
             for split in (None, 3):
