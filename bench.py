@@ -27,9 +27,12 @@ if ROOT not in sys.path:
 PEAK_TFLOPS = {"bf16": 2500.0, "f16": 2500.0, "f32": 157.3}
 PEAK_HBM_GBS = 8000.0
 
-# HBM bytes per launch measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE (see
-# profiles/), scaled by a copy kernel of known size; None where not measured.
-MEASURED_TRAFFIC = {}
+# Bytes per launch that cross the L2 <-> memory boundary, from rocprofv3 --pmc
+# FETCH_SIZE and WRITE_SIZE (profiles/*_summary.md), each scaled by what the same
+# counter reads for a plain 1 GiB device copy (FETCH_SIZE reads half the bytes:
+# factor 2.0; WRITE_SIZE factor 1.0).  Summed over the kernels of one launch.
+# None where not measured.
+MEASURED_TRAFFIC = {"C3": 2.218e9, "C5": 5.525e8, "C2": 8.41e8, "C4": 8.71e8}
 
 
 def log(*a):

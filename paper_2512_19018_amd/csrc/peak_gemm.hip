@@ -207,7 +207,7 @@ static double tiled_cost(const Variant &v, const peak_gemm_desc_t &d, int split)
     else if (v.bm * v.bn >= 128 * 128) eff = 0.6;
     else eff = 0.3;
     if (!v.direct) eff *= 0.7;
-    if (v.dt == DT_F32 && v.ns == 3) eff *= 1.05;     // measured: the 3-stage fp32 ring is ahead of the 2-stage one
+    if (v.dt == DT_F32 && v.ns == 3 && v.bm == 256) eff *= 1.05;     // measured: the 3-stage fp32 ring is ahead of the 2-stage one
     const double fixed = 4.0e6;                     // launch + prologue + epilogue, same units
     return rounds * (tile_work / eff + fixed) + (split > 1 ? 2.0e6 : 0.0);
 }
