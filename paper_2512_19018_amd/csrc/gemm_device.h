@@ -34,7 +34,8 @@ enum {
     GF_A_VEC = 1,      // A base and row stride are 16-byte aligned
     GF_B_VEC = 2,      // B likewise
     GF_C_VEC = 4,      // C rows allow 4-element vector access
-    GF_WS_VEC = 8      // workspace rows (N floats) allow 16-byte access
+    GF_WS_VEC = 8,     // workspace rows (N floats) allow 16-byte access
+    GF_C_VEC16 = 16    // C base and row stride are 16-byte aligned
 };
 
 struct GemmArgs {
@@ -133,7 +134,8 @@ struct Cfg {
     // another full stage of both (asymmetric ring, all-direct two-phase loop only).
     static constexpr int NSA = NS_ + AX_, NSB = NS_;
     static constexpr int LDS_BYTES = A_BYTES * NSA + B_BYTES * NSB;
-    static constexpr bool PIPE = NS_ >= 3 && AX_ == 0;   // run-ahead main loop (see gemm_kernel)
+    static constexpr bool PIPE = NS_ >= 4 && AX_ == 0;   // run-ahead main loop (see gemm_kernel); with 3 stages the
+                                                         // two-phase loop keeps loads two steps ahead instead
     static_assert(AX_ == 0 || (NS_ == 2 && DIRECT_ && !A_T_ && !B_T_), "extra A stages: two-phase, both operands direct");
     static_assert(WTM % 32 == 0 && WTN % 32 == 0, "wave tile is a grid of 32x32 MFMA blocks");
     static_assert(RB_ == 128 || RB_ == 64, "tile row is 64 or 128 bytes");
@@ -609,14 +611,14 @@ __global__ __launch_bounds__(C::NT) void gemm_kernel(const GemmArgs p)
             }
         }
     } else {
-        // Run-ahead scheme (NS >= 3): at the barrier of step j tiles <= j+1 are
+        // Run-ahead scheme (NS >= 4): at the barrier of step j tiles <= j+1 are
         // complete, so the fragments of the next tile's first k-group are fetched
         // before that barrier and the MFMA stream never waits on LDS behind it.
         //   step j:  registers <- tile j+2 ; direct loads of tile j+NS-1 -> stage (j-1) % NS ;
         //            per k-group: fetch the next fragments, then MFMAs on the current ones ;
         //            registers -> stage (j+2) % NS ; wait for own direct loads of tile j+2 ; barrier
-        static_assert(!C::PIPE || (C::NS >= 3 && C::KG % 2 == 0), "run-ahead needs 3 stages and an even number of k-groups");
-        constexpr int PN = C::PIPE ? C::NS : 3;
+        static_assert(!C::PIPE || (C::NS >= 4 && C::KG % 2 == 0), "run-ahead needs 4 stages and an even number of k-groups");
+        constexpr int PN = C::PIPE ? C::NS : 4;
         if (DLOADS > 0) {
 #pragma unroll
             for (int s = 0; s < PN - 1; ++s) issue_direct_all(s, s);
@@ -690,6 +692,67 @@ __global__ __launch_bounds__(C::NT) void gemm_kernel(const GemmArgs p)
     const bool c_vec = p.flags & GF_C_VEC, ws_vec = p.flags & GF_WS_VEC;
     float *wsl = p.split > 1 ? p.ws + (int64_t)slice * p.M * p.N : nullptr;
     const bool interior = m0 + C::BM <= p.M && n0 + C::BN <= p.N;      // whole tile inside C: no masks
+    // Interior tiles with 16-byte aligned C rows: each wave turns its 32-row slabs
+    // around in LDS (fp32, padded rows) so that a store instruction writes whole
+    // row segments of the wave tile (16 bytes per lane, WTN elements per row)
+    // instead of 32 scattered 8-byte pieces.
+    constexpr int SROW = C::WTN * 4 + 16;                              // scratch row stride, bytes
+    constexpr bool STAGED_OK = 32 * SROW * C::NW <= C::LDS_BYTES;
+    if (STAGED_OK && interior && !wsl && (p.flags & GF_C_VEC16)) {
+        lds_barrier();                                                 // nobody still reads the last stage
+        char *scr = lds + wave * (32 * SROW);
+        constexpr int OUT_ROW = C::WTN * C::ESZ;                       // bytes of one output row of the wave tile
+        constexpr int LPR = OUT_ROW / 16;                              // lanes per row on the way out
+        constexpr int RPI = 64 / LPR;                                  // rows per store instruction
+        static_assert(OUT_ROW % 16 == 0 && 64 % LPR == 0 && 32 % RPI == 0, "wave tile rows split into 16-byte pieces");
+        const int orow = lane / LPR, ocol = (lane % LPR) * (16 / C::ESZ);   // row within the group, first column (elements)
+#pragma unroll
+        for (int mi = 0; mi < C::MI; ++mi) {
+#pragma unroll
+            for (int ni = 0; ni < C::NI; ++ni)
+#pragma unroll
+                for (int vq = 0; vq < 4; ++vq) {
+                    f32x4 v = {p.alpha * acc[mi][ni][vq * 4 + 0], p.alpha * acc[mi][ni][vq * 4 + 1],
+                               p.alpha * acc[mi][ni][vq * 4 + 2], p.alpha * acc[mi][ni][vq * 4 + 3]};
+                    *(f32x4 *)(scr + r32 * SROW + (ni * 32 + vq * 8 + half * 4) * 4) = v;
+                }
+            asm volatile("" ::: "memory");
+#pragma unroll
+            for (int g = 0; g < 32 / RPI; ++g) {
+                const int row = g * RPI + orow;
+                const int64_t m = m0 + wm * C::WTM + mi * 32 + row;
+                const int64_t n = n0 + wn * C::WTN + ocol;
+                const char *src = scr + row * SROW + ocol * 4;
+                if (C::DT == DT_F32) {
+                    f32x4 o = *(const f32x4 *)src;
+                    float *dst = (float *)p.C + m * p.ldc + n;
+                    if (p.beta != 0.0f) {
+                        const f32x4 c = *(const f32x4 *)dst;
+                        o[0] += p.beta * c[0]; o[1] += p.beta * c[1]; o[2] += p.beta * c[2]; o[3] += p.beta * c[3];
+                    }
+                    *(f32x4 *)dst = o;
+                } else {
+                    const f32x4 lo = *(const f32x4 *)src, hi = *(const f32x4 *)(src + 16);
+                    float o[8] = {lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
+                    uint16_t *dst = (uint16_t *)p.C + m * p.ldc + n;
+                    union { u32x4 u; _Float16 h[8]; __bf16 b[8]; } pk;
+                    if (p.beta != 0.0f) {
+                        pk.u = *(const u32x4 *)dst;
+#pragma unroll
+                        for (int e = 0; e < 8; ++e) o[e] += p.beta * (C::DT == DT_F16 ? (float)pk.h[e] : (float)pk.b[e]);
+                    }
+#pragma unroll
+                    for (int e = 0; e < 8; ++e) {
+                        if (C::DT == DT_F16) pk.h[e] = (_Float16)o[e];
+                        else pk.b[e] = (__bf16)o[e];
+                    }
+                    *(u32x4 *)dst = pk.u;
+                }
+            }
+            asm volatile("" ::: "memory");
+        }
+        return;
+    }
     if (interior && !wsl && c_vec) {
 #pragma unroll
         for (int mi = 0; mi < C::MI; ++mi) {

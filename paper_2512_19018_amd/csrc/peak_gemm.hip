@@ -386,6 +386,7 @@ peak_status_t peak_gemm_run(peak_gemm_plan_t *p, float alpha, const void *A, con
     a.alpha = alpha; a.beta = beta;
     a.split = 1;
     if ((uintptr_t)C % (4 * es) == 0 && (d.ldc * es) % (4 * es) == 0) a.flags |= GF_C_VEC;
+    if ((uintptr_t)C % 16 == 0 && (d.ldc * es) % 16 == 0) a.flags |= GF_C_VEC16;
 
     const bool no_product = (d.K == 0 || alpha == 0.0f);
     if (no_product) {
