@@ -109,7 +109,7 @@ PEAK_DEV int swz(int r)
 }
 
 template <int DT_, int BM_, int BN_, int RB_, int WAVES_M_, int WAVES_N_, int NS_,
-          bool A_T_, bool B_T_, bool DIRECT_, int AX_ = 0>
+          bool A_T_, bool B_T_, bool DIRECT_, int AX_ = 0, bool TR_ = false>
 struct Cfg {
     static constexpr int DT = DT_;
     static constexpr int ESZ = DT_ == DT_F32 ? 4 : 2;
@@ -127,6 +127,10 @@ struct Cfg {
     static constexpr bool A_T = A_T_;                 // A stored K rows x M (does not run along K)
     static constexpr bool B_T = B_T_;                 // B stored K rows x N (does not run along K)
     static constexpr bool DIRECT = DIRECT_;           // K-running operands go global -> LDS directly
+    // 16-bit B stored K x N: copied global -> LDS directly as [k][n] rows and read
+    // back with the transposing LDS read (ds_read_b64_tr_b16), no register staging
+    static constexpr bool B_TR = TR_;
+    static_assert(!TR_ || (DIRECT_ && B_T_ && !A_T_ && DT_ != DT_F32 && RB_ == 128), "transposing reads: 16-bit, B stored K x N, direct");
     static constexpr int A_BYTES = BM_ * RB_;
     static constexpr int B_BYTES = BN_ * RB_;
     // LDS: NSA stages of the A tile, then NSB stages of the B tile.  AX extra A
@@ -320,6 +324,56 @@ struct LoaderDirect {
     }
 };
 
+// Direct global -> LDS copy of a 16-bit B stored K x N (rows run along N).  The
+// LDS tile keeps that orientation: BK rows of BN elements.  16-byte chunk c of
+// row k sits at chunk position c ^ (2 * (k & 3)), which makes the transposing
+// fragment reads (4 k-rows x 32 bytes per 16 lanes) conflict-free.  Columns past
+// N read the start of the next row (or zero past the end of the matrix: the
+// descriptor ends there); they only feed columns of C that are never stored.
+template <class C>
+struct LoaderDirectKN {
+    static constexpr int ROWB = C::BN * C::ESZ;                   // bytes per k-row of the tile
+    static constexpr int CPRN = ROWB / 16;
+    static constexpr int RPI = 1024 / ROWB;                       // k-rows per wave instruction
+    static constexpr int NINST = C::BK / RPI;
+    static constexpr int PER_WAVE = (NINST + C::NW - 1) / C::NW;
+    static_assert(1024 % ROWB == 0 && C::BK % RPI == 0, "whole rows per instruction");
+    __amdgpu_buffer_rsrc_t rsrc;
+    int voff[PER_WAVE];
+    int step_bytes;                                               // BK rows of the stored matrix
+
+    PEAK_DEVM void init(const void *base, int64_t ld, int64_t n0, int64_t N, int64_t k0, int64_t K, int wave, int lane)
+    {
+        const uint64_t panel = (uint64_t)((const char *)base + (k0 * ld + n0) * C::ESZ);
+        const int64_t bytes = ((K - k0 - 1) * ld + (N - n0)) * C::ESZ;       // < 2^31, checked when the plan is made
+        const uint64_t panel_u = ((uint64_t)(uint32_t)__builtin_amdgcn_readfirstlane((int)(panel >> 32)) << 32) |
+                                 (uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)panel);
+        rsrc = __builtin_amdgcn_make_buffer_rsrc((void *)panel_u, 0, __builtin_amdgcn_readfirstlane((int)bytes), 0x00020000);
+        step_bytes = __builtin_amdgcn_readfirstlane((int)(C::BK * ld * C::ESZ));
+#pragma unroll
+        for (int i = 0; i < PER_WAVE; ++i) {
+            const int j = wave + C::NW * i;
+            const int row = j * RPI + lane / CPRN;
+            const int pos = lane % CPRN;
+            const int c = pos ^ (2 * (row & 3));
+            voff[i] = (int)((row * ld + (int64_t)c * C::EPC) * C::ESZ);
+        }
+    }
+
+    template <int PART, int NPARTS>
+    PEAK_DEVM void issue(char *lds_tile, int ktile, int wave) const
+    {
+#pragma unroll
+        for (int i = 0; i < PER_WAVE; ++i) {
+            const int j = wave + C::NW * i;
+            if (i % NPARTS == PART && (NINST % C::NW == 0 || j < NINST)) {
+                __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc, (__attribute__((address_space(3))) void *)(lds_tile + j * 1024),
+                                                         16, voff[i], ktile * step_bytes, 0, 0);
+            }
+        }
+    }
+};
+
 // ---------------------------------------------------------------------------
 // MFMA on one 16-byte fragment pair.  The roles are swapped on purpose: the B
 // tile's rows (n) feed the instruction's row operand and the A tile's rows (m)
@@ -467,26 +521,48 @@ __global__ __launch_bounds__(C::NT) void gemm_kernel(const GemmArgs p)
     for (int ni = 0; ni < C::NI; ++ni) {
         const int r = wn * C::WTN + ni * 32 + r32;
         b_addr[ni] = r * C::RB + ((half ^ swz<C::CPR>(r)) << 4);
+        if (C::B_TR) {
+            // transposing read: the 16 lanes of a group cover 4 k-rows x 16 n; lane i of the group
+            // points at k-row i/4, columns 4*(i%4) .. +3 of its group's 16
+            const int i16 = lane & 15, g16 = (lane & 31) >> 4;
+            const int krow = half * 8 + (i16 >> 2);
+            const int ncol = wn * C::WTN + ni * 32 + 16 * g16 + 4 * (i16 & 3);
+            b_addr[ni] = krow * (C::BN * C::ESZ) + (((ncol >> 3) ^ (2 * (krow & 3))) << 4) + (i16 & 1) * 8;
+        }
     }
+    // fragment of B for k-group kg: 8 k per lane
+    auto read_b = [&](const char *stb, int ni, int kg) -> u32x4 {
+        if (C::B_TR) {
+            typedef short s16x4 __attribute__((ext_vector_type(4)));
+            const char *q0 = stb + b_addr[ni] + (16 * kg) * (C::BN * C::ESZ);
+            const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4 *)q0);
+            const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4 *)(q0 + 4 * (C::BN * C::ESZ)));
+            const u32x2 l2 = __builtin_bit_cast(u32x2, lo), h2 = __builtin_bit_cast(u32x2, hi);
+            return u32x4{l2[0], l2[1], h2[0], h2[1]};
+        }
+        return *(const u32x4 *)(stb + (b_addr[ni] ^ (kg << 5)));
+    };
 
     // operand loaders
-    constexpr bool A_DIRECT = C::DIRECT && !C::A_T, B_DIRECT = C::DIRECT && !C::B_T;
+    constexpr bool A_DIRECT = C::DIRECT && !C::A_T, B_DIRECT = C::DIRECT && (!C::B_T || C::B_TR);
     LoaderDirect<C, C::BM> dA;
     LoaderDirect<C, C::BN> dB;
+    LoaderDirectKN<C> nB;
     LoaderK<C, C::BM> kA;
     LoaderK<C, C::BN> kB;
     LoaderT<C, C::BM> tA;
     LoaderT<C, C::BN> tB;
     // loads per thread and tile that stay in flight across iterations
     constexpr int LA = A_DIRECT ? LoaderDirect<C, C::BM>::PER_WAVE : 0;
-    constexpr int LB = B_DIRECT ? LoaderDirect<C, C::BN>::PER_WAVE : 0;
+    constexpr int LB = !B_DIRECT ? 0 : (C::B_TR ? LoaderDirectKN<C>::PER_WAVE : LoaderDirect<C, C::BN>::PER_WAVE);
     constexpr int DLOADS = LA + LB;
     constexpr int P = C::NS - 1;                            // prefetch distance of the direct loads
     static_assert(!A_DIRECT || LoaderDirect<C, C::BM>::NINST % C::NW == 0, "every wave issues the same number of loads");
-    static_assert(!B_DIRECT || LoaderDirect<C, C::BN>::NINST % C::NW == 0, "every wave issues the same number of loads");
+    static_assert(!B_DIRECT || (C::B_TR ? LoaderDirectKN<C>::NINST : LoaderDirect<C, C::BN>::NINST) % C::NW == 0, "every wave issues the same number of loads");
 
     if (A_DIRECT) dA.init(p.A, p.lda, m0, p.M, kbase, p.K, wave, lane);
-    if (B_DIRECT) dB.init(p.B, p.ldb, n0, p.N, kbase, p.K, wave, lane);
+    if (B_DIRECT && !C::B_TR) dB.init(p.B, p.ldb, n0, p.N, kbase, p.K, wave, lane);
+    if (B_DIRECT && C::B_TR) nB.init(p.B, p.ldb, n0, p.N, kbase, p.K, wave, lane);
 
     auto a_stage = [&](int s) { return lds + s * C::A_BYTES; };
     auto b_stage = [&](int s) { return lds + C::NSA * C::A_BYTES + s * C::B_BYTES; };
@@ -528,7 +604,8 @@ __global__ __launch_bounds__(C::NT) void gemm_kernel(const GemmArgs p)
     };
     auto issue_b = [&](int kt, int sb, auto part, auto nparts) {
         constexpr int PART = decltype(part)::value, NPARTS = decltype(nparts)::value;
-        if (B_DIRECT) dB.template issue<PART, NPARTS>(b_stage(sb), rotated(kt < KT ? kt : KT - 1), wave);
+        if (B_DIRECT && !C::B_TR) dB.template issue<PART, NPARTS>(b_stage(sb), rotated(kt < KT ? kt : KT - 1), wave);
+        if (B_DIRECT && C::B_TR) nB.template issue<PART, NPARTS>(b_stage(sb), rotated(kt < KT ? kt : KT - 1), wave);
     };
     auto issue_direct_all = [&](int kt, int stage) {
         issue_a(kt, stage, IC<0>{}, IC<1>{});
@@ -537,10 +614,25 @@ __global__ __launch_bounds__(C::NT) void gemm_kernel(const GemmArgs p)
     auto mfma_half = [&](const u32x4 *af, const u32x4 *bf, auto half_c) {
         constexpr int H = decltype(half_c)::value;
         constexpr int MH = C::MI > 1 ? C::MI / 2 : 1;
+        constexpr int M_LO = C::MI > 1 ? H * MH : 0, M_HI = C::MI > 1 ? (H + 1) * MH : (H == 0 ? 1 : 0);
+        if (C::DT == DT_F32) {
+            // k step outermost: consecutive MFMAs go to different accumulators instead of
+            // four in a row waiting on the same one
 #pragma unroll
-        for (int mi = (C::MI > 1 ? H * MH : 0); mi < (C::MI > 1 ? (H + 1) * MH : (H == 0 ? 1 : 0)); ++mi)
+            for (int st = 0; st < 4; ++st)
 #pragma unroll
-            for (int ni = 0; ni < C::NI; ++ni) mfma_frag<C::DT>(acc[mi][ni], bf[ni], af[mi]);
+                for (int mi = M_LO; mi < M_HI; ++mi)
+#pragma unroll
+                    for (int ni = 0; ni < C::NI; ++ni) {
+                        const f32x4 bq = __builtin_bit_cast(f32x4, bf[ni]), aq = __builtin_bit_cast(f32x4, af[mi]);
+                        acc[mi][ni] = __builtin_amdgcn_mfma_f32_32x32x2f32(bq[st], aq[st], acc[mi][ni], 0, 0, 0);
+                    }
+        } else {
+#pragma unroll
+            for (int mi = M_LO; mi < M_HI; ++mi)
+#pragma unroll
+                for (int ni = 0; ni < C::NI; ++ni) mfma_frag<C::DT>(acc[mi][ni], bf[ni], af[mi]);
+        }
     };
     // two-phase step: all k-groups of one stage
     auto compute = [&](int sa, int sb) {
@@ -551,7 +643,7 @@ __global__ __launch_bounds__(C::NT) void gemm_kernel(const GemmArgs p)
 #pragma unroll
             for (int mi = 0; mi < C::MI; ++mi) af[mi] = *(const u32x4 *)(sta + (a_addr[mi] ^ (kg << 5)));
 #pragma unroll
-            for (int ni = 0; ni < C::NI; ++ni) bf[ni] = *(const u32x4 *)(stb + (b_addr[ni] ^ (kg << 5)));
+            for (int ni = 0; ni < C::NI; ++ni) bf[ni] = read_b(stb, ni, kg);
             mfma_half(af, bf, IC<0>{});
             mfma_half(af, bf, IC<1>{});
         }
@@ -637,7 +729,7 @@ __global__ __launch_bounds__(C::NT) void gemm_kernel(const GemmArgs p)
             const char *sta = a_stage(stage), *stb = b_stage(stage);
 #pragma unroll
             for (int i = 0; i < (C::MI > C::NI ? C::MI : C::NI); ++i) {
-                if (i < C::NI) bf[set][i] = *(const u32x4 *)(stb + (b_addr[i] ^ (kg << 5)));
+                if (i < C::NI) bf[set][i] = read_b(stb, i, kg);
                 if (i < C::MI) af[set][i] = *(const u32x4 *)(sta + (a_addr[i] ^ (kg << 5)));
             }
         };
@@ -667,7 +759,7 @@ __global__ __launch_bounds__(C::NT) void gemm_kernel(const GemmArgs p)
                         // other wave of the SIMD is in the same phase (or there is no other wave);
                         // spread out, they issue in the shadow of the MFMA before them.
                         constexpr int NMFMA = C::MI * C::NI * (C::DT == DT_F32 ? 4 : 1);
-                        constexpr int NDS = C::MI + C::NI;
+                        constexpr int NDS = C::MI + C::NI * (C::B_TR ? 2 : 1);
                         constexpr int NVM = (LA + C::KG - 1 - kg) / C::KG + (LB + C::KG - 1 - kg) / C::KG;
                         constexpr int PER = C::DT == DT_F32 ? 4 : 1;       // MFMAs per slot
                         static_for<NMFMA / PER>([&](auto ic) {

@@ -52,7 +52,7 @@ def test_exact_integers_every_variant(gu, oracle, dtype, transA, transB):
     fragment layout, the swizzle, the transposing stores and the edge masks of
     every kernel variant built for the layout."""
     for vid, name in gu.variants_for(dtype, transA, transB):
-        direct = "_d" in name or "skinny" in name
+        direct = "_d" in name or "_t2" in name or "skinny" in name
         # K <= 64 keeps |sum| <= 4*64 = 256
         if "skinny" in name:
             import re
@@ -92,7 +92,7 @@ def test_random_every_direct_variant_deep_k(gu, oracle, dtype):
     their staging rings several times, ragged M and N."""
     for transA, transB in LAYOUTS:
         for vid, name in gu.variants_for(dtype, transA, transB):
-            if not ("_d" in name or "skinny" in name):
+            if not ("_d" in name or "_t2" in name or "skinny" in name):
                 continue
             M, N, K = ((13, 1000, 4096) if "skinny" in name else (300, 520, 1024))
             A, B, C = _stored(6000 + vid, dtype, M, N, K, transA, transB)
