@@ -127,10 +127,12 @@ struct Cfg {
     static constexpr bool A_T = A_T_;                 // A stored K rows x M (does not run along K)
     static constexpr bool B_T = B_T_;                 // B stored K rows x N (does not run along K)
     static constexpr bool DIRECT = DIRECT_;           // K-running operands go global -> LDS directly
-    // 16-bit B stored K x N: copied global -> LDS directly as [k][n] rows and read
-    // back with the transposing LDS read (ds_read_b64_tr_b16), no register staging
+    // B stored K x N: copied global -> LDS directly as [k][n] rows, no register
+    // staging.  16-bit fragments come back through the transposing LDS read
+    // (ds_read_b64_tr_b16); fp32 needs no transposition at all (one float per lane
+    // and MFMA, 32 lanes along a row)
     static constexpr bool B_TR = TR_;
-    static_assert(!TR_ || (DIRECT_ && B_T_ && !A_T_ && DT_ != DT_F32 && RB_ == 128), "transposing reads: 16-bit, B stored K x N, direct");
+    static_assert(!TR_ || (DIRECT_ && B_T_ && !A_T_ && RB_ == 128), "B kept as [k][n] rows in LDS: B stored K x N, direct");
     static constexpr int A_BYTES = BM_ * RB_;
     static constexpr int B_BYTES = BN_ * RB_;
     // LDS: NSA stages of the A tile, then NSB stages of the B tile.  AX extra A
@@ -355,7 +357,7 @@ struct LoaderDirectKN {
             const int j = wave + C::NW * i;
             const int row = j * RPI + lane / CPRN;
             const int pos = lane % CPRN;
-            const int c = pos ^ (2 * (row & 3));
+            const int c = C::DT == DT_F32 ? pos : pos ^ (2 * (row & 3));     // fp32 reads are row-wise: no swizzle
             voff[i] = (int)((row * ld + (int64_t)c * C::EPC) * C::ESZ);
         }
     }
@@ -521,7 +523,10 @@ __global__ __launch_bounds__(C::NT) void gemm_kernel(const GemmArgs p)
     for (int ni = 0; ni < C::NI; ++ni) {
         const int r = wn * C::WTN + ni * 32 + r32;
         b_addr[ni] = r * C::RB + ((half ^ swz<C::CPR>(r)) << 4);
-        if (C::B_TR) {
+        if (C::B_TR && C::DT == DT_F32) {
+            // [k][n] rows of floats: lane reads row 8*kg + 4*half + step, column n
+            b_addr[ni] = (4 * half) * (C::BN * 4) + r * 4;
+        } else if (C::B_TR) {
             // transposing read: the 16 lanes of a group cover 4 k-rows x 16 n; lane i of the group
             // points at k-row i/4, columns 4*(i%4) .. +3 of its group's 16
             const int i16 = lane & 15, g16 = (lane & 31) >> 4;
@@ -532,6 +537,11 @@ __global__ __launch_bounds__(C::NT) void gemm_kernel(const GemmArgs p)
     }
     // fragment of B for k-group kg: 8 k per lane
     auto read_b = [&](const char *stb, int ni, int kg) -> u32x4 {
+        if (C::B_TR && C::DT == DT_F32) {
+            const char *q0 = stb + b_addr[ni] + (8 * kg) * (C::BN * 4);
+            return u32x4{*(const uint32_t *)q0, *(const uint32_t *)(q0 + C::BN * 4), *(const uint32_t *)(q0 + 2 * C::BN * 4),
+                         *(const uint32_t *)(q0 + 3 * C::BN * 4)};
+        }
         if (C::B_TR) {
             typedef short s16x4 __attribute__((ext_vector_type(4)));
             const char *q0 = stb + b_addr[ni] + (16 * kg) * (C::BN * C::ESZ);
@@ -759,7 +769,7 @@ __global__ __launch_bounds__(C::NT) void gemm_kernel(const GemmArgs p)
                         // other wave of the SIMD is in the same phase (or there is no other wave);
                         // spread out, they issue in the shadow of the MFMA before them.
                         constexpr int NMFMA = C::MI * C::NI * (C::DT == DT_F32 ? 4 : 1);
-                        constexpr int NDS = C::MI + C::NI * (C::B_TR ? 2 : 1);
+                        constexpr int NDS = C::MI + C::NI * (!C::B_TR ? 1 : (C::DT == DT_F32 ? 4 : 2));
                         constexpr int NVM = (LA + C::KG - 1 - kg) / C::KG + (LB + C::KG - 1 - kg) / C::KG;
                         constexpr int PER = C::DT == DT_F32 ? 4 : 1;       // MFMAs per slot
                         static_for<NMFMA / PER>([&](auto ic) {

