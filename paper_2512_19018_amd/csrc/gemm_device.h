@@ -522,17 +522,19 @@ __global__ __launch_bounds__(C::NT) void gemm_kernel(const GemmArgs p)
 #pragma unroll
     for (int ni = 0; ni < C::NI; ++ni) {
         const int r = wn * C::WTN + ni * 32 + r32;
-        b_addr[ni] = r * C::RB + ((half ^ swz<C::CPR>(r)) << 4);
+        // (the B region's offset is part of the address, so that the stage offset left over
+        // for the read instruction fits its 16-bit immediate field)
+        b_addr[ni] = C::NSA * C::A_BYTES + r * C::RB + ((half ^ swz<C::CPR>(r)) << 4);
         if (C::B_TR && C::DT == DT_F32) {
             // [k][n] rows of floats: lane reads row 8*kg + 4*half + step, column n
-            b_addr[ni] = (4 * half) * (C::BN * 4) + r * 4;
+            b_addr[ni] = C::NSA * C::A_BYTES + (4 * half) * (C::BN * 4) + r * 4;
         } else if (C::B_TR) {
             // transposing read: the 16 lanes of a group cover 4 k-rows x 16 n; lane i of the group
             // points at k-row i/4, columns 4*(i%4) .. +3 of its group's 16
             const int i16 = lane & 15, g16 = (lane & 31) >> 4;
             const int krow = half * 8 + (i16 >> 2);
             const int ncol = wn * C::WTN + ni * 32 + 16 * g16 + 4 * (i16 & 3);
-            b_addr[ni] = krow * (C::BN * C::ESZ) + (((ncol >> 3) ^ (2 * (krow & 3))) << 4) + (i16 & 1) * 8;
+            b_addr[ni] = C::NSA * C::A_BYTES + krow * (C::BN * C::ESZ) + (((ncol >> 3) ^ (2 * (krow & 3))) << 4) + (i16 & 1) * 8;
         }
     }
     // fragment of B for k-group kg: 8 k per lane
@@ -575,7 +577,8 @@ __global__ __launch_bounds__(C::NT) void gemm_kernel(const GemmArgs p)
     if (B_DIRECT && C::B_TR) nB.init(p.B, p.ldb, n0, p.N, kbase, p.K, wave, lane);
 
     auto a_stage = [&](int s) { return lds + s * C::A_BYTES; };
-    auto b_stage = [&](int s) { return lds + C::NSA * C::A_BYTES + s * C::B_BYTES; };
+    auto b_stage = [&](int s) { return lds + C::NSA * C::A_BYTES + s * C::B_BYTES; };   // for the loaders
+    auto b_frag_base = [&](int s) { return lds + s * C::B_BYTES; };                     // for read_b (b_addr holds the rest)
 
     // K rotation: this workgroup walks its K tiles starting at tile `rot` and
     // wraps around.  Workgroups that share an A or B panel in one XCD's L2 start
@@ -646,7 +649,7 @@ __global__ __launch_bounds__(C::NT) void gemm_kernel(const GemmArgs p)
     };
     // two-phase step: all k-groups of one stage
     auto compute = [&](int sa, int sb) {
-        const char *sta = a_stage(sa), *stb = b_stage(sb);
+        const char *sta = a_stage(sa), *stb = b_frag_base(sb);
 #pragma unroll
         for (int kg = 0; kg < C::KG; ++kg) {
             u32x4 af[C::MI], bf[C::NI];
@@ -656,6 +659,7 @@ __global__ __launch_bounds__(C::NT) void gemm_kernel(const GemmArgs p)
             for (int ni = 0; ni < C::NI; ++ni) bf[ni] = read_b(stb, ni, kg);
             mfma_half(af, bf, IC<0>{});
             mfma_half(af, bf, IC<1>{});
+            __builtin_amdgcn_sched_barrier(0);          // one k-group's fragments live at a time
         }
     };
 
@@ -736,7 +740,7 @@ __global__ __launch_bounds__(C::NT) void gemm_kernel(const GemmArgs p)
         u32x4 af[2][C::MI], bf[2][C::NI];
         auto fetch = [&](int stage, int kg, int set) {
             // in the order the MFMAs of the next k-group consume them
-            const char *sta = a_stage(stage), *stb = b_stage(stage);
+            const char *sta = a_stage(stage), *stb = b_frag_base(stage);
 #pragma unroll
             for (int i = 0; i < (C::MI > C::NI ? C::MI : C::NI); ++i) {
                 if (i < C::NI) bf[set][i] = read_b(stb, i, kg);
