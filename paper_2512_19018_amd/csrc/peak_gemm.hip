@@ -161,6 +161,11 @@ static const Variant g_variants[] = {
     TILED_TR("f32_t256x128w8_nn", DT_F32, 256, 128, 128, 4, 2, 2),
     TILED_TR("f32_t256x128w4_nn", DT_F32, 256, 128, 128, 2, 2, 2),
     TILED_TR("f32_t128x64w4_nn", DT_F32, 128, 64, 128, 2, 2, 2),
+    // 75..: more streaming shapes
+    SKINNY("bf16_skinny64k512s2_nt", DT_BF16, 64, 512, 2),
+    SKINNY("bf16_skinny16k512s3_nt", DT_BF16, 16, 512, 3),
+    SKINNY("bf16_skinny32k512s2_nt", DT_BF16, 32, 512, 2),
+    SKINNY("f16_skinny64k512s2_nt", DT_F16, 64, 512, 2),
 };
 constexpr int NUM_VARIANTS = (int)(sizeof(g_variants) / sizeof(g_variants[0]));
 
@@ -355,7 +360,7 @@ peak_status_t peak_gemm_create(const peak_gemm_desc_t *desc, peak_gemm_plan_t **
             if (v.kind != KIND_TILED) {
                 // a streaming kernel wins whenever it applies: long row runs through LDS first,
                 // the register-streaming one for K that is not a multiple of 512
-                const bool preferred = strstr(v.name, "skinny32k512s3") != nullptr;
+                const bool preferred = strstr(v.name, "skinny64k512s2") != nullptr;
                 const bool second = v.kind == KIND_SKINNY_REG && strstr(v.name, "_d8_") != nullptr;
                 if (preferred) { pick = i; break; }
                 if (second && skinny_pick < 0) skinny_pick = i;

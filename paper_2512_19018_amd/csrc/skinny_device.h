@@ -41,12 +41,13 @@ struct SkinnyCfg {
 // within the aligned group of 16 chunks c belongs to)
 PEAK_DEV int skinny_pos(int r, int c) { return c ^ (r & 15); }
 
-// Number of K slices: about 4 workgroups per CU over the run, at least 4 stages each.
+// Number of K slices: one workgroup per CU is enough once it streams (measured:
+// splitting further only adds the reduction pass), at least 4 stages each.
 static inline int skinny_split(int64_t N, int64_t K, int bn, int kstep)
 {
     const int64_t tiles_n = (N + bn - 1) / bn;
     const int64_t ktiles = (K + kstep - 1) / kstep;
-    int64_t s = (1024 + tiles_n - 1) / tiles_n;
+    int64_t s = (256 + tiles_n - 1) / tiles_n;
     if (s > ktiles / 4) s = ktiles / 4;
     if (s < 1) s = 1;
     if (s > 64) s = 64;
