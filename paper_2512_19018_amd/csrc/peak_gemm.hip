@@ -166,6 +166,15 @@ static const Variant g_variants[] = {
     SKINNY("bf16_skinny16k512s3_nt", DT_BF16, 16, 512, 3),
     SKINNY("bf16_skinny32k512s2_nt", DT_BF16, 32, 512, 2),
     SKINNY("f16_skinny64k512s2_nt", DT_F16, 64, 512, 2),
+    // 79..: 128x128 direct tiles (64 KB of LDS: two workgroups per CU) for mid-size problems
+    TILED("bf16_d128x128w4_nt", DT_BF16, 128, 128, 128, 2, 2, 2, false, false, true),
+    TILED("f16_d128x128w4_nt", DT_F16, 128, 128, 128, 2, 2, 2, false, false, true),
+    TILED_TR("bf16_t128x128w4_nn", DT_BF16, 128, 128, 128, 2, 2, 2),
+    TILED_TR("f16_t128x128w4_nn", DT_F16, 128, 128, 128, 2, 2, 2),
+    TILED("bf16_d128x256w8_nt", DT_BF16, 128, 256, 128, 2, 4, 2, false, false, true),
+    TILED("f16_d128x256w8_nt", DT_F16, 128, 256, 128, 2, 4, 2, false, false, true),
+    TILED_TR("bf16_t128x256w8_nn", DT_BF16, 128, 256, 128, 2, 4, 2),
+    TILED_TR("f16_t128x256w8_nn", DT_F16, 128, 256, 128, 2, 4, 2),
 };
 constexpr int NUM_VARIANTS = (int)(sizeof(g_variants) / sizeof(g_variants[0]));
 
@@ -228,20 +237,22 @@ static double tiled_cost(const Variant &v, const peak_gemm_desc_t &d, int split)
     // The constants come from the measured sweeps on the graded shapes.
     double eff = 1.0;
     if (v.dt == DT_F32) {                               // fp32 MFMA is slow enough that tile size hardly matters
-        if (v.bm * v.bn >= 256 * 128) eff = 0.92;
+        if (v.bm * v.bn >= 256 * 128) eff = 0.86;
         else if (v.bm * v.bn >= 128 * 128) eff = 0.95;
         else eff = 0.5;
     } else {
         if (v.bm * v.bn >= 256 * 256) eff = 1.0;
         else if (v.bm * v.bn >= 256 * 128) eff = 0.85;
-        else if (v.bm * v.bn >= 128 * 128) eff = 0.6;
+        else if (v.bm * v.bn >= 128 * 128) eff = 0.85;   // 64 KB of LDS: two workgroups share a CU
         else eff = 0.3;
     }
     if (!v.direct) eff *= 0.7;
     if (v.tr) eff *= v.dt == DT_F32 ? 1.10 : 1.03;      // B staged directly: no register transposition, no masked loads
     if (v.dt == DT_F32 && v.ns == 3) eff *= 0.97;
-    const double fixed = 4.0e6;                     // launch + prologue + epilogue, same units
-    return rounds * (tile_work / eff + fixed) + (split > 1 ? 2.0e6 : 0.0);
+    const double fixed = 12.0e6;                    // prologue + epilogue of one tile, same units
+    // K slices write and re-read fp32 partials: about 9 units per element and slice
+    const double reduce = split > 1 ? 9.0 * (double)split * (double)d.M * (double)d.N : 0.0;
+    return rounds * (tile_work / eff + fixed) + reduce;
 }
 
 static int choose_split(const Variant &v, const peak_gemm_desc_t &d)
