@@ -282,14 +282,20 @@ struct LoaderT {
 // the swizzled layout comes out.  The buffer descriptor covers exactly this
 // workgroup's panel, so a lane can never touch memory outside the operand; the
 // step along K goes into the scalar offset.
+// A per-lane offset no descriptor of ours reaches (panels stay below 2^31 bytes):
+// a buffer load with it is out of range and delivers zeros.
+constexpr int OOB_VOFFSET = 0x7FFFFF00;
+
 template <class C, int ROWS>
 struct LoaderDirect {
     static constexpr int NINST = ROWS * C::CPR / 64;              // wave instructions per tile
     static constexpr int PER_WAVE = (NINST + C::NW - 1) / C::NW;
     __amdgpu_buffer_rsrc_t rsrc;
     int voff[PER_WAVE];                                           // this lane's byte offset in the panel, per instruction
+    int tailmask;                                                 // bit i: instruction i's chunk lies past K in the last K tile
 
-    PEAK_DEVM void init(const void *base, int64_t ld, int64_t row0, int64_t nrows, int64_t k0, int64_t K, int wave, int lane)
+    // tail_k: number of valid k in the matrix's last K tile (BK when K is a multiple of BK)
+    PEAK_DEVM void init(const void *base, int64_t ld, int64_t row0, int64_t nrows, int64_t k0, int64_t K, int tail_k, int wave, int lane)
     {
         int64_t rows_here = nrows - row0;                         // >= 1
         if (rows_here > ROWS) rows_here = ROWS;
@@ -299,6 +305,7 @@ struct LoaderDirect {
         const uint64_t panel_u = ((uint64_t)(uint32_t)__builtin_amdgcn_readfirstlane((int)(panel >> 32)) << 32) |
                                  (uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)panel);
         rsrc = __builtin_amdgcn_make_buffer_rsrc((void *)panel_u, 0, __builtin_amdgcn_readfirstlane((int)bytes), 0x00020000);
+        tailmask = 0;
 #pragma unroll
         for (int i = 0; i < PER_WAVE; ++i) {
             const int j = wave + C::NW * i;
@@ -307,20 +314,25 @@ struct LoaderDirect {
             const int c = pos ^ swz<C::CPR>(row);
             if (row > rows_here - 1) row = (int)rows_here - 1;    // duplicate of a valid row; its results are never stored
             voff[i] = (int)((row * ld + (int64_t)c * C::EPC) * C::ESZ);
+            if (c * C::EPC >= tail_k) tailmask |= 1 << i;
         }
     }
 
     // ktile: tile index relative to k0.  Issues this wave's instructions i with
     // i % NPARTS == PART, so that a tile's loads can be spread over a step.
+    // tail: this is the matrix's last K tile and K stops inside it; chunks past K
+    // are fetched with an offset beyond the descriptor's range, which stores zeros.
     template <int PART, int NPARTS>
-    PEAK_DEVM void issue(char *lds_tile, int ktile, int wave) const
+    PEAK_DEVM void issue(char *lds_tile, int ktile, bool tail, int wave) const
     {
+        const int bits = tail ? tailmask : 0;
 #pragma unroll
         for (int i = 0; i < PER_WAVE; ++i) {
             const int j = wave + C::NW * i;
             if (i % NPARTS == PART && (NINST % C::NW == 0 || j < NINST)) {
+                const int vo = (bits >> i) & 1 ? OOB_VOFFSET : voff[i];
                 __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc, (__attribute__((address_space(3))) void *)(lds_tile + j * 1024),
-                                                         16, voff[i], ktile * C::RB, 0, 0);
+                                                         16, vo, ktile * C::RB, 0, 0);
             }
         }
     }
@@ -329,9 +341,10 @@ struct LoaderDirect {
 // Direct global -> LDS copy of a 16-bit B stored K x N (rows run along N).  The
 // LDS tile keeps that orientation: BK rows of BN elements.  16-byte chunk c of
 // row k sits at chunk position c ^ (2 * (k & 3)), which makes the transposing
-// fragment reads (4 k-rows x 32 bytes per 16 lanes) conflict-free.  Columns past
-// N read the start of the next row (or zero past the end of the matrix: the
-// descriptor ends there); they only feed columns of C that are never stored.
+// fragment reads (4 k-rows x 32 bytes per 16 lanes) conflict-free.  N is a whole
+// number of chunks; a chunk that would start at or past column N fetches the
+// row's last valid chunk instead (it only feeds columns of C that are never
+// stored), so every access stays inside the matrix.
 template <class C>
 struct LoaderDirectKN {
     static constexpr int ROWB = C::BN * C::ESZ;                   // bytes per k-row of the tile
@@ -343,8 +356,9 @@ struct LoaderDirectKN {
     __amdgpu_buffer_rsrc_t rsrc;
     int voff[PER_WAVE];
     int step_bytes;                                               // BK rows of the stored matrix
+    int tailmask;                                                 // bit i: instruction i's k-row lies past K in the last K tile
 
-    PEAK_DEVM void init(const void *base, int64_t ld, int64_t n0, int64_t N, int64_t k0, int64_t K, int wave, int lane)
+    PEAK_DEVM void init(const void *base, int64_t ld, int64_t n0, int64_t N, int64_t k0, int64_t K, int tail_k, int wave, int lane)
     {
         const uint64_t panel = (uint64_t)((const char *)base + (k0 * ld + n0) * C::ESZ);
         const int64_t bytes = ((K - k0 - 1) * ld + (N - n0)) * C::ESZ;       // < 2^31, checked when the plan is made
@@ -352,25 +366,31 @@ struct LoaderDirectKN {
                                  (uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)panel);
         rsrc = __builtin_amdgcn_make_buffer_rsrc((void *)panel_u, 0, __builtin_amdgcn_readfirstlane((int)bytes), 0x00020000);
         step_bytes = __builtin_amdgcn_readfirstlane((int)(C::BK * ld * C::ESZ));
+        const int last_chunk = (int)((N - n0) / C::EPC) - 1;                  // >= 0: N and n0 are multiples of EPC
+        tailmask = 0;
 #pragma unroll
         for (int i = 0; i < PER_WAVE; ++i) {
             const int j = wave + C::NW * i;
             const int row = j * RPI + lane / CPRN;
             const int pos = lane % CPRN;
-            const int c = C::DT == DT_F32 ? pos : pos ^ (2 * (row & 3));     // fp32 reads are row-wise: no swizzle
+            int c = C::DT == DT_F32 ? pos : pos ^ (2 * (row & 3));           // fp32 reads are row-wise: no swizzle
+            if (c > last_chunk) c = last_chunk;
             voff[i] = (int)((row * ld + (int64_t)c * C::EPC) * C::ESZ);
+            if (row >= tail_k) tailmask |= 1 << i;
         }
     }
 
     template <int PART, int NPARTS>
-    PEAK_DEVM void issue(char *lds_tile, int ktile, int wave) const
+    PEAK_DEVM void issue(char *lds_tile, int ktile, bool tail, int wave) const
     {
+        const int bits = tail ? tailmask : 0;
 #pragma unroll
         for (int i = 0; i < PER_WAVE; ++i) {
             const int j = wave + C::NW * i;
             if (i % NPARTS == PART && (NINST % C::NW == 0 || j < NINST)) {
+                const int vo = (bits >> i) & 1 ? OOB_VOFFSET : voff[i];
                 __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc, (__attribute__((address_space(3))) void *)(lds_tile + j * 1024),
-                                                         16, voff[i], ktile * step_bytes, 0, 0);
+                                                         16, vo, ktile * step_bytes, 0, 0);
             }
         }
     }
@@ -572,9 +592,12 @@ __global__ __launch_bounds__(C::NT) void gemm_kernel(const GemmArgs p)
     static_assert(!A_DIRECT || LoaderDirect<C, C::BM>::NINST % C::NW == 0, "every wave issues the same number of loads");
     static_assert(!B_DIRECT || (C::B_TR ? LoaderDirectKN<C>::NINST : LoaderDirect<C, C::BN>::NINST) % C::NW == 0, "every wave issues the same number of loads");
 
-    if (A_DIRECT) dA.init(p.A, p.lda, m0, p.M, kbase, p.K, wave, lane);
-    if (B_DIRECT && !C::B_TR) dB.init(p.B, p.ldb, n0, p.N, kbase, p.K, wave, lane);
-    if (B_DIRECT && C::B_TR) nB.init(p.B, p.ldb, n0, p.N, kbase, p.K, wave, lane);
+    // valid k in the matrix's last K tile; only the slice that holds that tile can see a short one
+    const int tail_k = __builtin_amdgcn_readfirstlane((int)(p.K - (int64_t)(p.ktiles_total - 1) * C::BK));
+    const int tail_tile = tail_k < C::BK ? p.ktiles_total - 1 - kt_begin : -1;   // relative to the slice
+    if (A_DIRECT) dA.init(p.A, p.lda, m0, p.M, kbase, p.K, tail_k, wave, lane);
+    if (B_DIRECT && !C::B_TR) dB.init(p.B, p.ldb, n0, p.N, kbase, p.K, tail_k, wave, lane);
+    if (B_DIRECT && C::B_TR) nB.init(p.B, p.ldb, n0, p.N, kbase, p.K, tail_k, wave, lane);
 
     auto a_stage = [&](int s) { return lds + s * C::A_BYTES; };
     auto b_stage = [&](int s) { return lds + C::NSA * C::A_BYTES + s * C::B_BYTES; };   // for the loaders
@@ -613,12 +636,14 @@ __global__ __launch_bounds__(C::NT) void gemm_kernel(const GemmArgs p)
     // into a free stage, so the number of loads in flight stays what the waits assume.
     auto issue_a = [&](int kt, int sa, auto part, auto nparts) {
         constexpr int PART = decltype(part)::value, NPARTS = decltype(nparts)::value;
-        if (A_DIRECT) dA.template issue<PART, NPARTS>(a_stage(sa), rotated(kt < KT ? kt : KT - 1), wave);
+        const int kr = rotated(kt < KT ? kt : KT - 1);
+        if (A_DIRECT) dA.template issue<PART, NPARTS>(a_stage(sa), kr, kr == tail_tile, wave);
     };
     auto issue_b = [&](int kt, int sb, auto part, auto nparts) {
         constexpr int PART = decltype(part)::value, NPARTS = decltype(nparts)::value;
-        if (B_DIRECT && !C::B_TR) dB.template issue<PART, NPARTS>(b_stage(sb), rotated(kt < KT ? kt : KT - 1), wave);
-        if (B_DIRECT && C::B_TR) nB.template issue<PART, NPARTS>(b_stage(sb), rotated(kt < KT ? kt : KT - 1), wave);
+        const int kr = rotated(kt < KT ? kt : KT - 1);
+        if (B_DIRECT && !C::B_TR) dB.template issue<PART, NPARTS>(b_stage(sb), kr, kr == tail_tile, wave);
+        if (B_DIRECT && C::B_TR) nB.template issue<PART, NPARTS>(b_stage(sb), kr, kr == tail_tile, wave);
     };
     auto issue_direct_all = [&](int kt, int stage) {
         issue_a(kt, stage, IC<0>{}, IC<1>{});

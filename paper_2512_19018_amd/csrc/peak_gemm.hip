@@ -47,7 +47,7 @@ struct Variant {
     int kind;
     int dt;
     int a_t, b_t;        // operand layouts the kernel was built for (1: stored K rows x M/N)
-    int direct;          // needs 16-byte aligned operands and K % BK == 0
+    int direct;          // needs 16-byte aligned operand rows (tiled: K a whole number of 16-byte chunks; skinny: K % BK == 0)
     int bm, bn, bk, nt, ns, lds;
     int max_m;           // skinny kernels: largest M
     launch_fn launch;
@@ -212,7 +212,13 @@ static bool variant_fits(const Variant &v, const peak_gemm_desc_t &d)
     if (v.kind != KIND_TILED && d.M > v.max_m) return false;
     if (v.direct) {
         const int es = esize_of(d.dtype);
-        if (d.K % v.bk != 0 || d.K < v.bk) return false;
+        if (v.kind == KIND_TILED) {
+            // K may stop inside the last K tile, at a 16-byte chunk boundary
+            if ((d.K * es) % 16 != 0) return false;
+            if (v.tr && (d.N * es) % 16 != 0) return false;
+        } else if (d.K % v.bk != 0 || d.K < v.bk) {
+            return false;
+        }
         if ((d.lda * es) % 16 != 0 || (d.ldb * es) % 16 != 0) return false;
         // a workgroup's operand panel is addressed with 32-bit byte offsets
         const int64_t lim = (int64_t)1 << 31;

@@ -61,14 +61,17 @@ def test_exact_integers_every_variant(gu, oracle, dtype, transA, transB):
             shapes = [(16, 192, ks), (7, 130, 2 * ks), (1, 64, ks)]
         elif direct:
             bk = 32 if ("f32" in name or "k32" in name) else 64
-            shapes = [(256, 256, bk), (300, 500, 2 * bk if 2 * bk <= 64 else bk), (100, 72, bk)]
+            epc = 16 // pi.DTYPE_SIZE[dtype]
+            # the last two stop K inside a K tile, at a 16-byte chunk boundary
+            shapes = [(256, 256, bk), (300, 504, 2 * bk if 2 * bk <= 64 else bk), (100, 72, bk),
+                      (300, 504, bk + epc), (70, 40, bk - epc)]
         else:
             shapes = [(128, 128, 64), (200, 333, 40), (77, 5, 33), (1, 1, 1), (129, 257, 64)]
         for case, (M, N, K) in enumerate(shapes):
             for alpha, beta in [(1.0, 0.0), (-1.0, 2.0)]:
                 pad = (0, 0, 0) if direct else (case % 2 * 3, case % 2 * 5, case % 2 * 7)
                 A, B, C = _stored(1000 + vid * 10 + case, dtype, M, N, K, transA, transB, pad, ints=True,
-                                  amp=1 if K > 256 else 2)
+                                  amp=1 if K > 64 else 2)
                 if direct:
                     # aligned leading dimensions for the direct kernels
                     al = 16 // pi.DTYPE_SIZE[dtype]
@@ -94,14 +97,16 @@ def test_random_every_direct_variant_deep_k(gu, oracle, dtype):
         for vid, name in gu.variants_for(dtype, transA, transB):
             if not (re.search(r"_[dt]\d", name) or "skinny" in name):
                 continue
-            M, N, K = ((13, 1000, 4096) if "skinny" in name else (300, 520, 1024))
-            A, B, C = _stored(6000 + vid, dtype, M, N, K, transA, transB)
-            ref = oracle.gemm(dtype, transA, transB, M, N, K, 1.0, A, B, 0.25, C)
-            for split in (None, 3):
-                got, raw, info = gu.run_gemm(dtype, transA, transB, M, N, K, 1.0, 0.25, A, B, C,
-                                             flags=gu.pg.force_flags(variant=vid, split=split))
-                err = oracle.rel_frobenius(got, ref)
-                assert err <= gu.TOL[dtype], (info, err)
+            # tiled kernels also get a K that ends inside the last K tile (of the last K slice)
+            shapes = [(13, 1000, 4096)] if "skinny" in name else [(300, 520, 1024), (260, 264, 1000)]
+            for M, N, K in shapes:
+                A, B, C = _stored(6000 + vid, dtype, M, N, K, transA, transB)
+                ref = oracle.gemm(dtype, transA, transB, M, N, K, 1.0, A, B, 0.25, C)
+                for split in (None, 3):
+                    got, raw, info = gu.run_gemm(dtype, transA, transB, M, N, K, 1.0, 0.25, A, B, C,
+                                                 flags=gu.pg.force_flags(variant=vid, split=split))
+                    err = oracle.rel_frobenius(got, ref)
+                    assert err <= gu.TOL[dtype], (info, M, N, K, err)
 
 
 @pytest.mark.parametrize("dtype", DTYPES)

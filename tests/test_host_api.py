@@ -82,9 +82,20 @@ def test_forced_variant_must_fit():
     st, h = pg.peak_gemm_create(_desc(dtype=pg.PEAK_DT_F32, flags=pg.force_flags(variant=f32_nn)))
     assert st == pg.PEAK_OK and "f32_r128x128_nn" in pg.peak_gemm_plan_info(h)
     pg.peak_gemm_destroy(h)
-    # direct-to-LDS variants need K a multiple of their K tile and 16-byte aligned rows
+    # direct-to-LDS variants need K a whole number of 16-byte chunks and 16-byte aligned rows
     direct = names.index("bf16_d256x256w8_nt")
-    st, _ = pg.peak_gemm_create(_desc(512, 512, 1000, tB=1, flags=pg.force_flags(variant=direct)))
+    st, _ = pg.peak_gemm_create(_desc(512, 512, 1004, tB=1, lda=1008, ldb=1008, flags=pg.force_flags(variant=direct)))
+    assert st == pg.PEAK_ERR_UNSUPPORTED
+    st, h = pg.peak_gemm_create(_desc(512, 512, 1000, tB=1, flags=pg.force_flags(variant=direct)))
+    assert st == pg.PEAK_OK
+    pg.peak_gemm_destroy(h)
+    # the streaming kernels for M <= 16 take whole K steps only
+    skinny = names.index("bf16_skinny64k512s2_nt")
+    st, _ = pg.peak_gemm_create(_desc(16, 512, 1000, tB=1, flags=pg.force_flags(variant=skinny)))
+    assert st == pg.PEAK_ERR_UNSUPPORTED
+    # [k][n] staging of B needs N a whole number of chunks as well
+    tr = names.index("bf16_t256x256w8_nn")
+    st, _ = pg.peak_gemm_create(_desc(512, 500, 1024, ldb=504, flags=pg.force_flags(variant=tr)))
     assert st == pg.PEAK_ERR_UNSUPPORTED
     st, _ = pg.peak_gemm_create(_desc(512, 512, 1024, tB=1, lda=1028, flags=pg.force_flags(variant=direct)))
     assert st == pg.PEAK_ERR_UNSUPPORTED
