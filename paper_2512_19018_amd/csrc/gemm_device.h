@@ -109,7 +109,7 @@ PEAK_DEV int swz(int r)
 }
 
 template <int DT_, int BM_, int BN_, int RB_, int WAVES_M_, int WAVES_N_, int NS_,
-          bool A_T_, bool B_T_, bool DIRECT_, int AX_ = 0, bool TR_ = false>
+          bool A_T_, bool B_T_, bool DIRECT_, int AX_ = 0, bool TR_ = false, bool PP_ = false>
 struct Cfg {
     static constexpr int DT = DT_;
     static constexpr int ESZ = DT_ == DT_F32 ? 4 : 2;
@@ -140,8 +140,13 @@ struct Cfg {
     // another full stage of both (asymmetric ring, all-direct two-phase loop only).
     static constexpr int NSA = NS_ + AX_, NSB = NS_;
     static constexpr int LDS_BYTES = A_BYTES * NSA + B_BYTES * NSB;
-    static constexpr bool PIPE = NS_ >= 4 && AX_ == 0;   // run-ahead main loop (see gemm_kernel); with 3 stages the
+    static constexpr bool PIPE = NS_ >= 4 && AX_ == 0 && !PP_;   // run-ahead main loop (see gemm_kernel); with 3 stages the
                                                          // two-phase loop keeps loads two steps ahead instead
+    // Alternating main loop: the two waves of a SIMD take turns, one reading
+    // fragments and issuing loads while the other multiplies (see gemm_kernel)
+    static constexpr bool PP = PP_;
+    static_assert(!PP_ || (NS_ >= 2 && AX_ == 0 && DIRECT_ && !A_T_ && (!B_T_ || TR_) && WAVES_M_ * WAVES_N_ == 8),
+                  "alternating loop: 8 waves, both operands direct");
     static_assert(AX_ == 0 || (NS_ == 2 && DIRECT_ && !A_T_ && !B_T_), "extra A stages: two-phase, both operands direct");
     static_assert(WTM % 32 == 0 && WTN % 32 == 0, "wave tile is a grid of 32x32 MFMA blocks");
     static_assert(RB_ == 128 || RB_ == 64, "tile row is 64 or 128 bytes");
@@ -689,7 +694,82 @@ __global__ __launch_bounds__(C::NT) void gemm_kernel(const GemmArgs p)
     };
 
     constexpr bool ALL_DIRECT = A_DIRECT && B_DIRECT;
-    if (C::NSA != C::NSB) {
+#ifdef PEAK_NO_PREFETCH2
+    constexpr bool PREFETCH2 = false;
+#else
+    constexpr bool PREFETCH2 = ALL_DIRECT && C::NS == 2 && C::NSA == C::NSB && C::KG % 2 == 0 && !C::PP;
+#endif
+    if (C::PP) {
+        // Alternating scheme.  Waves w and w+4 share a SIMD.  A K tile is worked off two
+        // k-groups at a time; for each such part a wave first reads its fragments from
+        // LDS (and, in a tile's first part, issues its share of the loads of a later
+        // tile), then runs the part's MFMAs from registers.  The second group of four waves runs one
+        // phase behind the first, so on every SIMD one wave is multiplying while the
+        // other one is reading; a barrier ends every phase.
+        // With two parts per tile:
+        //   phase        4t      4t+1     4t+2     4t+3
+        //   waves 0-3  read t.0  mul t.0  read t.1  mul t.1
+        //   waves 4-7  mul t-1.1 read t.0 mul t.0   read t.1
+        // Tile t's stage is free once its last read phase (4t+3) has ended.
+        constexpr int HK = 2;                                       // k-groups per phase
+        constexpr int UPT = C::KG / HK;                             // phase pairs per K tile
+        const int grp = __builtin_amdgcn_readfirstlane(wave >> 2);
+        u32x4 af[HK][C::MI], bf[HK][C::NI];
+        auto fetch_half = [&](int stage, int h) {
+            const char *sta = a_stage(stage), *stb = b_frag_base(stage);
+#pragma unroll
+            for (int kk = 0; kk < HK; ++kk) {
+#pragma unroll
+                for (int ni = 0; ni < C::NI; ++ni) bf[kk][ni] = read_b(stb, ni, h * HK + kk);
+#pragma unroll
+                for (int mi = 0; mi < C::MI; ++mi) af[kk][mi] = *(const u32x4 *)(sta + (a_addr[mi] ^ ((h * HK + kk) << 5)));
+            }
+        };
+        auto multiply_half = [&]() {
+            __builtin_amdgcn_s_setprio(1);
+#pragma unroll
+            for (int kk = 0; kk < HK; ++kk) {
+                mfma_half(af[kk], bf[kk], IC<0>{});
+                mfma_half(af[kk], bf[kk], IC<1>{});
+            }
+            __builtin_amdgcn_s_setprio(0);
+        };
+        auto end_phase = [&]() {
+            __builtin_amdgcn_sched_barrier(0);
+            lds_barrier();
+            __builtin_amdgcn_sched_barrier(0);
+        };
+        // With NS stages the loads of tile t+NS-1 go out in the first read phase of
+        // tile t (its stage held tile t-1, whose last read phase has just ended), and
+        // before the barrier that precedes the first read of tile t+1 every wave has
+        // waited until at most NS-2 of its tiles are still in flight.  Past the end
+        // the last tile is fetched again, so that the count stays what the waits assume.
+        constexpr int INFLIGHT = (C::NS - 2) * DLOADS;
+#pragma unroll
+        for (int s = 0; s < C::NS - 1; ++s) issue_direct_all(s, s);
+        wait_vmcnt<INFLIGHT>();                                     // tile 0
+        lds_barrier();
+        if (grp == 1) end_phase();                                  // the second group starts one phase late
+        for (int kt0 = 0; kt0 < KT; kt0 += C::NS) {
+            static_for<C::NS>([&](auto sc) {
+                constexpr int s = decltype(sc)::value;
+                const int kt = kt0 + s;
+                if (kt < KT) {
+                    static_for<UPT>([&](auto hc) {
+                        constexpr int h = decltype(hc)::value;
+                        if (h == 0) issue_direct_all(kt + C::NS - 1, (s + C::NS - 1) % C::NS);
+                        fetch_half(s, h);
+                        if (h == UPT - 1 && grp == 1) wait_vmcnt<INFLIGHT>();
+                        end_phase();
+                        multiply_half();
+                        if (h == UPT - 1 && grp == 0) wait_vmcnt<INFLIGHT>();
+                        end_phase();
+                    });
+                }
+            });
+        }
+        if (grp == 0) end_phase();                                  // the first group finishes one phase early
+    } else if (C::NSA != C::NSB) {
         // Two-phase scheme with A running further ahead than B (all direct).  Per
         // step the order of issue is B(j+PB) then A(j+PA); at the barrier of step j
         // tile j of both operands must be complete.
@@ -712,6 +792,60 @@ __global__ __launch_bounds__(C::NT) void gemm_kernel(const GemmArgs p)
                     issue_b(j + PB, (u + PB) % C::NSB, IC<0>{}, IC<1>{});
                     issue_a(j + PA, (u + PA) % C::NSA, IC<0>{}, IC<1>{});
                     compute(u % C::NSA, u % C::NSB);
+                }
+            });
+        }
+    } else if (PREFETCH2) {
+        // Two stages, fragments one k-group ahead.  The barrier of a tile sits before
+        // its last k-group: by then every wave has read all of the tile (the last
+        // k-group's fragments were fetched one k-group earlier) and has waited for its
+        // own loads of the next tile.  So after it the tile's stage can be refilled
+        // (tile kt+2, a whole step before it is needed) and the next tile's first
+        // fragments can be fetched, and the MFMA stream never waits on LDS.
+        u32x4 af[2][C::MI], bf[2][C::NI];
+        auto fetch = [&](int stage, int kg, int set) {
+            const char *sta = a_stage(stage), *stb = b_frag_base(stage);
+#pragma unroll
+            for (int i = 0; i < (C::MI > C::NI ? C::MI : C::NI); ++i) {
+                if (i < C::NI) bf[set][i] = read_b(stb, i, kg);
+                if (i < C::MI) af[set][i] = *(const u32x4 *)(sta + (a_addr[i] ^ (kg << 5)));
+            }
+        };
+        issue_direct_all(0, 0);
+        wait_vmcnt<0>();
+        lds_barrier();
+        issue_direct_all(1, 1);
+        fetch(0, 0, 0);
+        for (int kt0 = 0; kt0 < KT; kt0 += 2) {
+            static_for<2>([&](auto sc) {
+                constexpr int s = decltype(sc)::value;
+                const int kt = kt0 + s;
+                if (kt < KT) {
+                    static_for<C::KG>([&](auto kgc) {
+                        constexpr int kg = decltype(kgc)::value;
+                        constexpr bool LAST = kg + 1 == C::KG;
+                        if constexpr (LAST) {
+                            wait_vmcnt<0>();                            // own loads of tile kt+1
+                            lds_barrier();                              // tile kt+1 complete, tile kt read
+                            issue_direct_all(kt + 2, s);
+                            fetch(1 - s, 0, 0);
+                        } else {
+                            fetch(s, kg + 1, (kg + 1) & 1);
+                        }
+                        mfma_half(af[kg & 1], bf[kg & 1], IC<0>{});
+                        mfma_half(af[kg & 1], bf[kg & 1], IC<1>{});
+                        constexpr int NMFMA = C::MI * C::NI * (C::DT == DT_F32 ? 4 : 1);
+                        constexpr int NDS = C::MI + C::NI * (!C::B_TR ? 1 : (C::DT == DT_F32 ? 4 : 2));
+                        constexpr int NVM = LAST ? DLOADS : 0;
+                        constexpr int PER = C::DT == DT_F32 ? 4 : 1;       // MFMAs per slot
+                        static_for<NMFMA / PER>([&](auto ic) {
+                            constexpr int i = decltype(ic)::value;
+                            __builtin_amdgcn_sched_group_barrier(0x008, PER, 0);
+                            if constexpr (i < NDS) __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+                            else if constexpr (i - NDS < NVM) __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);
+                        });
+                        __builtin_amdgcn_sched_barrier(0);
+                    });
                 }
             });
         }

@@ -69,6 +69,11 @@ struct Variant {
      Cfg<DT, BM, BN, RB, WMW, WNW, NS, false, true, true, 0, true>::LDS_BYTES, 0,                      \
      &launch_gemm<Cfg<DT, BM, BN, RB, WMW, WNW, NS, false, true, true, 0, true>>, 1}
 
+#define TILED_PP(NAME, DT, BM, BN, RB, WMW, WNW, NS, TR)                                              \
+    {NAME, KIND_TILED, DT, 0, TR, 1, BM, BN, RB / (DT == DT_F32 ? 4 : 2), WMW * WNW * 64, NS,          \
+     Cfg<DT, BM, BN, RB, WMW, WNW, NS, false, TR != 0, true, 0, TR != 0, true>::LDS_BYTES, 0,          \
+     &launch_gemm<Cfg<DT, BM, BN, RB, WMW, WNW, NS, false, TR != 0, true, 0, TR != 0, true>>, TR}
+
 #define TILED_LAYOUTS(NAME, DT, BM, BN, RB, WMW, WNW, NS)                                              \
     TILED(NAME "_nt", DT, BM, BN, RB, WMW, WNW, NS, false, false, false),                             \
     TILED(NAME "_nn", DT, BM, BN, RB, WMW, WNW, NS, false, true, false),                              \
@@ -175,6 +180,16 @@ static const Variant g_variants[] = {
     TILED("f16_d128x256w8_nt", DT_F16, 128, 256, 128, 2, 4, 2, false, false, true),
     TILED_TR("bf16_t128x256w8_nn", DT_BF16, 128, 256, 128, 2, 4, 2),
     TILED_TR("f16_t128x256w8_nn", DT_F16, 128, 256, 128, 2, 4, 2),
+    // 87..: 256x256, the two waves of a SIMD alternate between reading and multiplying
+    TILED_PP("bf16_p256x256w8_nt", DT_BF16, 256, 256, 128, 2, 4, 2, 0),
+    TILED_PP("f16_p256x256w8_nt", DT_F16, 256, 256, 128, 2, 4, 2, 0),
+    TILED_PP("bf16_pt256x256w8_nn", DT_BF16, 256, 256, 128, 2, 4, 2, 1),
+    TILED_PP("f16_pt256x256w8_nn", DT_F16, 256, 256, 128, 2, 4, 2, 1),
+    // 91..: the same with 32-deep K tiles in a ring of 5 or 4
+    TILED_PP("bf16_p256x256w8k32s5_nt", DT_BF16, 256, 256, 64, 2, 4, 5, 0),
+    TILED_PP("f16_p256x256w8k32s5_nt", DT_F16, 256, 256, 64, 2, 4, 5, 0),
+    TILED_PP("bf16_p256x256w8k32s4_nt", DT_BF16, 256, 256, 64, 2, 4, 4, 0),
+    TILED_PP("f16_p256x256w8k32s4_nt", DT_F16, 256, 256, 64, 2, 4, 4, 0),
 };
 constexpr int NUM_VARIANTS = (int)(sizeof(g_variants) / sizeof(g_variants[0]));
 
@@ -183,6 +198,7 @@ constexpr int NUM_VARIANTS = (int)(sizeof(g_variants) / sizeof(g_variants[0]));
 static bool variant_selectable(int id)
 {
     const char *n = g_variants[id].name;
+    if (strstr(n, "_p256") || strstr(n, "_pt256")) return false;
     if (strstr(n, "k32s4") || strstr(n, "k32s5") || strstr(n, "w8a3") || strstr(n, "r256x256") || strstr(n, "w4k32") || strstr(n, "w4_nt") && strstr(n, "d256x256")) return false;
     return true;
 }
