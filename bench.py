@@ -32,7 +32,7 @@ PEAK_HBM_GBS = 8000.0
 # counter reads for a plain 1 GiB device copy (FETCH_SIZE reads half the bytes:
 # factor 2.0; WRITE_SIZE factor 1.0).  Summed over the kernels of one launch.
 # None where not measured.
-MEASURED_TRAFFIC = {"C3": 2.218e9, "C5": 5.525e8, "C2": 8.41e8, "C4": 8.71e8}
+MEASURED_TRAFFIC = {"C3": 1.755e9, "C5": 5.424e8, "C2": 8.97e8, "C4": 7.33e8}
 
 
 def log(*a):
@@ -48,7 +48,7 @@ def main():
     ap.add_argument("--only", action="store_true", help="time only the headline workload")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU-oracle baseline leg")
     ap.add_argument("--no-torch", action="store_true", help="skip the torch.matmul context rows")
-    ap.add_argument("--variant", type=int, default=None, help="force a kernel variant id (sweeps)")
+    ap.add_argument("--variant", default=None, help="force a kernel variant, by id or name (sweeps)")
     ap.add_argument("--split", type=int, default=None, help="force a K split (sweeps)")
     ap.add_argument("--fast-inputs", action="store_true",
                     help="sweeps only: random device-generated inputs instead of the seeded host generator")
@@ -113,7 +113,12 @@ def main():
         dB = [dev(B) for _ in range(nset)]
         dC = [dev(C) for _ in range(nset)]
         lda, ldb, ldc = w.ld()
-        flags = pg.force_flags(variant, split)
+        if variant is not None and not str(variant).isdigit():
+            names = [pg.peak_gemm_variant_name(i) for i in range(pg.peak_gemm_variant_count())]
+            if variant not in names:
+                raise SystemExit("bench.py: no kernel variant named %r" % (variant,))
+            variant = names.index(variant)
+        flags = pg.force_flags(None if variant is None else int(variant), split)
         res = {"workload": name, "note": w.note, "dtype": pi.DTYPE_NAMES[w.dtype], "M": w.M, "N": w.N, "K": w.K,
                "transA": w.transA, "transB": w.transB, "alpha": w.alpha, "beta": w.beta, "buffer_sets": nset}
         with pg.Plan(w.M, w.N, w.K, w.dtype, w.transA, w.transB, lda, ldb, ldc, flags) as plan:

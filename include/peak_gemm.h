@@ -129,6 +129,24 @@ int peak_gemm_plan_info(const peak_gemm_plan_t *plan, char *buf, size_t n);
 int peak_gemm_variant_count(void);
 const char *peak_gemm_variant_name(int id);
 
+/* Selector table from an offline sweep (the exhaustive search over tuning
+ * parameters of the paper's Section 3.4, "performance evaluators": enumerate
+ * the valid parameter settings, time them, keep the best).
+ *
+ * `path` names a text file in host memory's file system, one entry per line:
+ *     <dtype f32|f16|bf16> <transA 0|1> <transB 0|1> <M> <N> <K> <variant name> <split>
+ * ('#' starts a comment; further columns are ignored).  After a successful
+ * load, peak_gemm_create() with no forced variant uses the entry whose first
+ * six columns equal the descriptor's, provided that variant fits the
+ * descriptor's leading dimensions and alignment; otherwise the built-in cost
+ * model decides as before.  The table replaces any table loaded earlier;
+ * path == NULL clears it.  Returns the number of entries now held, or -1 if
+ * the file cannot be read or a line is malformed or names an unknown variant
+ * (the previous table is then kept).  The file named by the environment
+ * variable PEAK_GEMM_TUNING, if set, is loaded at the first peak_gemm_create().
+ * Not thread-safe against concurrent peak_gemm_create() calls. */
+int peak_gemm_load_tuning(const char *path);
+
 #ifdef __cplusplus
 }
 #endif

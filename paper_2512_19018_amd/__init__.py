@@ -10,5 +10,5 @@ from .binding import (  # noqa: F401
     PeakGemmDesc, PeakError, lib_path, load_library,
     peak_gemm_create, peak_gemm_workspace_bytes, peak_gemm_run, peak_gemm_destroy,
     peak_status_string, peak_gemm_plan_info, peak_gemm_variant_count, peak_gemm_variant_name,
-    force_flags, Plan,
+    peak_gemm_load_tuning, force_flags, Plan,
 )

@@ -62,6 +62,8 @@ def load_library():
         lib.peak_gemm_variant_count.argtypes = []
         lib.peak_gemm_variant_name.restype = ctypes.c_char_p
         lib.peak_gemm_variant_name.argtypes = [ctypes.c_int]
+        lib.peak_gemm_load_tuning.restype = ctypes.c_int
+        lib.peak_gemm_load_tuning.argtypes = [ctypes.c_char_p]
         _LIB = lib
     return _LIB
 
@@ -77,6 +79,11 @@ def peak_gemm_variant_count() -> int:
 def peak_gemm_variant_name(i: int):
     s = load_library().peak_gemm_variant_name(int(i))
     return s.decode() if s is not None else None
+
+
+def peak_gemm_load_tuning(path) -> int:
+    """Load (or, with None, clear) the selector table; returns the number of entries, -1 on error."""
+    return load_library().peak_gemm_load_tuning(None if path is None else os.fsencode(path))
 
 
 def force_flags(variant: int | None = None, split: int | None = None) -> int:

@@ -506,6 +506,7 @@ PEAK_DEV void tile_of_block(int t, int tiles_m, int tiles_n, int group_m, int &t
 template <class C>
 __global__ __launch_bounds__(C::NT) void gemm_kernel(const GemmArgs p)
 {
+#if defined(__HIP_DEVICE_COMPILE__)   // the host pass only needs the kernel's symbol; the body uses device-only builtins
     __shared__ __attribute__((aligned(1024))) char lds[C::LDS_BYTES];
 
     const int tid = threadIdx.x;
@@ -1056,6 +1057,7 @@ __global__ __launch_bounds__(C::NT) void gemm_kernel(const GemmArgs p)
             }
         }
     }
+#endif
 }
 
 // ---------------------------------------------------------------------------

@@ -8,6 +8,7 @@
 #include <cstdlib>
 #include <cstring>
 #include <new>
+#include <vector>
 
 #include "gemm_device.h"
 #include "skinny_device.h"
@@ -92,104 +93,84 @@ struct Variant {
 // B as stored (t: N x K, runs along K; n: K x N).  So "_nt" is transA=0,
 // transB=1: both operands K-contiguous.
 static const Variant g_variants[] = {
-    // 0..11: register-staged 128x128 tiles, any alignment, any K
+    // register-staged tiles: any alignment, any K, all four layouts
     TILED_LAYOUTS("f32_r128x128", DT_F32, 128, 128, 128, 2, 2, 2),
     TILED_LAYOUTS("f16_r128x128", DT_F16, 128, 128, 128, 2, 2, 2),
     TILED_LAYOUTS("bf16_r128x128", DT_BF16, 128, 128, 128, 2, 2, 2),
-    // 12..23: register-staged 64x64 tiles for small problems
     TILED_LAYOUTS("f32_r64x64", DT_F32, 64, 64, 128, 2, 2, 2),
     TILED_LAYOUTS("f16_r64x64", DT_F16, 64, 64, 128, 2, 2, 2),
     TILED_LAYOUTS("bf16_r64x64", DT_BF16, 64, 64, 128, 2, 2, 2),
-    // 24..: direct-to-LDS 256x256 tiles, 8 waves
+
+    // 16-bit, both operands along K ("_nt"): direct-to-LDS, two 64-deep stages
     TILED("bf16_d256x256w8_nt", DT_BF16, 256, 256, 128, 2, 4, 2, false, false, true),
     TILED("f16_d256x256w8_nt", DT_F16, 256, 256, 128, 2, 4, 2, false, false, true),
-    TILED("bf16_d256x256w8_nn", DT_BF16, 256, 256, 128, 2, 4, 2, false, true, true),
-    TILED("f16_d256x256w8_nn", DT_F16, 256, 256, 128, 2, 4, 2, false, true, true),
-    // 28..: same tile, 64-byte rows, 4-deep ring
-    TILED("bf16_d256x256w8k32s4_nt", DT_BF16, 256, 256, 64, 2, 4, 4, false, false, true),
-    TILED("f16_d256x256w8k32s4_nt", DT_F16, 256, 256, 64, 2, 4, 4, false, false, true),
-    // 30..: 4 waves, 128x128 per wave
-    TILED("bf16_d256x256w4_nt", DT_BF16, 256, 256, 128, 2, 2, 2, false, false, true),
-    TILED("f16_d256x256w4_nt", DT_F16, 256, 256, 128, 2, 2, 2, false, false, true),
-    // 32..: fp32
-    TILED("f32_d128x128w4_nn", DT_F32, 128, 128, 128, 2, 2, 2, false, true, true),
-    TILED("f32_d128x128w4_nt", DT_F32, 128, 128, 128, 2, 2, 2, false, false, true),
-    TILED("f32_d256x128w8_nn", DT_F32, 256, 128, 128, 4, 2, 2, false, true, true),
-    // 35..: 256x128 16-bit tiles (more tiles for mid-size problems)
-    TILED("bf16_d256x128w8_nt", DT_BF16, 256, 128, 128, 4, 2, 3, false, false, true),
-    TILED("f16_d256x128w8_nt", DT_F16, 256, 128, 128, 4, 2, 3, false, false, true),
-    TILED("bf16_d256x128w8_nn", DT_BF16, 256, 128, 128, 4, 2, 3, false, true, true),
-    TILED("f16_d256x128w8_nn", DT_F16, 256, 128, 128, 4, 2, 3, false, true, true),
-    // 39..: skinny (M <= 16), both operands along K
-    SKINNY("bf16_skinny16s3_nt", DT_BF16, 64, 128, 3),
-    SKINNY("f16_skinny16s3_nt", DT_F16, 64, 128, 3),
-    SKINNY("bf16_skinny16s4_nt", DT_BF16, 64, 128, 4),
-    SKINNY("f16_skinny16s4_nt", DT_F16, 64, 128, 4),
-    // 43..: run-ahead ring for row-major B, and 3-stage fp32
-    TILED("bf16_d256x256w8k32s4_nn", DT_BF16, 256, 256, 64, 2, 4, 4, false, true, true),
-    TILED("f16_d256x256w8k32s4_nn", DT_F16, 256, 256, 64, 2, 4, 4, false, true, true),
-    TILED("f32_d256x128w8s3_nn", DT_F32, 256, 128, 128, 4, 2, 3, false, true, true),
-    TILED("f32_d128x128w4s3_nn", DT_F32, 128, 128, 128, 2, 2, 3, false, true, true),
-    TILED("f32_d128x128w4s3_nt", DT_F32, 128, 128, 128, 2, 2, 3, false, false, true),
-    // 48..: deepest ring that fits 160 KB
-    TILED("bf16_d256x256w8k32s5_nt", DT_BF16, 256, 256, 64, 2, 4, 5, false, false, true),
-    TILED("f16_d256x256w8k32s5_nt", DT_F16, 256, 256, 64, 2, 4, 5, false, false, true),
-    // 50..: one wave per SIMD, 128x128 per wave, run-ahead ring
-    TILED("bf16_d256x256w4k32s4_nt", DT_BF16, 256, 256, 64, 2, 2, 4, false, false, true),
-    TILED("f16_d256x256w4k32s4_nt", DT_F16, 256, 256, 64, 2, 2, 4, false, false, true),
-    // 52..: register-staged 256x256 (global -> VGPR -> LDS), for comparison with the direct path
-    TILED("bf16_r256x256w8_nt", DT_BF16, 256, 256, 128, 2, 4, 2, false, false, false),
-    TILED("bf16_r256x256w8s3k32_nt", DT_BF16, 256, 256, 64, 2, 4, 4, false, false, false),
-    // 54..: register-streaming skinny kernels (no LDS, no barriers)
-    SKINNY_REG("bf16_skinnyreg_d8_nt", DT_BF16, 8, 4),
-    SKINNY_REG("f16_skinnyreg_d8_nt", DT_F16, 8, 4),
-    SKINNY_REG("bf16_skinnyreg_d4_nt", DT_BF16, 4, 4),
-    SKINNY_REG("bf16_skinnyreg_d12_nt", DT_BF16, 12, 4),
-    // 58..: LDS-ring skinny kernels with longer contiguous runs per row
-    SKINNY("bf16_skinny32k512s3_nt", DT_BF16, 32, 512, 3),
-    SKINNY("bf16_skinny32k256s4_nt", DT_BF16, 32, 256, 4),
-    SKINNY("bf16_skinny64k256s3_nt", DT_BF16, 64, 256, 3),
-    SKINNY("bf16_skinny64k128s6_nt", DT_BF16, 64, 128, 6),
-    SKINNY("f16_skinny32k512s3_nt", DT_F16, 32, 512, 3),
-    // 63..: two B stages, three A stages (160 KB): A's loads run two steps ahead
-    TILED_AX("bf16_d256x256w8a3_nt", DT_BF16, 256, 256, 128, 2, 4, 2, 1),
-    TILED_AX("f16_d256x256w8a3_nt", DT_F16, 256, 256, 128, 2, 4, 2, 1),
-    // 65..: row-major B staged directly and read with transposing LDS reads
-    TILED_TR("bf16_t256x256w8_nn", DT_BF16, 256, 256, 128, 2, 4, 2),
-    TILED_TR("f16_t256x256w8_nn", DT_F16, 256, 256, 128, 2, 4, 2),
-    TILED_TR("bf16_t256x128w8_nn", DT_BF16, 256, 128, 128, 4, 2, 3),
-    TILED_TR("f16_t256x128w8_nn", DT_F16, 256, 128, 128, 4, 2, 3),
-    // 69..: fp32 with row-major B staged directly (no transposition needed)
-    TILED_TR("f32_t256x128w8s3_nn", DT_F32, 256, 128, 128, 4, 2, 3),
-    TILED_TR("f32_t128x128w4s3_nn", DT_F32, 128, 128, 128, 2, 2, 3),
-    TILED_TR("f32_t128x128w4_nn", DT_F32, 128, 128, 128, 2, 2, 2),
-    TILED_TR("f32_t256x128w8_nn", DT_F32, 256, 128, 128, 4, 2, 2),
-    TILED_TR("f32_t256x128w4_nn", DT_F32, 256, 128, 128, 2, 2, 2),
-    TILED_TR("f32_t128x64w4_nn", DT_F32, 128, 64, 128, 2, 2, 2),
-    // 75..: more streaming shapes
-    SKINNY("bf16_skinny64k512s2_nt", DT_BF16, 64, 512, 2),
-    SKINNY("bf16_skinny16k512s3_nt", DT_BF16, 16, 512, 3),
-    SKINNY("bf16_skinny32k512s2_nt", DT_BF16, 32, 512, 2),
-    SKINNY("f16_skinny64k512s2_nt", DT_F16, 64, 512, 2),
-    // 79..: 128x128 direct tiles (64 KB of LDS: two workgroups per CU) for mid-size problems
-    TILED("bf16_d128x128w4_nt", DT_BF16, 128, 128, 128, 2, 2, 2, false, false, true),
-    TILED("f16_d128x128w4_nt", DT_F16, 128, 128, 128, 2, 2, 2, false, false, true),
-    TILED_TR("bf16_t128x128w4_nn", DT_BF16, 128, 128, 128, 2, 2, 2),
-    TILED_TR("f16_t128x128w4_nn", DT_F16, 128, 128, 128, 2, 2, 2),
     TILED("bf16_d128x256w8_nt", DT_BF16, 128, 256, 128, 2, 4, 2, false, false, true),
     TILED("f16_d128x256w8_nt", DT_F16, 128, 256, 128, 2, 4, 2, false, false, true),
-    TILED_TR("bf16_t128x256w8_nn", DT_BF16, 128, 256, 128, 2, 4, 2),
-    TILED_TR("f16_t128x256w8_nn", DT_F16, 128, 256, 128, 2, 4, 2),
-    // 87..: 256x256, the two waves of a SIMD alternate between reading and multiplying
+    TILED("bf16_d128x128w4_nt", DT_BF16, 128, 128, 128, 2, 2, 2, false, false, true),
+    TILED("f16_d128x128w4_nt", DT_F16, 128, 128, 128, 2, 2, 2, false, false, true),
+    // three stages
+    TILED("bf16_d256x128w8_nt", DT_BF16, 256, 128, 128, 4, 2, 3, false, false, true),
+    TILED("f16_d256x128w8_nt", DT_F16, 256, 128, 128, 4, 2, 3, false, false, true),
+    // 32-deep K tiles in a ring of 4 or 5 with the run-ahead loop; 8 waves or 4 (one per SIMD)
+    TILED("bf16_d256x256w8k32s4_nt", DT_BF16, 256, 256, 64, 2, 4, 4, false, false, true),
+    TILED("f16_d256x256w8k32s4_nt", DT_F16, 256, 256, 64, 2, 4, 4, false, false, true),
+    TILED("bf16_d256x256w8k32s5_nt", DT_BF16, 256, 256, 64, 2, 4, 5, false, false, true),
+    TILED("f16_d256x256w8k32s5_nt", DT_F16, 256, 256, 64, 2, 4, 5, false, false, true),
+    TILED("bf16_d256x256w4k32s4_nt", DT_BF16, 256, 256, 64, 2, 2, 4, false, false, true),
+    TILED("f16_d256x256w4k32s4_nt", DT_F16, 256, 256, 64, 2, 2, 4, false, false, true),
+    // two B stages, three A stages (160 KB): A's loads run two steps ahead
+    TILED_AX("bf16_d256x256w8a3_nt", DT_BF16, 256, 256, 128, 2, 4, 2, 1),
+    TILED_AX("f16_d256x256w8a3_nt", DT_F16, 256, 256, 128, 2, 4, 2, 1),
+    // the two waves of a SIMD alternate between reading fragments and multiplying
     TILED_PP("bf16_p256x256w8_nt", DT_BF16, 256, 256, 128, 2, 4, 2, 0),
     TILED_PP("f16_p256x256w8_nt", DT_F16, 256, 256, 128, 2, 4, 2, 0),
+
+    // 16-bit, B stored K x N ("_nn"): A direct, B transposed through registers ...
+    TILED("bf16_d256x256w8_nn", DT_BF16, 256, 256, 128, 2, 4, 2, false, true, true),
+    TILED("f16_d256x256w8_nn", DT_F16, 256, 256, 128, 2, 4, 2, false, true, true),
+    TILED("bf16_d256x128w8_nn", DT_BF16, 256, 128, 128, 4, 2, 3, false, true, true),
+    TILED("f16_d256x128w8_nn", DT_F16, 256, 128, 128, 4, 2, 3, false, true, true),
+    TILED("bf16_d256x256w8k32s4_nn", DT_BF16, 256, 256, 64, 2, 4, 4, false, true, true),
+    TILED("f16_d256x256w8k32s4_nn", DT_F16, 256, 256, 64, 2, 4, 4, false, true, true),
+    // ... or B staged directly as [k][n] rows and read with transposing LDS reads
+    TILED_TR("bf16_t256x256w8_nn", DT_BF16, 256, 256, 128, 2, 4, 2),
+    TILED_TR("f16_t256x256w8_nn", DT_F16, 256, 256, 128, 2, 4, 2),
+    TILED_TR("bf16_t128x256w8_nn", DT_BF16, 128, 256, 128, 2, 4, 2),
+    TILED_TR("f16_t128x256w8_nn", DT_F16, 128, 256, 128, 2, 4, 2),
+    TILED_TR("bf16_t128x128w4_nn", DT_BF16, 128, 128, 128, 2, 2, 2),
+    TILED_TR("f16_t128x128w4_nn", DT_F16, 128, 128, 128, 2, 2, 2),
+    TILED_TR("bf16_t256x128w8_nn", DT_BF16, 256, 128, 128, 4, 2, 3),
+    TILED_TR("f16_t256x128w8_nn", DT_F16, 256, 128, 128, 4, 2, 3),
     TILED_PP("bf16_pt256x256w8_nn", DT_BF16, 256, 256, 128, 2, 4, 2, 1),
     TILED_PP("f16_pt256x256w8_nn", DT_F16, 256, 256, 128, 2, 4, 2, 1),
-    // 91..: the same with 32-deep K tiles in a ring of 5 or 4
-    TILED_PP("bf16_p256x256w8k32s5_nt", DT_BF16, 256, 256, 64, 2, 4, 5, 0),
-    TILED_PP("f16_p256x256w8k32s5_nt", DT_F16, 256, 256, 64, 2, 4, 5, 0),
-    TILED_PP("bf16_p256x256w8k32s4_nt", DT_BF16, 256, 256, 64, 2, 4, 4, 0),
-    TILED_PP("f16_p256x256w8k32s4_nt", DT_F16, 256, 256, 64, 2, 4, 4, 0),
+
+    // fp32: A direct; B through registers ("_d", either layout) or directly as [k][n] rows ("_t": no
+    // transposition needed, one float per lane and MFMA)
+    TILED("f32_d128x128w4_nt", DT_F32, 128, 128, 128, 2, 2, 2, false, false, true),
+    TILED("f32_d128x128w4s3_nt", DT_F32, 128, 128, 128, 2, 2, 3, false, false, true),
+    TILED("f32_d128x128w4_nn", DT_F32, 128, 128, 128, 2, 2, 2, false, true, true),
+    TILED("f32_d128x128w4s3_nn", DT_F32, 128, 128, 128, 2, 2, 3, false, true, true),
+    TILED("f32_d256x128w8_nn", DT_F32, 256, 128, 128, 4, 2, 2, false, true, true),
+    TILED("f32_d256x128w8s3_nn", DT_F32, 256, 128, 128, 4, 2, 3, false, true, true),
+    TILED_TR("f32_t128x128w4_nn", DT_F32, 128, 128, 128, 2, 2, 2),
+    TILED_TR("f32_t128x128w4s3_nn", DT_F32, 128, 128, 128, 2, 2, 3),
+    TILED_TR("f32_t256x128w8_nn", DT_F32, 256, 128, 128, 4, 2, 2),
+    TILED_TR("f32_t256x128w8s3_nn", DT_F32, 256, 128, 128, 4, 2, 3),
+    TILED_TR("f32_t256x128w4_nn", DT_F32, 256, 128, 128, 2, 2, 2),
+    TILED_TR("f32_t128x64w4_nn", DT_F32, 128, 64, 128, 2, 2, 2),
+
+    // M <= 16, both operands along K: B is streamed once.  LDS ring of BN rows x KSTEP ...
+    SKINNY("bf16_skinny16s3_nt", DT_BF16, 64, 128, 3),
+    SKINNY("f16_skinny16s3_nt", DT_F16, 64, 128, 3),
+    SKINNY("bf16_skinny32k512s3_nt", DT_BF16, 32, 512, 3),
+    SKINNY("f16_skinny32k512s3_nt", DT_F16, 32, 512, 3),
+    SKINNY("bf16_skinny64k256s3_nt", DT_BF16, 64, 256, 3),
+    SKINNY("f16_skinny64k256s3_nt", DT_F16, 64, 256, 3),
+    SKINNY("bf16_skinny64k512s2_nt", DT_BF16, 64, 512, 2),
+    SKINNY("f16_skinny64k512s2_nt", DT_F16, 64, 512, 2),
+    // ... or straight into registers (no LDS, no barriers)
+    SKINNY_REG("bf16_skinnyreg_d8_nt", DT_BF16, 8, 4),
+    SKINNY_REG("f16_skinnyreg_d8_nt", DT_F16, 8, 4),
 };
 constexpr int NUM_VARIANTS = (int)(sizeof(g_variants) / sizeof(g_variants[0]));
 
@@ -199,7 +180,7 @@ static bool variant_selectable(int id)
 {
     const char *n = g_variants[id].name;
     if (strstr(n, "_p256") || strstr(n, "_pt256")) return false;
-    if (strstr(n, "k32s4") || strstr(n, "k32s5") || strstr(n, "w8a3") || strstr(n, "r256x256") || strstr(n, "w4k32") || strstr(n, "w4_nt") && strstr(n, "d256x256")) return false;
+    if (strstr(n, "k32s4") || strstr(n, "k32s5") || strstr(n, "w8a3") || strstr(n, "w4k32")) return false;
     return true;
 }
 
@@ -320,7 +301,74 @@ static void plan_geometry(peak_gemm_plan *p, const Variant &v, int forced_split)
     p->ws_bytes = p->split > 1 ? (size_t)p->split * (size_t)d.M * (size_t)d.N * sizeof(float) : 0;
 }
 
+// Selector table from an offline sweep: exact shape -> variant and K split.
+struct TuneEntry {
+    int dt, ta, tb;
+    int64_t M, N, K;
+    int variant, split;
+};
+static std::vector<TuneEntry> g_tuning;
+static bool g_tuning_env_done = false;
+
+static int variant_by_name(const char *name)
+{
+    for (int i = 0; i < NUM_VARIANTS; ++i)
+        if (strcmp(g_variants[i].name, name) == 0) return i;
+    return -1;
+}
+
+static int load_tuning_file(const char *path)
+{
+    FILE *f = fopen(path, "r");
+    if (!f) return -1;
+    std::vector<TuneEntry> table;
+    char line[512];
+    bool ok = true;
+    while (ok && fgets(line, sizeof line, f)) {
+        char *hash = strchr(line, '#');
+        if (hash) *hash = 0;
+        char dt[16], name[128];
+        TuneEntry e;
+        long long M, N, K;
+        const int n = sscanf(line, "%15s %d %d %lld %lld %lld %127s %d", dt, &e.ta, &e.tb, &M, &N, &K, name, &e.split);
+        if (n <= 0) continue;                               // blank or comment line
+        e.dt = strcmp(dt, "f32") == 0 ? PEAK_DT_F32 : strcmp(dt, "f16") == 0 ? PEAK_DT_F16 : strcmp(dt, "bf16") == 0 ? PEAK_DT_BF16 : -1;
+        e.variant = n >= 7 ? variant_by_name(name) : -1;
+        e.M = M; e.N = N; e.K = K;
+        ok = n == 8 && e.dt >= 0 && e.variant >= 0 && (e.ta | 1) == 1 && (e.tb | 1) == 1 && M > 0 && N > 0 && K > 0 &&
+             e.split >= 1 && e.split <= 255 && g_variants[e.variant].dt == e.dt;
+        if (ok) table.push_back(e);
+    }
+    fclose(f);
+    if (!ok) return -1;
+    g_tuning.swap(table);
+    return (int)g_tuning.size();
+}
+
+static const TuneEntry *tuned(const peak_gemm_desc_t &d)
+{
+    if (!g_tuning_env_done) {
+        g_tuning_env_done = true;
+        if (const char *e = getenv("PEAK_GEMM_TUNING")) load_tuning_file(e);
+    }
+    for (const TuneEntry &e : g_tuning)
+        if (e.dt == (int)d.dtype && e.ta == d.transA && e.tb == d.transB && e.M == d.M && e.N == d.N && e.K == d.K &&
+            variant_fits(g_variants[e.variant], d))
+            return &e;
+    return nullptr;
+}
+
 extern "C" {
+
+int peak_gemm_load_tuning(const char *path)
+{
+    g_tuning_env_done = true;                               // an explicit call overrides the environment
+    if (!path) {
+        g_tuning.clear();
+        return 0;
+    }
+    return load_tuning_file(path);
+}
 
 const char *peak_status_string(peak_status_t s)
 {
@@ -378,12 +426,16 @@ peak_status_t peak_gemm_create(const peak_gemm_desc_t *desc, peak_gemm_plan_t **
     }
 
     int pick = -1;
+    int table_split = 0;
     if (forced >= 0) {
         if (forced >= NUM_VARIANTS || !variant_fits(g_variants[forced], d)) {
             delete p;
             return PEAK_ERR_UNSUPPORTED;
         }
         pick = forced;
+    } else if (const TuneEntry *t = tuned(d)) {
+        pick = t->variant;
+        table_split = t->split;
     } else {
         double best = 0.0;
         int skinny_pick = -1;
@@ -410,7 +462,7 @@ peak_status_t peak_gemm_create(const peak_gemm_desc_t *desc, peak_gemm_plan_t **
         }
     }
     p->variant = pick;
-    plan_geometry(p, g_variants[pick], forced_split);
+    plan_geometry(p, g_variants[pick], forced_split > 0 ? forced_split : table_split);
     const int64_t grid = (int64_t)p->tiles_m * p->tiles_n * p->split;
     if (grid > 0x7FFFFFFF) {
         delete p;

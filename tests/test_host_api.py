@@ -153,3 +153,58 @@ def test_missing_library_fails_loudly(monkeypatch, tmp_path):
         b.load_library()
     monkeypatch.undo()
     importlib.reload(b)
+
+
+def test_selector_table_overrides_the_cost_model(tmp_path):
+    """A table from an offline sweep decides for the shapes it lists, if the
+    variant fits; everything else goes through the cost model as before."""
+    try:
+        with pg.Plan(8192, 8192, 8192, pg.PEAK_DT_BF16, 0, 1) as p:
+            default = p.info()
+        assert "bf16_d256x256w8_nt" in default
+        table = tmp_path / "table.txt"
+        table.write_text("# comment\n"
+                         "bf16 0 1 8192 8192 8192 bf16_d256x128w8_nt 2   # 900.0 us\n"
+                         "\n"
+                         "f32 0 0 4096 4096 4096 f32_t256x128w8_nn 1\n")
+        assert pg.peak_gemm_load_tuning(str(table)) == 2
+        with pg.Plan(8192, 8192, 8192, pg.PEAK_DT_BF16, 0, 1) as p:
+            assert "bf16_d256x128w8_nt" in p.info() and "split=2" in p.info()
+        with pg.Plan(4096, 4096, 4096, pg.PEAK_DT_F32, 0, 0) as p:
+            assert "f32_t256x128w8_nn" in p.info()
+        # same shape, but rows not 16-byte aligned: the tabled variant does not fit, the cost model decides
+        with pg.Plan(8192, 8192, 8192, pg.PEAK_DT_BF16, 0, 1, lda=8193) as p:
+            assert "bf16_r128x128_nt" in p.info()
+        # another shape: untouched
+        with pg.Plan(4096, 4096, 4096, pg.PEAK_DT_BF16, 0, 1) as p:
+            assert "bf16_d256x256w8_nt" in p.info()
+        # forcing still wins over the table
+        names = [pg.peak_gemm_variant_name(i) for i in range(pg.peak_gemm_variant_count())]
+        with pg.Plan(8192, 8192, 8192, pg.PEAK_DT_BF16, 0, 1,
+                     flags=pg.force_flags(variant=names.index("bf16_d128x128w4_nt"))) as p:
+            assert "bf16_d128x128w4_nt" in p.info()
+        # a malformed file is refused and the table in force stays
+        bad = tmp_path / "bad.txt"
+        bad.write_text("bf16 0 1 8192 8192 8192 no_such_variant 1\n")
+        assert pg.peak_gemm_load_tuning(str(bad)) == -1
+        bad.write_text("bf16 0 1 8192 8192 8192 f32_t256x128w8_nn 1\n")      # dtype of the variant differs
+        assert pg.peak_gemm_load_tuning(str(bad)) == -1
+        assert pg.peak_gemm_load_tuning(str(tmp_path / "missing.txt")) == -1
+        with pg.Plan(8192, 8192, 8192, pg.PEAK_DT_BF16, 0, 1) as p:
+            assert "bf16_d256x128w8_nt" in p.info()
+    finally:
+        assert pg.peak_gemm_load_tuning(None) == 0
+    with pg.Plan(8192, 8192, 8192, pg.PEAK_DT_BF16, 0, 1) as p:
+        assert p.info() == default
+
+
+def test_tuner_enumerates_only_accepted_settings():
+    from paper_2512_19018_amd import tune
+    cands = tune.candidates(pg.PEAK_DT_BF16, 0, 1, 256, 512, 1024)
+    names = {c[1] for c in cands}
+    assert "bf16_d256x256w8_nt" in names and "bf16_r128x128_nt" in names
+    assert not any(n.startswith(("f16_", "f32_")) or n.endswith(("_nn", "_tt", "_tn")) for n in names)
+    assert not any("skinny" in n for n in names)                   # M > 16
+    assert len({(c[0], c[2]) for c in cands}) == len(cands)        # each (variant, effective split) once
+    line = tune.table_line(pg.PEAK_DT_BF16, 0, 1, 256, 512, 1024, "bf16_d256x256w8_nt", 4, 12.5)
+    assert line.split()[:8] == ["bf16", "0", "1", "256", "512", "1024", "bf16_d256x256w8_nt", "4"]
