@@ -345,8 +345,11 @@ struct LoaderDirect {
 
 // Direct global -> LDS copy of a 16-bit B stored K x N (rows run along N).  The
 // LDS tile keeps that orientation: BK rows of BN elements.  16-byte chunk c of
-// row k sits at chunk position c ^ (2 * (k & 3)), which makes the transposing
-// fragment reads (4 k-rows x 32 bytes per 16 lanes) conflict-free.  N is a whole
+// row k sits at chunk position c ^ (4 * (k & 3)): a transposing fragment read
+// takes 4 k-rows x 64 bytes per 32 lanes, the rows are a multiple of 256 bytes
+// apart, and the XOR moves each of the four rows to its own 64-byte group of
+// banks (measured: with 2 * (k & 3) a quarter of the LDS cycles were bank
+// conflicts, rows k and k+1 sharing a group).  N is a whole
 // number of chunks; a chunk that would start at or past column N fetches the
 // row's last valid chunk instead (it only feeds columns of C that are never
 // stored), so every access stays inside the matrix.
@@ -378,7 +381,7 @@ struct LoaderDirectKN {
             const int j = wave + C::NW * i;
             const int row = j * RPI + lane / CPRN;
             const int pos = lane % CPRN;
-            int c = C::DT == DT_F32 ? pos : pos ^ (2 * (row & 3));           // fp32 reads are row-wise: no swizzle
+            int c = C::DT == DT_F32 ? pos : pos ^ (4 * (row & 3));           // fp32 reads are row-wise: no swizzle
             if (c > last_chunk) c = last_chunk;
             voff[i] = (int)((row * ld + (int64_t)c * C::EPC) * C::ESZ);
             if (row >= tail_k) tailmask |= 1 << i;
@@ -560,7 +563,7 @@ __global__ __launch_bounds__(C::NT) void gemm_kernel(const GemmArgs p)
             const int i16 = lane & 15, g16 = (lane & 31) >> 4;
             const int krow = half * 8 + (i16 >> 2);
             const int ncol = wn * C::WTN + ni * 32 + 16 * g16 + 4 * (i16 & 3);
-            b_addr[ni] = C::NSA * C::A_BYTES + krow * (C::BN * C::ESZ) + (((ncol >> 3) ^ (2 * (krow & 3))) << 4) + (i16 & 1) * 8;
+            b_addr[ni] = C::NSA * C::A_BYTES + krow * (C::BN * C::ESZ) + (((ncol >> 3) ^ (4 * (krow & 3))) << 4) + (i16 & 1) * 8;
         }
     }
     // fragment of B for k-group kg: 8 k per lane
@@ -804,12 +807,44 @@ __global__ __launch_bounds__(C::NT) void gemm_kernel(const GemmArgs p)
         // (tile kt+2, a whole step before it is needed) and the next tile's first
         // fragments can be fetched, and the MFMA stream never waits on LDS.
         u32x4 af[2][C::MI], bf[2][C::NI];
+        // The compiler's wait-count pass puts s_waitcnt vmcnt(0) in front of every
+        // transposing LDS read that follows a direct-to-LDS load (it takes them to alias),
+        // which would expose the whole load latency once per tile.  So the transposing
+        // reads of this loop are issued as assembly, into the halves bl/bh, and their
+        // completion is waited for by hand: at the start of each k-group everything the
+        // wave has asked of LDS (the fragments fetched one k-group earlier) has arrived.
+        // In-order return of LDS data keeps the compiler's own lgkmcnt waits for the A
+        // fragments valid with the extra reads in between (they can only over-wait).
+        constexpr bool TR_ASM = C::B_TR && C::DT != DT_F32;
+        u32x2 bl[2][C::NI], bh[2][C::NI];
+        const uint32_t lds_b0 = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) char *)lds;
         auto fetch = [&](int stage, int kg, int set) {
             const char *sta = a_stage(stage), *stb = b_frag_base(stage);
 #pragma unroll
             for (int i = 0; i < (C::MI > C::NI ? C::MI : C::NI); ++i) {
-                if (i < C::NI) bf[set][i] = read_b(stb, i, kg);
+                if (i < C::NI) {
+                    if constexpr (TR_ASM) {
+                        const uint32_t a0 = lds_b0 + stage * C::B_BYTES + b_addr[i] + (16 * kg) * (C::BN * C::ESZ);
+                        asm volatile("ds_read_b64_tr_b16 %0, %1" : "=v"(bl[set][i]) : "v"(a0) : "memory");
+                        asm volatile("ds_read_b64_tr_b16 %0, %1 offset:%2" : "=v"(bh[set][i]) : "v"(a0), "n"(4 * C::BN * C::ESZ) : "memory");
+                    } else {
+                        bf[set][i] = read_b(stb, i, kg);
+                    }
+                }
                 if (i < C::MI) af[set][i] = *(const u32x4 *)(sta + (a_addr[i] ^ (kg << 5)));
+            }
+        };
+        // the B fragments of `set` have arrived (see above): hand them to the compiler
+        auto settle = [&](auto setc) {
+            constexpr int set = decltype(setc)::value;
+            if constexpr (TR_ASM) {
+                __builtin_amdgcn_s_waitcnt(waitcnt_imm(63, 0));
+#pragma unroll
+                for (int i = 0; i < C::NI; ++i) {
+                    asm volatile("" : "+v"(bl[set][i]), "+v"(bh[set][i]));
+                    bf[set][i] = u32x4{bl[set][i][0], bl[set][i][1], bh[set][i][0], bh[set][i][1]};
+                }
+                __builtin_amdgcn_sched_barrier(0);
             }
         };
         issue_direct_all(0, 0);
@@ -828,15 +863,17 @@ __global__ __launch_bounds__(C::NT) void gemm_kernel(const GemmArgs p)
                         if constexpr (LAST) {
                             wait_vmcnt<0>();                            // own loads of tile kt+1
                             lds_barrier();                              // tile kt+1 complete, tile kt read
+                            settle(IC<(kg & 1)>{});
                             issue_direct_all(kt + 2, s);
                             fetch(1 - s, 0, 0);
                         } else {
+                            settle(IC<(kg & 1)>{});
                             fetch(s, kg + 1, (kg + 1) & 1);
                         }
                         mfma_half(af[kg & 1], bf[kg & 1], IC<0>{});
                         mfma_half(af[kg & 1], bf[kg & 1], IC<1>{});
                         constexpr int NMFMA = C::MI * C::NI * (C::DT == DT_F32 ? 4 : 1);
-                        constexpr int NDS = C::MI + C::NI * (!C::B_TR ? 1 : (C::DT == DT_F32 ? 4 : 2));
+                        constexpr int NDS = C::MI + (TR_ASM ? 0 : C::NI * (!C::B_TR ? 1 : 4));
                         constexpr int NVM = LAST ? DLOADS : 0;
                         constexpr int PER = C::DT == DT_F32 ? 4 : 1;       // MFMAs per slot
                         static_for<NMFMA / PER>([&](auto ic) {
