@@ -52,6 +52,9 @@ def main():
     ap.add_argument("--split", type=int, default=None, help="force a K split (sweeps)")
     ap.add_argument("--fast-inputs", action="store_true",
                     help="sweeps only: random device-generated inputs instead of the seeded host generator")
+    ap.add_argument("--constant-inputs", action="store_true",
+                    help="diagnostic only: every element 1.0 (the matrix pipe then draws far less power; shows how "
+                         "much of the time is the chip's power limit)")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="run a plain 1 GiB device copy instead (to scale FETCH_SIZE / WRITE_SIZE under rocprofv3)")
     args = ap.parse_args()
@@ -90,11 +93,12 @@ def main():
     def time_workload(name, steps, warmup, variant=None, split=None, with_torch=True):
         w = pi.WORKLOADS[name]
         t0 = time.time()
-        if args.fast_inputs:
+        if args.fast_inputs or args.constant_inputs:
             tdt0 = {pi.F32: torch.float32, pi.F16: torch.float16, pi.BF16: torch.bfloat16}[w.dtype]
 
             def rnd(r, c):
-                t = (torch.randn(r, c, device="cuda") * w.scale).to(tdt0)
+                t = (torch.ones(r, c, device="cuda") if args.constant_inputs
+                     else torch.randn(r, c, device="cuda") * w.scale).to(tdt0)
                 t = t.view(torch.int16) if w.dtype != pi.F32 else t
                 a = t.cpu().numpy()
                 return a.view(np.uint16) if w.dtype != pi.F32 else a

@@ -847,10 +847,20 @@ __global__ __launch_bounds__(C::NT) void gemm_kernel(const GemmArgs p)
                 __builtin_amdgcn_sched_barrier(0);
             }
         };
+        // With two waves per SIMD (waves w and w+4), the second wave issues its loads one
+        // k-group after the first: a wave can sit at its load instructions for a while
+        // when the CU's load queue is full, and this way the other wave of the SIMD is
+        // multiplying meanwhile instead of sitting there as well.
+#ifdef PEAK_NO_STAGGER
+        constexpr bool STAGGER = false;
+#else
+        constexpr bool STAGGER = C::NW == 8 && C::KG >= 3 && C::DT != DT_F32;   // (fp32: measured slightly worse)
+#endif
+        const int grp = __builtin_amdgcn_readfirstlane(wave >> 2);
         issue_direct_all(0, 0);
         wait_vmcnt<0>();
         lds_barrier();
-        issue_direct_all(1, 1);
+        if (!STAGGER || grp == 0) issue_direct_all(1, 1);
         fetch(0, 0, 0);
         for (int kt0 = 0; kt0 < KT; kt0 += 2) {
             static_for<2>([&](auto sc) {
@@ -864,10 +874,13 @@ __global__ __launch_bounds__(C::NT) void gemm_kernel(const GemmArgs p)
                             wait_vmcnt<0>();                            // own loads of tile kt+1
                             lds_barrier();                              // tile kt+1 complete, tile kt read
                             settle(IC<(kg & 1)>{});
-                            issue_direct_all(kt + 2, s);
+                            if (!STAGGER || grp == 0) issue_direct_all(kt + 2, s);
                             fetch(1 - s, 0, 0);
                         } else {
                             settle(IC<(kg & 1)>{});
+                            if constexpr (kg == 0) {
+                                if (STAGGER && grp == 1) issue_direct_all(kt + 1, 1 - s);
+                            }
                             fetch(s, kg + 1, (kg + 1) & 1);
                         }
                         mfma_half(af[kg & 1], bf[kg & 1], IC<0>{});
