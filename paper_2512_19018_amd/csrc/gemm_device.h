@@ -109,7 +109,7 @@ PEAK_DEV int swz(int r)
 }
 
 template <int DT_, int BM_, int BN_, int RB_, int WAVES_M_, int WAVES_N_, int NS_,
-          bool A_T_, bool B_T_, bool DIRECT_, int AX_ = 0, bool TR_ = false, bool PP_ = false>
+          bool A_T_, bool B_T_, bool DIRECT_, int AX_ = 0, bool TR_ = false, bool PP_ = false, bool ATR_ = false>
 struct Cfg {
     static constexpr int DT = DT_;
     static constexpr int ESZ = DT_ == DT_F32 ? 4 : 2;
@@ -132,7 +132,10 @@ struct Cfg {
     // (ds_read_b64_tr_b16); fp32 needs no transposition at all (one float per lane
     // and MFMA, 32 lanes along a row)
     static constexpr bool B_TR = TR_;
-    static_assert(!TR_ || (DIRECT_ && B_T_ && !A_T_ && RB_ == 128), "B kept as [k][n] rows in LDS: B stored K x N, direct");
+    // the same for A stored K x M: [k][m] rows in LDS, read with the transposing read
+    static constexpr bool A_TR = ATR_;
+    static_assert(!ATR_ || (DIRECT_ && A_T_ && RB_ == 128 && AX_ == 0 && !PP_), "A kept as [k][m] rows in LDS: A stored K x M, direct");
+    static_assert(!TR_ || (DIRECT_ && B_T_ && (!A_T_ || ATR_) && RB_ == 128), "B kept as [k][n] rows in LDS: B stored K x N, direct");
     static constexpr int A_BYTES = BM_ * RB_;
     static constexpr int B_BYTES = BN_ * RB_;
     // LDS: NSA stages of the A tile, then NSB stages of the B tile.  AX extra A
@@ -343,8 +346,9 @@ struct LoaderDirect {
     }
 };
 
-// Direct global -> LDS copy of a 16-bit B stored K x N (rows run along N).  The
-// LDS tile keeps that orientation: BK rows of BN elements.  16-byte chunk c of
+// Direct global -> LDS copy of an operand stored K x N (B with transB = 0; the
+// same serves A stored K x M, with M for N and COLS = BM).  The LDS tile keeps
+// that orientation: BK rows of COLS elements.  16-byte chunk c of
 // row k sits at chunk position c ^ (4 * (k & 3)): a transposing fragment read
 // takes 4 k-rows x 64 bytes per 32 lanes, the rows are a multiple of 256 bytes
 // apart, and the XOR moves each of the four rows to its own 64-byte group of
@@ -353,9 +357,9 @@ struct LoaderDirect {
 // number of chunks; a chunk that would start at or past column N fetches the
 // row's last valid chunk instead (it only feeds columns of C that are never
 // stored), so every access stays inside the matrix.
-template <class C>
+template <class C, int COLS>
 struct LoaderDirectKN {
-    static constexpr int ROWB = C::BN * C::ESZ;                   // bytes per k-row of the tile
+    static constexpr int ROWB = COLS * C::ESZ;                    // bytes per k-row of the tile
     static constexpr int CPRN = ROWB / 16;
     static constexpr int RPI = 1024 / ROWB;                       // k-rows per wave instruction
     static constexpr int NINST = C::BK / RPI;
@@ -547,6 +551,14 @@ __global__ __launch_bounds__(C::NT) void gemm_kernel(const GemmArgs p)
     for (int mi = 0; mi < C::MI; ++mi) {
         const int r = wm * C::WTM + mi * 32 + r32;
         a_addr[mi] = r * C::RB + ((half ^ swz<C::CPR>(r)) << 4);
+        if (C::A_TR && C::DT == DT_F32) {
+            a_addr[mi] = (4 * half) * (C::BM * 4) + r * 4;
+        } else if (C::A_TR) {
+            const int i16 = lane & 15, g16 = (lane & 31) >> 4;
+            const int krow = half * 8 + (i16 >> 2);
+            const int mcol = wm * C::WTM + mi * 32 + 16 * g16 + 4 * (i16 & 3);
+            a_addr[mi] = krow * (C::BM * C::ESZ) + (((mcol >> 3) ^ (4 * (krow & 3))) << 4) + (i16 & 1) * 8;
+        }
     }
 #pragma unroll
     for (int ni = 0; ni < C::NI; ++ni) {
@@ -566,6 +578,23 @@ __global__ __launch_bounds__(C::NT) void gemm_kernel(const GemmArgs p)
             b_addr[ni] = C::NSA * C::A_BYTES + krow * (C::BN * C::ESZ) + (((ncol >> 3) ^ (4 * (krow & 3))) << 4) + (i16 & 1) * 8;
         }
     }
+    // fragment of A for k-group kg: 8 k per lane (the [k][m] forms mirror read_b below)
+    auto read_a = [&](const char *sta, int mi, int kg) -> u32x4 {
+        if (C::A_TR && C::DT == DT_F32) {
+            const char *q0 = sta + a_addr[mi] + (8 * kg) * (C::BM * 4);
+            return u32x4{*(const uint32_t *)q0, *(const uint32_t *)(q0 + C::BM * 4), *(const uint32_t *)(q0 + 2 * C::BM * 4),
+                         *(const uint32_t *)(q0 + 3 * C::BM * 4)};
+        }
+        if (C::A_TR) {
+            typedef short s16x4 __attribute__((ext_vector_type(4)));
+            const char *q0 = sta + a_addr[mi] + (16 * kg) * (C::BM * C::ESZ);
+            const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4 *)q0);
+            const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4 *)(q0 + 4 * (C::BM * C::ESZ)));
+            const u32x2 l2 = __builtin_bit_cast(u32x2, lo), h2 = __builtin_bit_cast(u32x2, hi);
+            return u32x4{l2[0], l2[1], h2[0], h2[1]};
+        }
+        return *(const u32x4 *)(sta + (a_addr[mi] ^ (kg << 5)));
+    };
     // fragment of B for k-group kg: 8 k per lane
     auto read_b = [&](const char *stb, int ni, int kg) -> u32x4 {
         if (C::B_TR && C::DT == DT_F32) {
@@ -585,26 +614,28 @@ __global__ __launch_bounds__(C::NT) void gemm_kernel(const GemmArgs p)
     };
 
     // operand loaders
-    constexpr bool A_DIRECT = C::DIRECT && !C::A_T, B_DIRECT = C::DIRECT && (!C::B_T || C::B_TR);
+    constexpr bool A_DIRECT = C::DIRECT && (!C::A_T || C::A_TR), B_DIRECT = C::DIRECT && (!C::B_T || C::B_TR);
     LoaderDirect<C, C::BM> dA;
     LoaderDirect<C, C::BN> dB;
-    LoaderDirectKN<C> nB;
+    LoaderDirectKN<C, C::BM> nA;
+    LoaderDirectKN<C, C::BN> nB;
     LoaderK<C, C::BM> kA;
     LoaderK<C, C::BN> kB;
     LoaderT<C, C::BM> tA;
     LoaderT<C, C::BN> tB;
     // loads per thread and tile that stay in flight across iterations
-    constexpr int LA = A_DIRECT ? LoaderDirect<C, C::BM>::PER_WAVE : 0;
-    constexpr int LB = !B_DIRECT ? 0 : (C::B_TR ? LoaderDirectKN<C>::PER_WAVE : LoaderDirect<C, C::BN>::PER_WAVE);
+    constexpr int LA = !A_DIRECT ? 0 : (C::A_TR ? LoaderDirectKN<C, C::BM>::PER_WAVE : LoaderDirect<C, C::BM>::PER_WAVE);
+    constexpr int LB = !B_DIRECT ? 0 : (C::B_TR ? LoaderDirectKN<C, C::BN>::PER_WAVE : LoaderDirect<C, C::BN>::PER_WAVE);
     constexpr int DLOADS = LA + LB;
     constexpr int P = C::NS - 1;                            // prefetch distance of the direct loads
-    static_assert(!A_DIRECT || LoaderDirect<C, C::BM>::NINST % C::NW == 0, "every wave issues the same number of loads");
-    static_assert(!B_DIRECT || (C::B_TR ? LoaderDirectKN<C>::NINST : LoaderDirect<C, C::BN>::NINST) % C::NW == 0, "every wave issues the same number of loads");
+    static_assert(!A_DIRECT || (C::A_TR ? LoaderDirectKN<C, C::BM>::NINST : LoaderDirect<C, C::BM>::NINST) % C::NW == 0, "every wave issues the same number of loads");
+    static_assert(!B_DIRECT || (C::B_TR ? LoaderDirectKN<C, C::BN>::NINST : LoaderDirect<C, C::BN>::NINST) % C::NW == 0, "every wave issues the same number of loads");
 
     // valid k in the matrix's last K tile; only the slice that holds that tile can see a short one
     const int tail_k = __builtin_amdgcn_readfirstlane((int)(p.K - (int64_t)(p.ktiles_total - 1) * C::BK));
     const int tail_tile = tail_k < C::BK ? p.ktiles_total - 1 - kt_begin : -1;   // relative to the slice
-    if (A_DIRECT) dA.init(p.A, p.lda, m0, p.M, kbase, p.K, tail_k, wave, lane);
+    if (A_DIRECT && !C::A_TR) dA.init(p.A, p.lda, m0, p.M, kbase, p.K, tail_k, wave, lane);
+    if (A_DIRECT && C::A_TR) nA.init(p.A, p.lda, m0, p.M, kbase, p.K, tail_k, wave, lane);
     if (B_DIRECT && !C::B_TR) dB.init(p.B, p.ldb, n0, p.N, kbase, p.K, tail_k, wave, lane);
     if (B_DIRECT && C::B_TR) nB.init(p.B, p.ldb, n0, p.N, kbase, p.K, tail_k, wave, lane);
 
@@ -646,7 +677,8 @@ __global__ __launch_bounds__(C::NT) void gemm_kernel(const GemmArgs p)
     auto issue_a = [&](int kt, int sa, auto part, auto nparts) {
         constexpr int PART = decltype(part)::value, NPARTS = decltype(nparts)::value;
         const int kr = rotated(kt < KT ? kt : KT - 1);
-        if (A_DIRECT) dA.template issue<PART, NPARTS>(a_stage(sa), kr, kr == tail_tile, wave);
+        if (A_DIRECT && !C::A_TR) dA.template issue<PART, NPARTS>(a_stage(sa), kr, kr == tail_tile, wave);
+        if (A_DIRECT && C::A_TR) nA.template issue<PART, NPARTS>(a_stage(sa), kr, kr == tail_tile, wave);
     };
     auto issue_b = [&](int kt, int sb, auto part, auto nparts) {
         constexpr int PART = decltype(part)::value, NPARTS = decltype(nparts)::value;
@@ -688,7 +720,7 @@ __global__ __launch_bounds__(C::NT) void gemm_kernel(const GemmArgs p)
         for (int kg = 0; kg < C::KG; ++kg) {
             u32x4 af[C::MI], bf[C::NI];
 #pragma unroll
-            for (int mi = 0; mi < C::MI; ++mi) af[mi] = *(const u32x4 *)(sta + (a_addr[mi] ^ (kg << 5)));
+            for (int mi = 0; mi < C::MI; ++mi) af[mi] = read_a(sta, mi, kg);
 #pragma unroll
             for (int ni = 0; ni < C::NI; ++ni) bf[ni] = read_b(stb, ni, kg);
             mfma_half(af, bf, IC<0>{});
@@ -726,7 +758,7 @@ __global__ __launch_bounds__(C::NT) void gemm_kernel(const GemmArgs p)
 #pragma unroll
                 for (int ni = 0; ni < C::NI; ++ni) bf[kk][ni] = read_b(stb, ni, h * HK + kk);
 #pragma unroll
-                for (int mi = 0; mi < C::MI; ++mi) af[kk][mi] = *(const u32x4 *)(sta + (a_addr[mi] ^ ((h * HK + kk) << 5)));
+                for (int mi = 0; mi < C::MI; ++mi) af[kk][mi] = read_a(sta, mi, h * HK + kk);
             }
         };
         auto multiply_half = [&]() {
@@ -815,8 +847,8 @@ __global__ __launch_bounds__(C::NT) void gemm_kernel(const GemmArgs p)
         // wave has asked of LDS (the fragments fetched one k-group earlier) has arrived.
         // In-order return of LDS data keeps the compiler's own lgkmcnt waits for the A
         // fragments valid with the extra reads in between (they can only over-wait).
-        constexpr bool TR_ASM = C::B_TR && C::DT != DT_F32;
-        u32x2 bl[2][C::NI], bh[2][C::NI];
+        constexpr bool TR_ASM = C::B_TR && C::DT != DT_F32, ATR_ASM = C::A_TR && C::DT != DT_F32;
+        u32x2 bl[2][C::NI], bh[2][C::NI], al[2][C::MI], ah[2][C::MI];
         const uint32_t lds_b0 = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) char *)lds;
         auto fetch = [&](int stage, int kg, int set) {
             const char *sta = a_stage(stage), *stb = b_frag_base(stage);
@@ -831,18 +863,35 @@ __global__ __launch_bounds__(C::NT) void gemm_kernel(const GemmArgs p)
                         bf[set][i] = read_b(stb, i, kg);
                     }
                 }
-                if (i < C::MI) af[set][i] = *(const u32x4 *)(sta + (a_addr[i] ^ (kg << 5)));
+                if (i < C::MI) {
+                    if constexpr (ATR_ASM) {
+                        const uint32_t a0 = lds_b0 + stage * C::A_BYTES + a_addr[i] + (16 * kg) * (C::BM * C::ESZ);
+                        asm volatile("ds_read_b64_tr_b16 %0, %1" : "=v"(al[set][i]) : "v"(a0) : "memory");
+                        asm volatile("ds_read_b64_tr_b16 %0, %1 offset:%2" : "=v"(ah[set][i]) : "v"(a0), "n"(4 * C::BM * C::ESZ) : "memory");
+                    } else {
+                        af[set][i] = read_a(sta, i, kg);
+                    }
+                }
             }
         };
-        // the B fragments of `set` have arrived (see above): hand them to the compiler
+        // the assembly-read fragments of `set` have arrived (see above): hand them to the compiler
         auto settle = [&](auto setc) {
             constexpr int set = decltype(setc)::value;
-            if constexpr (TR_ASM) {
+            if constexpr (TR_ASM || ATR_ASM) {
                 __builtin_amdgcn_s_waitcnt(waitcnt_imm(63, 0));
+                if constexpr (TR_ASM) {
 #pragma unroll
-                for (int i = 0; i < C::NI; ++i) {
-                    asm volatile("" : "+v"(bl[set][i]), "+v"(bh[set][i]));
-                    bf[set][i] = u32x4{bl[set][i][0], bl[set][i][1], bh[set][i][0], bh[set][i][1]};
+                    for (int i = 0; i < C::NI; ++i) {
+                        asm volatile("" : "+v"(bl[set][i]), "+v"(bh[set][i]));
+                        bf[set][i] = u32x4{bl[set][i][0], bl[set][i][1], bh[set][i][0], bh[set][i][1]};
+                    }
+                }
+                if constexpr (ATR_ASM) {
+#pragma unroll
+                    for (int i = 0; i < C::MI; ++i) {
+                        asm volatile("" : "+v"(al[set][i]), "+v"(ah[set][i]));
+                        af[set][i] = u32x4{al[set][i][0], al[set][i][1], ah[set][i][0], ah[set][i][1]};
+                    }
                 }
                 __builtin_amdgcn_sched_barrier(0);
             }
@@ -886,7 +935,7 @@ __global__ __launch_bounds__(C::NT) void gemm_kernel(const GemmArgs p)
                         mfma_half(af[kg & 1], bf[kg & 1], IC<0>{});
                         mfma_half(af[kg & 1], bf[kg & 1], IC<1>{});
                         constexpr int NMFMA = C::MI * C::NI * (C::DT == DT_F32 ? 4 : 1);
-                        constexpr int NDS = C::MI + (TR_ASM ? 0 : C::NI * (!C::B_TR ? 1 : 4));
+                        constexpr int NDS = (ATR_ASM ? 0 : C::MI * (!C::A_TR ? 1 : 4)) + (TR_ASM ? 0 : C::NI * (!C::B_TR ? 1 : 4));
                         constexpr int NVM = LAST ? DLOADS : 0;
                         constexpr int PER = C::DT == DT_F32 ? 4 : 1;       // MFMAs per slot
                         static_for<NMFMA / PER>([&](auto ic) {
@@ -900,6 +949,11 @@ __global__ __launch_bounds__(C::NT) void gemm_kernel(const GemmArgs p)
                 }
             });
         }
+        // The last k-group fetched fragments of a tile that does not exist.  Reads issued as
+        // assembly must still be waited for and their registers kept until then: the compiler
+        // takes the unused results for dead, and an LDS read that returns after its registers
+        // were given to something else (an address of the epilogue, say) would overwrite it.
+        settle(IC<0>{});
     } else if (!C::PIPE) {
         // Two-phase scheme: at the barrier of step kt tile kt is complete; its
         // fragments are read after the barrier.
@@ -954,7 +1008,7 @@ __global__ __launch_bounds__(C::NT) void gemm_kernel(const GemmArgs p)
 #pragma unroll
             for (int i = 0; i < (C::MI > C::NI ? C::MI : C::NI); ++i) {
                 if (i < C::NI) bf[set][i] = read_b(stb, i, kg);
-                if (i < C::MI) af[set][i] = *(const u32x4 *)(sta + (a_addr[i] ^ (kg << 5)));
+                if (i < C::MI) af[set][i] = read_a(sta, i, kg);
             }
         };
         // tiles 0 and 1 complete; first fragments

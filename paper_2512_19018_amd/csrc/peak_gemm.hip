@@ -52,7 +52,8 @@ struct Variant {
     int bm, bn, bk, nt, ns, lds;
     int max_m;           // skinny kernels: largest M
     launch_fn launch;
-    int tr;              // B (K x N, 16-bit) goes to LDS untransposed and is read with transposing LDS reads
+    int tr;              // B (K x N) goes to LDS untransposed ([k][n] rows)
+    int atr;             // A (K x M) goes to LDS untransposed ([k][m] rows)
 };
 
 #define TILED(NAME, DT, BM, BN, RB, WMW, WNW, NS, AT, BT, DIR)                                         \
@@ -69,6 +70,12 @@ struct Variant {
     {NAME, KIND_TILED, DT, 0, 1, 1, BM, BN, RB / (DT == DT_F32 ? 4 : 2), WMW * WNW * 64, NS,                                \
      Cfg<DT, BM, BN, RB, WMW, WNW, NS, false, true, true, 0, true>::LDS_BYTES, 0,                      \
      &launch_gemm<Cfg<DT, BM, BN, RB, WMW, WNW, NS, false, true, true, 0, true>>, 1}
+
+// A stored K x M staged directly as [k][m] rows; B either along K ("_tt") or [k][n] rows as well ("_tn")
+#define TILED_ATR(NAME, DT, BM, BN, RB, WMW, WNW, NS, BTR)                                             \
+    {NAME, KIND_TILED, DT, 1, BTR, 1, BM, BN, RB / (DT == DT_F32 ? 4 : 2), WMW * WNW * 64, NS,         \
+     Cfg<DT, BM, BN, RB, WMW, WNW, NS, true, BTR != 0, true, 0, BTR != 0, false, true>::LDS_BYTES, 0,  \
+     &launch_gemm<Cfg<DT, BM, BN, RB, WMW, WNW, NS, true, BTR != 0, true, 0, BTR != 0, false, true>>, BTR, 1}
 
 #define TILED_PP(NAME, DT, BM, BN, RB, WMW, WNW, NS, TR)                                              \
     {NAME, KIND_TILED, DT, 0, TR, 1, BM, BN, RB / (DT == DT_F32 ? 4 : 2), WMW * WNW * 64, NS,          \
@@ -159,6 +166,20 @@ static const Variant g_variants[] = {
     TILED_TR("f32_t256x128w4_nn", DT_F32, 256, 128, 128, 2, 2, 2),
     TILED_TR("f32_t128x64w4_nn", DT_F32, 128, 64, 128, 2, 2, 2),
 
+    // A stored K x M ("_t?"): staged directly as [k][m] rows
+    TILED_ATR("bf16_t256x256w8_tt", DT_BF16, 256, 256, 128, 2, 4, 2, 0),
+    TILED_ATR("f16_t256x256w8_tt", DT_F16, 256, 256, 128, 2, 4, 2, 0),
+    TILED_ATR("bf16_t256x256w8_tn", DT_BF16, 256, 256, 128, 2, 4, 2, 1),
+    TILED_ATR("f16_t256x256w8_tn", DT_F16, 256, 256, 128, 2, 4, 2, 1),
+    TILED_ATR("bf16_t128x128w4_tt", DT_BF16, 128, 128, 128, 2, 2, 2, 0),
+    TILED_ATR("f16_t128x128w4_tt", DT_F16, 128, 128, 128, 2, 2, 2, 0),
+    TILED_ATR("bf16_t128x128w4_tn", DT_BF16, 128, 128, 128, 2, 2, 2, 1),
+    TILED_ATR("f16_t128x128w4_tn", DT_F16, 128, 128, 128, 2, 2, 2, 1),
+    TILED_ATR("f32_t128x128w4_tt", DT_F32, 128, 128, 128, 2, 2, 2, 0),
+    TILED_ATR("f32_t128x128w4_tn", DT_F32, 128, 128, 128, 2, 2, 2, 1),
+    TILED_ATR("f32_t256x128w8_tt", DT_F32, 256, 128, 128, 4, 2, 2, 0),
+    TILED_ATR("f32_t256x128w8_tn", DT_F32, 256, 128, 128, 4, 2, 2, 1),
+
     // M <= 16, both operands along K: B is streamed once.  LDS ring of BN rows x KSTEP ...
     SKINNY("bf16_skinny16s3_nt", DT_BF16, 64, 128, 3),
     SKINNY("f16_skinny16s3_nt", DT_F16, 64, 128, 3),
@@ -209,18 +230,21 @@ static bool variant_fits(const Variant &v, const peak_gemm_desc_t &d)
     if (v.kind != KIND_TILED && d.M > v.max_m) return false;
     if (v.direct) {
         const int es = esize_of(d.dtype);
+        const bool a_along_k = !v.a_t, b_along_k = !v.b_t;      // copied in 16-byte chunks along K
         if (v.kind == KIND_TILED) {
-            // K may stop inside the last K tile, at a 16-byte chunk boundary
-            if ((d.K * es) % 16 != 0) return false;
+            // K may stop inside the last K tile: at a 16-byte chunk boundary for an operand that
+            // runs along K, anywhere for one staged as [k][.] rows
+            if ((a_along_k || b_along_k) && (d.K * es) % 16 != 0) return false;
             if (v.tr && (d.N * es) % 16 != 0) return false;
+            if (v.atr && (d.M * es) % 16 != 0) return false;
         } else if (d.K % v.bk != 0 || d.K < v.bk) {
             return false;
         }
         if ((d.lda * es) % 16 != 0 || (d.ldb * es) % 16 != 0) return false;
         // a workgroup's operand panel is addressed with 32-bit byte offsets
         const int64_t lim = (int64_t)1 << 31;
-        if (((int64_t)(v.bm - 1) * d.lda + d.K) * es >= lim) return false;
-        if (v.tr ? ((d.K - 1) * d.ldb + d.N) * es >= lim : ((int64_t)(v.bn - 1) * d.ldb + d.K) * es >= lim) return false;
+        if (v.atr ? ((d.K - 1) * d.lda + d.M) * es >= lim : a_along_k && ((int64_t)(v.bm - 1) * d.lda + d.K) * es >= lim) return false;
+        if (v.tr ? ((d.K - 1) * d.ldb + d.N) * es >= lim : b_along_k && ((int64_t)(v.bn - 1) * d.ldb + d.K) * es >= lim) return false;
     }
     return true;
 }
@@ -251,6 +275,7 @@ static double tiled_cost(const Variant &v, const peak_gemm_desc_t &d, int split)
     }
     if (!v.direct) eff *= 0.7;
     if (v.tr) eff *= v.dt == DT_F32 ? 1.10 : 1.03;      // B staged directly: no register transposition, no masked loads
+    if (v.atr) eff *= 1.5;                              // likewise A; the alternative is the register-staged general tile
     if (v.dt == DT_F32 && v.ns == 3) eff *= 0.97;
     const double fixed = 12.0e6;                    // prologue + epilogue of one tile, same units
     // K slices write and re-read fp32 partials: about 9 units per element and slice

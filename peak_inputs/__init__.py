@@ -222,6 +222,11 @@ WORKLOADS = {
                         "paper shape f16 2048^2 NN"),
     "P4k_f16": Workload("P4k_f16", F16, 4096, 4096, 4096, 0, 0, 1.0, 0.0, "uniform", 1.0, 8,
                         "paper shape f16 4096^2 NN"),
+    # the two layouts with A stored K x M, as context for the [k][m] staging path
+    "T4k_bf16_tn": Workload("T4k_bf16_tn", BF16, 4096, 4096, 4096, 1, 0, 1.0, 0.0, "normal", 1.0 / math.sqrt(4096.0), 9,
+                            "bf16 4096^3 TN (A stored K x M, B stored K x N)"),
+    "T4k_bf16_tt": Workload("T4k_bf16_tt", BF16, 4096, 4096, 4096, 1, 1, 1.0, 0.0, "normal", 1.0 / math.sqrt(4096.0), 10,
+                            "bf16 4096^3 TT (A stored K x M, B stored N x K)"),
 }
 
 

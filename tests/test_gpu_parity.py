@@ -65,6 +65,11 @@ def test_exact_integers_every_variant(gu, oracle, dtype, transA, transB):
             # the last two stop K inside a K tile, at a 16-byte chunk boundary
             shapes = [(256, 256, bk), (300, 504, 2 * bk if 2 * bk <= 64 else bk), (100, 72, bk),
                       (300, 504, bk + epc), (70, 40, bk - epc)]
+            if transA:
+                # A staged as [k][m] rows: M a whole number of 16-byte chunks
+                shapes = [(-(-M // epc) * epc, N, K) for M, N, K in shapes]
+                if not transB:
+                    shapes.append((72, 40, bk + 5))        # both operands [k][.]: K may end anywhere
         else:
             shapes = [(128, 128, 64), (200, 333, 40), (77, 5, 33), (1, 1, 1), (129, 257, 64)]
         for case, (M, N, K) in enumerate(shapes):
@@ -99,6 +104,8 @@ def test_random_every_direct_variant_deep_k(gu, oracle, dtype):
                 continue
             # tiled kernels also get a K that ends inside the last K tile (of the last K slice)
             shapes = [(13, 1000, 4096)] if "skinny" in name else [(300, 520, 1024), (260, 264, 1000)]
+            if transA and "skinny" not in name:
+                shapes = [(304, 520, 1024), (264, 264, 1000)] + ([(264, 264, 1003)] if not transB else [])
             for M, N, K in shapes:
                 A, B, C = _stored(6000 + vid, dtype, M, N, K, transA, transB)
                 ref = oracle.gemm(dtype, transA, transB, M, N, K, 1.0, A, B, 0.25, C)

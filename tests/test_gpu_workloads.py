@@ -25,7 +25,8 @@ def _sample_rows(M, count, seed):
 
 
 @pytest.mark.parametrize("name,nrows", [("C1", 256), ("C2", 12), ("C3", 10), ("C3b", 16), ("C4", 12), ("C5", 16),
-                                        ("P2k_f32", 16), ("P2k_f16", 16), ("P4k_f16", 12)])
+                                        ("P2k_f32", 16), ("P2k_f16", 16), ("P4k_f16", 12),
+                                        ("T4k_bf16_tn", 12), ("T4k_bf16_tt", 12)])
 def test_workload_against_oracle(gu, oracle, name, nrows):
     w = pi.WORKLOADS[name]
     A, B, C = w.make()
