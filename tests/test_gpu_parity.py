@@ -227,3 +227,27 @@ def test_error_paths_on_device(gu):
         assert st == pg.PEAK_ERR_WORKSPACE
         st = pg.peak_gemm_run(plan.handle, 1.0, 0, a.data_ptr(), 0.0, c.data_ptr(), 0, 0, 0)
         assert st == pg.PEAK_ERR_INVALID_ARG
+
+
+@pytest.mark.parametrize("dtype", [pi.F16, pi.BF16])
+def test_two_workgroups_per_cu_with_assembly_issued_reads(gu, oracle, dtype):
+    """128x128 tiles take 64 KB of LDS, so a grid beyond 256 workgroups puts two on
+    a CU.  The kernels that stage an operand as [k][.] rows issue their transposing
+    LDS reads as assembly; the last ones of the K loop feed nothing, and must still
+    have returned before the epilogue reuses their registers (a late return once
+    overwrote a lane index there).  Full result against the oracle on sampled rows."""
+    M, N, K = 2560, 2560, 256
+    pre = "f16" if dtype == pi.F16 else "bf16"
+    names = [gu.pg.peak_gemm_variant_name(i) for i in range(gu.pg.peak_gemm_variant_count())]
+    rows = sorted({0, 1, 127, 128, 1279, 2431, 2559} | set(range(640, 648)))
+    for suffix, tA, tB in [("t128x128w4_nn", 0, 0), ("t128x128w4_tn", 1, 0), ("t128x128w4_tt", 1, 1)]:
+        vid = names.index("%s_%s" % (pre, suffix))
+        A, B, C = _stored(9100 + vid, dtype, M, N, K, tA, tB, scale=0.25)
+        ref = oracle.gemm(dtype, tA, tB, M, N, K, 1.0, A, B, 0.0, None, rows=rows)
+        C0 = gu.nan_fill(M, N, dtype)
+        for rep in range(3):
+            got, raw, info = gu.run_gemm(dtype, tA, tB, M, N, K, 1.0, 0.0, A, B, C0, flags=gu.pg.force_flags(variant=vid))
+            assert "grid=400" in info, info
+            err = oracle.rel_frobenius(got[rows], ref)
+            assert err <= gu.TOL[dtype], (info, rep, err)
+            assert np.isfinite(got).all(), info
