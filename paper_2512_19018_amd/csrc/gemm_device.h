@@ -150,7 +150,7 @@ struct Cfg {
     static constexpr bool PP = PP_;
     static_assert(!PP_ || (NS_ >= 2 && AX_ == 0 && DIRECT_ && !A_T_ && (!B_T_ || TR_) && WAVES_M_ * WAVES_N_ == 8),
                   "alternating loop: 8 waves, both operands direct");
-    static_assert(AX_ == 0 || (NS_ == 2 && DIRECT_ && !A_T_ && !B_T_), "extra A stages: two-phase, both operands direct");
+    static_assert(AX_ == 0 || (NS_ == 2 && DIRECT_ && !A_T_ && (!B_T_ || TR_)), "extra A stages: two stages of B, both operands direct");
     static_assert(WTM % 32 == 0 && WTN % 32 == 0, "wave tile is a grid of 32x32 MFMA blocks");
     static_assert(RB_ == 128 || RB_ == 64, "tile row is 64 or 128 bytes");
     static_assert((BM_ * CPR) % 64 == 0 && (BN_ * CPR) % 64 == 0, "whole wave loads");
@@ -733,7 +733,7 @@ __global__ __launch_bounds__(C::NT) void gemm_kernel(const GemmArgs p)
 #ifdef PEAK_NO_PREFETCH2
     constexpr bool PREFETCH2 = false;
 #else
-    constexpr bool PREFETCH2 = ALL_DIRECT && C::NS == 2 && C::NSA == C::NSB && C::KG % 2 == 0 && !C::PP;
+    constexpr bool PREFETCH2 = ALL_DIRECT && C::NS == 2 && C::KG % 2 == 0 && !C::PP;
 #endif
     if (C::PP) {
         // Alternating scheme.  Waves w and w+4 share a SIMD.  A K tile is worked off two
@@ -805,7 +805,7 @@ __global__ __launch_bounds__(C::NT) void gemm_kernel(const GemmArgs p)
             });
         }
         if (grp == 0) end_phase();                                  // the first group finishes one phase early
-    } else if (C::NSA != C::NSB) {
+    } else if (C::NSA != C::NSB && !PREFETCH2) {
         // Two-phase scheme with A running further ahead than B (all direct).  Per
         // step the order of issue is B(j+PB) then A(j+PA); at the barrier of step j
         // tile j of both operands must be complete.
@@ -850,8 +850,8 @@ __global__ __launch_bounds__(C::NT) void gemm_kernel(const GemmArgs p)
         constexpr bool TR_ASM = C::B_TR && C::DT != DT_F32, ATR_ASM = C::A_TR && C::DT != DT_F32;
         u32x2 bl[2][C::NI], bh[2][C::NI], al[2][C::MI], ah[2][C::MI];
         const uint32_t lds_b0 = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) char *)lds;
-        auto fetch = [&](int stage, int kg, int set) {
-            const char *sta = a_stage(stage), *stb = b_frag_base(stage);
+        auto fetch = [&](int stage_a, int stage, int kg, int set) {
+            const char *sta = a_stage(stage_a), *stb = b_frag_base(stage);
 #pragma unroll
             for (int i = 0; i < (C::MI > C::NI ? C::MI : C::NI); ++i) {
                 if (i < C::NI) {
@@ -865,7 +865,7 @@ __global__ __launch_bounds__(C::NT) void gemm_kernel(const GemmArgs p)
                 }
                 if (i < C::MI) {
                     if constexpr (ATR_ASM) {
-                        const uint32_t a0 = lds_b0 + stage * C::A_BYTES + a_addr[i] + (16 * kg) * (C::BM * C::ESZ);
+                        const uint32_t a0 = lds_b0 + stage_a * C::A_BYTES + a_addr[i] + (16 * kg) * (C::BM * C::ESZ);
                         asm volatile("ds_read_b64_tr_b16 %0, %1" : "=v"(al[set][i]) : "v"(a0) : "memory");
                         asm volatile("ds_read_b64_tr_b16 %0, %1 offset:%2" : "=v"(ah[set][i]) : "v"(a0), "n"(4 * C::BM * C::ESZ) : "memory");
                     } else {
@@ -906,37 +906,59 @@ __global__ __launch_bounds__(C::NT) void gemm_kernel(const GemmArgs p)
         constexpr bool STAGGER = C::NW == 8 && C::KG >= 3 && C::DT != DT_F32;   // (fp32: measured slightly worse)
 #endif
         const int grp = __builtin_amdgcn_readfirstlane(wave >> 2);
+        // Three A stages (asymmetric ring): the stage of A tile kt+2 is free a whole step
+        // before B's, so its loads go out one per k-group through step kt and have more
+        // than a step to land; only B's loads leave in a burst after the barrier.
+        constexpr bool AXP = PREFETCH2 && C::NSA == 3;
+        static_assert(!AXP || (LA == C::KG && C::NSB == 2), "one A load per wave and k-group");
+        constexpr int U = AXP ? 6 : 2;                               // tiles per trip: both stage indices static
+        constexpr int BPARTS = 1;                                    // B's loads in one burst (half of them a k-group later: no gain)
+        constexpr int PENDING = AXP ? C::KG - 1 : 0;                 // loads of the step under way at its barrier
         issue_direct_all(0, 0);
         wait_vmcnt<0>();
         lds_barrier();
-        if (!STAGGER || grp == 0) issue_direct_all(1, 1);
-        fetch(0, 0, 0);
-        for (int kt0 = 0; kt0 < KT; kt0 += 2) {
-            static_for<2>([&](auto sc) {
-                constexpr int s = decltype(sc)::value;
-                const int kt = kt0 + s;
+        if (AXP) {
+            issue_b(1, 1, IC<0>{}, IC<BPARTS>{});
+            issue_a(1, 1, IC<0>{}, IC<1>{});
+        } else if (!STAGGER || grp == 0) {
+            issue_direct_all(1, 1);
+        }
+        fetch(0, 0, 0, 0);
+        for (int kt0 = 0; kt0 < KT; kt0 += U) {
+            static_for<U>([&](auto uc) {
+                constexpr int u = decltype(uc)::value;
+                constexpr int s = u % 2, sa = AXP ? u % 3 : s;       // stages of tile kt: B's and A's
+                const int kt = kt0 + u;
                 if (kt < KT) {
                     static_for<C::KG>([&](auto kgc) {
                         constexpr int kg = decltype(kgc)::value;
                         constexpr bool LAST = kg + 1 == C::KG;
                         if constexpr (LAST) {
-                            wait_vmcnt<0>();                            // own loads of tile kt+1
+                            wait_vmcnt<PENDING>();                      // own loads of tile kt+1
                             lds_barrier();                              // tile kt+1 complete, tile kt read
                             settle(IC<(kg & 1)>{});
-                            if (!STAGGER || grp == 0) issue_direct_all(kt + 2, s);
-                            fetch(1 - s, 0, 0);
+                            if constexpr (AXP) {
+                                issue_b(kt + 2, s, IC<0>{}, IC<BPARTS>{});
+                                issue_a(kt + 2, (sa + 2) % 3, kgc, IC<C::KG>{});
+                            } else if (!STAGGER || grp == 0) {
+                                issue_direct_all(kt + 2, s);
+                            }
+                            fetch(AXP ? (sa + 1) % 3 : 1 - s, 1 - s, 0, 0);
                         } else {
                             settle(IC<(kg & 1)>{});
-                            if constexpr (kg == 0) {
+                            if constexpr (AXP) {
+                                if constexpr (kg == 0 && BPARTS == 2) issue_b(kt + 1, 1 - s, IC<1>{}, IC<2>{});
+                                issue_a(kt + 2, (sa + 2) % 3, kgc, IC<C::KG>{});
+                            } else if constexpr (kg == 0) {
                                 if (STAGGER && grp == 1) issue_direct_all(kt + 1, 1 - s);
                             }
-                            fetch(s, kg + 1, (kg + 1) & 1);
+                            fetch(sa, s, kg + 1, (kg + 1) & 1);
                         }
                         mfma_half(af[kg & 1], bf[kg & 1], IC<0>{});
                         mfma_half(af[kg & 1], bf[kg & 1], IC<1>{});
                         constexpr int NMFMA = C::MI * C::NI * (C::DT == DT_F32 ? 4 : 1);
                         constexpr int NDS = (ATR_ASM ? 0 : C::MI * (!C::A_TR ? 1 : 4)) + (TR_ASM ? 0 : C::NI * (!C::B_TR ? 1 : 4));
-                        constexpr int NVM = LAST ? DLOADS : 0;
+                        constexpr int NVM = AXP ? (LAST ? LB + 1 : 1) : (LAST ? DLOADS : 0);
                         constexpr int PER = C::DT == DT_F32 ? 4 : 1;       // MFMAs per slot
                         static_for<NMFMA / PER>([&](auto ic) {
                             constexpr int i = decltype(ic)::value;

@@ -66,6 +66,11 @@ struct Variant {
      Cfg<DT, BM, BN, RB, WMW, WNW, NS, false, false, true, AX>::LDS_BYTES, 0,                          \
      &launch_gemm<Cfg<DT, BM, BN, RB, WMW, WNW, NS, false, false, true, AX>>}
 
+#define TILED_AX_TR(NAME, DT, BM, BN, RB, WMW, WNW, NS, AX)                                           \
+    {NAME, KIND_TILED, DT, 0, 1, 1, BM, BN, RB / (DT == DT_F32 ? 4 : 2), WMW * WNW * 64, NS,           \
+     Cfg<DT, BM, BN, RB, WMW, WNW, NS, false, true, true, AX, true>::LDS_BYTES, 0,                     \
+     &launch_gemm<Cfg<DT, BM, BN, RB, WMW, WNW, NS, false, true, true, AX, true>>, 1}
+
 #define TILED_TR(NAME, DT, BM, BN, RB, WMW, WNW, NS)                                                   \
     {NAME, KIND_TILED, DT, 0, 1, 1, BM, BN, RB / (DT == DT_F32 ? 4 : 2), WMW * WNW * 64, NS,                                \
      Cfg<DT, BM, BN, RB, WMW, WNW, NS, false, true, true, 0, true>::LDS_BYTES, 0,                      \
@@ -142,6 +147,8 @@ static const Variant g_variants[] = {
     // ... or B staged directly as [k][n] rows and read with transposing LDS reads
     TILED_TR("bf16_t256x256w8_nn", DT_BF16, 256, 256, 128, 2, 4, 2),
     TILED_TR("f16_t256x256w8_nn", DT_F16, 256, 256, 128, 2, 4, 2),
+    TILED_AX_TR("bf16_t256x256w8a3_nn", DT_BF16, 256, 256, 128, 2, 4, 2, 1),
+    TILED_AX_TR("f16_t256x256w8a3_nn", DT_F16, 256, 256, 128, 2, 4, 2, 1),
     TILED_TR("bf16_t128x256w8_nn", DT_BF16, 128, 256, 128, 2, 4, 2),
     TILED_TR("f16_t128x256w8_nn", DT_F16, 128, 256, 128, 2, 4, 2),
     TILED_TR("bf16_t128x128w4_nn", DT_BF16, 128, 128, 128, 2, 2, 2),
@@ -201,7 +208,7 @@ static bool variant_selectable(int id)
 {
     const char *n = g_variants[id].name;
     if (strstr(n, "_p256") || strstr(n, "_pt256")) return false;
-    if (strstr(n, "k32s4") || strstr(n, "k32s5") || strstr(n, "w8a3") || strstr(n, "w4k32")) return false;
+    if (strstr(n, "k32s4") || strstr(n, "k32s5") || strstr(n, "w4k32")) return false;
     return true;
 }
 
@@ -275,6 +282,7 @@ static double tiled_cost(const Variant &v, const peak_gemm_desc_t &d, int split)
     }
     if (!v.direct) eff *= 0.7;
     if (v.tr) eff *= v.dt == DT_F32 ? 1.10 : 1.03;      // B staged directly: no register transposition, no masked loads
+XX
     if (v.atr) eff *= 1.5;                              // likewise A; the alternative is the register-staged general tile
     if (v.dt == DT_F32 && v.ns == 3) eff *= 0.97;
     const double fixed = 12.0e6;                    // prologue + epilogue of one tile, same units
