@@ -148,6 +148,11 @@ struct Cfg {
     // Alternating main loop: the two waves of a SIMD take turns, one reading
     // fragments and issuing loads while the other multiplies (see gemm_kernel)
     static constexpr bool PP = PP_;
+    // One wave per SIMD with a 128x128 wave tile: the 256 accumulator registers must sit in
+    // the accumulation half of the register file.  The compiler does not manage that (it
+    // keeps part of them in ordinary registers and spills), so for this shape the MFMAs of
+    // the main loop are written as assembly with the accumulators constrained to AGPRs.
+    static constexpr bool ACC_AGPR = WAVES_M_ * WAVES_N_ == 4 && (BM_ / WAVES_M_) * (BN_ / WAVES_N_) == 128 * 128 && DT_ != DT_F32;
     static_assert(!PP_ || (NS_ >= 2 && AX_ == 0 && DIRECT_ && !A_T_ && (!B_T_ || TR_) && WAVES_M_ * WAVES_N_ == 8),
                   "alternating loop: 8 waves, both operands direct");
     static_assert(AX_ == 0 || (NS_ == 2 && DIRECT_ && !A_T_ && (!B_T_ || TR_)), "extra A stages: two stages of B, both operands direct");
@@ -831,6 +836,106 @@ __global__ __launch_bounds__(C::NT) void gemm_kernel(const GemmArgs p)
                 }
             });
         }
+    } else if constexpr (PREFETCH2 && C::ACC_AGPR && !C::B_TR && !C::A_TR) {
+        // One wave per SIMD.  Same scheme as the prefetch loop below (fragments one k-group
+        // ahead, the tile's barrier before its last k-group, loads of tile kt+2 after it), but
+        // nothing else runs on the SIMD while this wave issues its LDS reads and loads, so
+        // the instruction order is fixed by hand: after each MFMA at most one fragment read
+        // of the next k-group and at most one load.  The MFMAs are assembly (accumulators in
+        // AGPRs); the compiler does not know their latencies, so the wait states that the
+        // hardware needs between the zeroing of the accumulators and the first MFMA, and
+        // between the last MFMA and the first read of an accumulator, are put in by hand.
+        constexpr int NM = C::MI * C::NI, NFR = C::MI + C::NI;
+        static_assert(NFR <= NM && DLOADS <= NM && C::MI == C::NI, "one read and one load per MFMA slot");
+        u32x4 af[2][C::MI], bf[2][C::NI];
+        auto fetch_one = [&](int stage_a, int stage, int kg, auto setc, auto fc) {
+            constexpr int set = decltype(setc)::value, f = decltype(fc)::value;
+            // B0 A0 B1 A1 ...: the order in which the MFMAs below first need them
+            if constexpr (f % 2 == 0) bf[set][f / 2] = read_b(b_frag_base(stage), f / 2, kg);
+            else af[set][f / 2] = read_a(a_stage(stage_a), f / 2, kg);
+        };
+        auto mfma_one = [&](auto setc, auto ic) {
+            constexpr int set = decltype(setc)::value, i = decltype(ic)::value;
+            constexpr int mi = i / C::NI, ni = i % C::NI;
+            f32x16 &c = acc[mi][ni];
+            const u32x4 &b = bf[set][ni], &a = af[set][mi];
+            if constexpr (C::DT == DT_BF16)
+                asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, %0" : "+a"(c) : "v"(b), "v"(a));
+            else
+                asm volatile("v_mfma_f32_32x32x16_f16 %0, %1, %2, %0" : "+a"(c) : "v"(b), "v"(a));
+        };
+        auto load_one = [&](int t, int stage, auto jc) {
+            constexpr int j = decltype(jc)::value;
+            if constexpr (j < LA) issue_a(t, stage, IC<j>{}, IC<LA>{});
+            else issue_b(t, stage, IC<j - LA>{}, IC<LB>{});
+        };
+        static_for<C::MI * C::NI>([&](auto ic) {                        // accumulators into AGPRs now
+            constexpr int i = decltype(ic)::value;
+            f32x16 &c = acc[i / C::NI][i % C::NI];
+            asm volatile("" : "+a"(c));
+        });
+        asm volatile("s_nop 7\n\ts_nop 7" ::: "memory");
+        // With a third A stage, A's loads of tile kt+2 are spread over the whole of step kt
+        // (APK per k-group) and have more than a step to land; B's follow the barrier, one
+        // every other MFMA.  Without it all loads of tile kt+2 follow the barrier.
+        constexpr bool AXP = C::NSA == 3;
+        constexpr int APK = AXP ? LA / C::KG : 0;                       // A loads per k-group
+        static_assert(!AXP || (LA % C::KG == 0 && APK >= 1), "A's loads divide over the k-groups");
+        constexpr int U = AXP ? 6 : 2;
+        constexpr int PENDING = AXP ? (C::KG - 1) * APK : 0;            // loads of the step under way at its barrier
+        issue_direct_all(0, 0);
+        wait_vmcnt<0>();
+        lds_barrier();
+        issue_b(1, 1, IC<0>{}, IC<1>{});
+        issue_a(1, 1, IC<0>{}, IC<1>{});
+        static_for<NFR>([&](auto fc) { fetch_one(0, 0, 0, IC<0>{}, fc); });
+        for (int kt0 = 0; kt0 < KT; kt0 += U) {
+            static_for<U>([&](auto uc) {
+                constexpr int u = decltype(uc)::value;
+                constexpr int s = u % 2, sa = AXP ? u % 3 : s;
+                constexpr int sa1 = AXP ? (sa + 1) % 3 : 1 - s, sa2 = AXP ? (sa + 2) % 3 : s;   // A stages of tiles kt+1, kt+2
+                const int kt = kt0 + u;
+                if (kt < KT) {
+                    static_for<C::KG>([&](auto kgc) {
+                        constexpr int kg = decltype(kgc)::value;
+                        constexpr bool LAST = kg + 1 == C::KG;
+                        constexpr int cur = kg & 1, nxt = cur ^ 1;
+                        if constexpr (LAST) {
+                            wait_vmcnt<PENDING>();                      // own loads of tile kt+1
+                            lds_barrier();                              // tile kt+1 complete, tile kt read
+                        }
+                        __builtin_amdgcn_sched_barrier(0);
+                        static_for<NM>([&](auto ic) {
+                            constexpr int i = decltype(ic)::value;
+                            mfma_one(IC<cur>{}, ic);
+                            if constexpr (i < NFR) {
+                                if constexpr (LAST) fetch_one(sa1, 1 - s, 0, IC<nxt>{}, ic);
+                                else fetch_one(sa, s, kg + 1, IC<nxt>{}, ic);
+                            }
+                            if constexpr (AXP) {
+                                // A: load number kg*APK + q of tile kt+2 after MFMA q*(NM/APK) + 1
+                                static_for<APK>([&](auto qc) {
+                                    constexpr int q = decltype(qc)::value;
+                                    if constexpr (i == q * (NM / APK) + 1) issue_a(kt + 2, sa2, IC<kg * APK + q>{}, IC<LA>{});
+                                });
+                                // B: after the barrier, one after every other MFMA
+                                if constexpr (LAST && i % 2 == 0 && i / 2 < LB) issue_b(kt + 2, s, IC<i / 2>{}, IC<LB>{});
+                            } else {
+                                if constexpr (LAST && i < DLOADS) load_one(kt + 2, s, ic);
+                            }
+                            __builtin_amdgcn_sched_barrier(0);
+                        });
+                    });
+                }
+            });
+        }
+        // 32x32x16 MFMA: 8 passes of 4 cycles; an accumulator may be read 18 wait states after the issue
+        asm volatile("s_nop 15\n\ts_nop 15" ::: "memory");
+        static_for<C::MI * C::NI>([&](auto ic) {
+            constexpr int i = decltype(ic)::value;
+            f32x16 &c = acc[i / C::NI][i % C::NI];
+            asm volatile("" : "+a"(c));
+        });
     } else if (PREFETCH2) {
         // Two stages, fragments one k-group ahead.  The barrier of a tile sits before
         // its last k-group: by then every wave has read all of the tile (the last

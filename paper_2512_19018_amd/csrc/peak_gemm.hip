@@ -120,6 +120,11 @@ static const Variant g_variants[] = {
     TILED("f16_d128x256w8_nt", DT_F16, 128, 256, 128, 2, 4, 2, false, false, true),
     TILED("bf16_d128x128w4_nt", DT_BF16, 128, 128, 128, 2, 2, 2, false, false, true),
     TILED("f16_d128x128w4_nt", DT_F16, 128, 128, 128, 2, 2, 2, false, false, true),
+    // one wave per SIMD, 128x128 per wave, accumulators in AGPRs
+    TILED("bf16_d256x256w4_nt", DT_BF16, 256, 256, 128, 2, 2, 2, false, false, true),
+    TILED("f16_d256x256w4_nt", DT_F16, 256, 256, 128, 2, 2, 2, false, false, true),
+    TILED_AX("bf16_d256x256w4a3_nt", DT_BF16, 256, 256, 128, 2, 2, 2, 1),
+    TILED_AX("f16_d256x256w4a3_nt", DT_F16, 256, 256, 128, 2, 2, 2, 1),
     // three stages
     TILED("bf16_d256x128w8_nt", DT_BF16, 256, 128, 128, 4, 2, 3, false, false, true),
     TILED("f16_d256x128w8_nt", DT_F16, 256, 128, 128, 4, 2, 3, false, false, true),
@@ -208,7 +213,7 @@ static bool variant_selectable(int id)
 {
     const char *n = g_variants[id].name;
     if (strstr(n, "_p256") || strstr(n, "_pt256")) return false;
-    if (strstr(n, "k32s4") || strstr(n, "k32s5") || strstr(n, "w4k32")) return false;
+    if (strstr(n, "k32s4") || strstr(n, "k32s5") || strstr(n, "w4k32") || strstr(n, "d256x256w4_") || strstr(n, "d256x256w4a3_")) return false;
     return true;
 }
 
