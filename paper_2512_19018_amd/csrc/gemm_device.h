@@ -918,7 +918,8 @@ __global__ __launch_bounds__(C::NT) void gemm_kernel(const GemmArgs p)
                                     constexpr int q = decltype(qc)::value;
                                     if constexpr (i == q * (NM / APK) + 1) issue_a(kt + 2, sa2, IC<kg * APK + q>{}, IC<LA>{});
                                 });
-                                // B: after the barrier, one after every other MFMA
+                                // B: after the barrier, one after every other MFMA (half of them a k-group
+                                // later instead: no gain)
                                 if constexpr (LAST && i % 2 == 0 && i / 2 < LB) issue_b(kt + 2, s, IC<i / 2>{}, IC<LB>{});
                             } else {
                                 if constexpr (LAST && i < DLOADS) load_one(kt + 2, s, ic);

@@ -213,7 +213,7 @@ static bool variant_selectable(int id)
 {
     const char *n = g_variants[id].name;
     if (strstr(n, "_p256") || strstr(n, "_pt256")) return false;
-    if (strstr(n, "k32s4") || strstr(n, "k32s5") || strstr(n, "w4k32") || strstr(n, "d256x256w4_") || strstr(n, "d256x256w4a3_")) return false;
+    if (strstr(n, "k32s4") || strstr(n, "k32s5") || strstr(n, "w4k32") || strstr(n, "d256x256w4_")) return false;
     return true;
 }
 
@@ -288,6 +288,7 @@ static double tiled_cost(const Variant &v, const peak_gemm_desc_t &d, int split)
     if (!v.direct) eff *= 0.7;
     if (v.tr) eff *= v.dt == DT_F32 ? 1.10 : 1.03;      // B staged directly: no register transposition, no masked loads
     if (v.lds > 140 * 1024 && v.ns == 2 && !v.tr) eff *= 1.02;   // third A stage, A's loads spread over the step (+2 % measured; nothing with [k][n] B)
+    if (v.nt == 256 && v.bm == 256 && v.bn == 256 && v.lds > 140 * 1024) eff *= 1.02;   // one wave per SIMD on top of that
     if (v.atr) eff *= 1.5;                              // likewise A; the alternative is the register-staged general tile
     if (v.dt == DT_F32 && v.ns == 3) eff *= 0.97;
     const double fixed = 12.0e6;                    // prologue + epilogue of one tile, same units

@@ -161,7 +161,7 @@ def test_selector_table_overrides_the_cost_model(tmp_path):
     try:
         with pg.Plan(8192, 8192, 8192, pg.PEAK_DT_BF16, 0, 1) as p:
             default = p.info()
-        assert "bf16_d256x256w8" in default
+        assert "bf16_d256x256w" in default
         table = tmp_path / "table.txt"
         table.write_text("# comment\n"
                          "bf16 0 1 8192 8192 8192 bf16_d256x128w8_nt 2   # 900.0 us\n"
@@ -177,7 +177,7 @@ def test_selector_table_overrides_the_cost_model(tmp_path):
             assert "bf16_r128x128_nt" in p.info()
         # another shape: untouched
         with pg.Plan(4096, 4096, 4096, pg.PEAK_DT_BF16, 0, 1) as p:
-            assert "bf16_d256x256w8" in p.info()
+            assert "bf16_d256x256w" in p.info()
         # forcing still wins over the table
         names = [pg.peak_gemm_variant_name(i) for i in range(pg.peak_gemm_variant_count())]
         with pg.Plan(8192, 8192, 8192, pg.PEAK_DT_BF16, 0, 1,
