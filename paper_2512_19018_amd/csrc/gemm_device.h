@@ -836,7 +836,7 @@ __global__ __launch_bounds__(C::NT) void gemm_kernel(const GemmArgs p)
                 }
             });
         }
-    } else if constexpr (PREFETCH2 && C::ACC_AGPR && !C::B_TR && !C::A_TR) {
+    } else if constexpr (PREFETCH2 && C::ACC_AGPR && !C::A_TR) {
         // One wave per SIMD.  Same scheme as the prefetch loop below (fragments one k-group
         // ahead, the tile's barrier before its last k-group, loads of tile kt+2 after it), but
         // nothing else runs on the SIMD while this wave issues its LDS reads and loads, so
@@ -848,11 +848,37 @@ __global__ __launch_bounds__(C::NT) void gemm_kernel(const GemmArgs p)
         constexpr int NM = C::MI * C::NI, NFR = C::MI + C::NI;
         static_assert(NFR <= NM && DLOADS <= NM && C::MI == C::NI, "one read and one load per MFMA slot");
         u32x4 af[2][C::MI], bf[2][C::NI];
+        // B kept as [k][n] rows: its transposing reads go out as assembly (the compiler would put a
+        // wait for all loads in front of each, see the loop below) into bl/bh and are handed over
+        // at the start of the next k-group, when everything asked of LDS has arrived
+        constexpr bool TRA = C::B_TR;
+        u32x2 bl[2][C::NI], bh[2][C::NI];
+        const uint32_t lds_b0 = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) char *)lds;
         auto fetch_one = [&](int stage_a, int stage, int kg, auto setc, auto fc) {
             constexpr int set = decltype(setc)::value, f = decltype(fc)::value;
             // B0 A0 B1 A1 ...: the order in which the MFMAs below first need them
-            if constexpr (f % 2 == 0) bf[set][f / 2] = read_b(b_frag_base(stage), f / 2, kg);
-            else af[set][f / 2] = read_a(a_stage(stage_a), f / 2, kg);
+            if constexpr (f % 2 == 1) {
+                af[set][f / 2] = read_a(a_stage(stage_a), f / 2, kg);
+            } else if constexpr (TRA) {
+                const uint32_t a0 = lds_b0 + stage * C::B_BYTES + b_addr[f / 2] + (16 * kg) * (C::BN * C::ESZ);
+                u32x2 &lo = bl[set][f / 2], &hi = bh[set][f / 2];
+                asm volatile("ds_read_b64_tr_b16 %0, %1" : "=v"(lo) : "v"(a0) : "memory");
+                asm volatile("ds_read_b64_tr_b16 %0, %1 offset:%2" : "=v"(hi) : "v"(a0), "n"(4 * C::BN * C::ESZ) : "memory");
+            } else {
+                bf[set][f / 2] = read_b(b_frag_base(stage), f / 2, kg);
+            }
+        };
+        auto settle = [&](auto setc) {
+            constexpr int set = decltype(setc)::value;
+            if constexpr (TRA) {
+                __builtin_amdgcn_s_waitcnt(waitcnt_imm(63, 0));
+#pragma unroll
+                for (int i = 0; i < C::NI; ++i) {
+                    u32x2 &lo = bl[set][i], &hi = bh[set][i];
+                    asm volatile("" : "+v"(lo), "+v"(hi));
+                    bf[set][i] = u32x4{lo[0], lo[1], hi[0], hi[1]};
+                }
+            }
         };
         auto mfma_one = [&](auto setc, auto ic) {
             constexpr int set = decltype(setc)::value, i = decltype(ic)::value;
@@ -904,6 +930,7 @@ __global__ __launch_bounds__(C::NT) void gemm_kernel(const GemmArgs p)
                             wait_vmcnt<PENDING>();                      // own loads of tile kt+1
                             lds_barrier();                              // tile kt+1 complete, tile kt read
                         }
+                        settle(IC<cur>{});
                         __builtin_amdgcn_sched_barrier(0);
                         static_for<NM>([&](auto ic) {
                             constexpr int i = decltype(ic)::value;
@@ -930,6 +957,7 @@ __global__ __launch_bounds__(C::NT) void gemm_kernel(const GemmArgs p)
                 }
             });
         }
+        settle(IC<0>{});      // the last k-group's reads feed nothing, but must have returned before their registers are reused
         // 32x32x16 MFMA: 8 passes of 4 cycles; an accumulator may be read 18 wait states after the issue
         asm volatile("s_nop 15\n\ts_nop 15" ::: "memory");
         static_for<C::MI * C::NI>([&](auto ic) {
@@ -1215,6 +1243,7 @@ __global__ __launch_bounds__(C::NT) void gemm_kernel(const GemmArgs p)
                     *(f32x4 *)(scr + r32 * SROW + (ni * 32 + vq * 8 + half * 4) * 4) = v;
                 }
             asm volatile("" ::: "memory");
+            __builtin_amdgcn_sched_barrier(0);         // one slab's accumulators out of the accumulation registers at a time
 #pragma unroll
             for (int g = 0; g < 32 / RPI; ++g) {
                 const int row = g * RPI + orow;
@@ -1248,6 +1277,7 @@ __global__ __launch_bounds__(C::NT) void gemm_kernel(const GemmArgs p)
                 }
             }
             asm volatile("" ::: "memory");
+            __builtin_amdgcn_sched_barrier(0);
         }
         return;
     }

@@ -152,6 +152,8 @@ static const Variant g_variants[] = {
     // ... or B staged directly as [k][n] rows and read with transposing LDS reads
     TILED_TR("bf16_t256x256w8_nn", DT_BF16, 256, 256, 128, 2, 4, 2),
     TILED_TR("f16_t256x256w8_nn", DT_F16, 256, 256, 128, 2, 4, 2),
+    TILED_AX_TR("bf16_t256x256w4a3_nn", DT_BF16, 256, 256, 128, 2, 2, 2, 1),
+    TILED_AX_TR("f16_t256x256w4a3_nn", DT_F16, 256, 256, 128, 2, 2, 2, 1),
     TILED_AX_TR("bf16_t256x256w8a3_nn", DT_BF16, 256, 256, 128, 2, 4, 2, 1),
     TILED_AX_TR("f16_t256x256w8a3_nn", DT_F16, 256, 256, 128, 2, 4, 2, 1),
     TILED_TR("bf16_t128x256w8_nn", DT_BF16, 128, 256, 128, 2, 4, 2),
