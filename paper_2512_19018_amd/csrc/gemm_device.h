@@ -140,7 +140,7 @@ struct Cfg {
     static constexpr int B_BYTES = BN_ * RB_;
     // LDS: NSA stages of the A tile, then NSB stages of the B tile.  AX extra A
     // stages let A's loads run one more step ahead than B's when LDS cannot hold
-    // another full stage of both (asymmetric ring, all-direct two-phase loop only).
+    // another full stage of both (asymmetric ring, prefetch loops only).
     static constexpr int NSA = NS_ + AX_, NSB = NS_;
     static constexpr int LDS_BYTES = A_BYTES * NSA + B_BYTES * NSB;
     static constexpr bool PIPE = NS_ >= 4 && AX_ == 0 && !PP_;   // run-ahead main loop (see gemm_kernel); with 3 stages the
@@ -155,7 +155,8 @@ struct Cfg {
     static constexpr bool ACC_AGPR = WAVES_M_ * WAVES_N_ == 4 && (BM_ / WAVES_M_) * (BN_ / WAVES_N_) == 128 * 128 && DT_ != DT_F32;
     static_assert(!PP_ || (NS_ >= 2 && AX_ == 0 && DIRECT_ && !A_T_ && (!B_T_ || TR_) && WAVES_M_ * WAVES_N_ == 8),
                   "alternating loop: 8 waves, both operands direct");
-    static_assert(AX_ == 0 || (NS_ == 2 && DIRECT_ && !A_T_ && (!B_T_ || TR_)), "extra A stages: two stages of B, both operands direct");
+    static_assert(AX_ == 0 || (AX_ == 1 && NS_ == 2 && RB_ == 128 && DIRECT_ && !A_T_ && (!B_T_ || TR_)),
+                  "one extra A stage: two stages of B, both operands direct");
     static_assert(WTM % 32 == 0 && WTN % 32 == 0, "wave tile is a grid of 32x32 MFMA blocks");
     static_assert(RB_ == 128 || RB_ == 64, "tile row is 64 or 128 bytes");
     static_assert((BM_ * CPR) % 64 == 0 && (BN_ * CPR) % 64 == 0, "whole wave loads");
@@ -735,11 +736,7 @@ __global__ __launch_bounds__(C::NT) void gemm_kernel(const GemmArgs p)
     };
 
     constexpr bool ALL_DIRECT = A_DIRECT && B_DIRECT;
-#ifdef PEAK_NO_PREFETCH2
-    constexpr bool PREFETCH2 = false;
-#else
     constexpr bool PREFETCH2 = ALL_DIRECT && C::NS == 2 && C::KG % 2 == 0 && !C::PP;
-#endif
     if (C::PP) {
         // Alternating scheme.  Waves w and w+4 share a SIMD.  A K tile is worked off two
         // k-groups at a time; for each such part a wave first reads its fragments from
@@ -810,32 +807,6 @@ __global__ __launch_bounds__(C::NT) void gemm_kernel(const GemmArgs p)
             });
         }
         if (grp == 0) end_phase();                                  // the first group finishes one phase early
-    } else if (C::NSA != C::NSB && !PREFETCH2) {
-        // Two-phase scheme with A running further ahead than B (all direct).  Per
-        // step the order of issue is B(j+PB) then A(j+PA); at the barrier of step j
-        // tile j of both operands must be complete.
-        constexpr int PA = C::NSA - 1, PB = C::NSB - 1;
-        constexpr int U = C::NSA * C::NSB;                              // unroll: both stage indices static
-        constexpr int ALLOWED = (PA - 1) * (LA + LB) < LA + (PB - 1) * (LA + LB) ? (PA - 1) * (LA + LB)
-                                                                               : LA + (PB - 1) * (LA + LB);
-        static_for<PA>([&](auto vc) {                                   // virtual steps -PA .. -1
-            constexpr int sv = decltype(vc)::value - PA;
-            if (sv + PB >= 0) issue_b(sv + PB, (sv + PB) % C::NSB, IC<0>{}, IC<1>{});
-            issue_a(sv + PA, (sv + PA) % C::NSA, IC<0>{}, IC<1>{});
-        });
-        for (int j0 = 0; j0 < KT; j0 += U) {
-            static_for<U>([&](auto uc) {
-                constexpr int u = decltype(uc)::value;
-                const int j = j0 + u;
-                if (j < KT) {
-                    wait_vmcnt<ALLOWED>();
-                    lds_barrier();
-                    issue_b(j + PB, (u + PB) % C::NSB, IC<0>{}, IC<1>{});
-                    issue_a(j + PA, (u + PA) % C::NSA, IC<0>{}, IC<1>{});
-                    compute(u % C::NSA, u % C::NSB);
-                }
-            });
-        }
     } else if constexpr (PREFETCH2 && C::ACC_AGPR && !C::A_TR) {
         // One wave per SIMD.  Same scheme as the prefetch loop below (fragments one k-group
         // ahead, the tile's barrier before its last k-group, loads of tile kt+2 after it), but
@@ -1034,11 +1005,7 @@ __global__ __launch_bounds__(C::NT) void gemm_kernel(const GemmArgs p)
         // k-group after the first: a wave can sit at its load instructions for a while
         // when the CU's load queue is full, and this way the other wave of the SIMD is
         // multiplying meanwhile instead of sitting there as well.
-#ifdef PEAK_NO_STAGGER
-        constexpr bool STAGGER = false;
-#else
         constexpr bool STAGGER = C::NW == 8 && C::KG >= 3 && C::DT != DT_F32;   // (fp32: measured slightly worse)
-#endif
         const int grp = __builtin_amdgcn_readfirstlane(wave >> 2);
         // Three A stages (asymmetric ring): the stage of A tile kt+2 is free a whole step
         // before B's, so its loads go out one per k-group through step kt and have more
