@@ -306,7 +306,7 @@ struct LoaderDirect {
     static constexpr int PER_WAVE = (NINST + C::NW - 1) / C::NW;
     __amdgpu_buffer_rsrc_t rsrc;
     int voff[PER_WAVE];                                           // this lane's byte offset in the panel, per instruction
-    int tailmask;                                                 // bit i: instruction i's chunk lies past K in the last K tile
+    int voff_tail[PER_WAVE];                                      // the same for the last K tile: out of range where the chunk lies past K
 
     // tail_k: number of valid k in the matrix's last K tile (BK when K is a multiple of BK)
     PEAK_DEVM void init(const void *base, int64_t ld, int64_t row0, int64_t nrows, int64_t k0, int64_t K, int tail_k, int wave, int lane)
@@ -319,7 +319,6 @@ struct LoaderDirect {
         const uint64_t panel_u = ((uint64_t)(uint32_t)__builtin_amdgcn_readfirstlane((int)(panel >> 32)) << 32) |
                                  (uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)panel);
         rsrc = __builtin_amdgcn_make_buffer_rsrc((void *)panel_u, 0, __builtin_amdgcn_readfirstlane((int)bytes), 0x00020000);
-        tailmask = 0;
 #pragma unroll
         for (int i = 0; i < PER_WAVE; ++i) {
             const int j = wave + C::NW * i;
@@ -328,7 +327,7 @@ struct LoaderDirect {
             const int c = pos ^ swz<C::CPR>(row);
             if (row > rows_here - 1) row = (int)rows_here - 1;    // duplicate of a valid row; its results are never stored
             voff[i] = (int)((row * ld + (int64_t)c * C::EPC) * C::ESZ);
-            if (c * C::EPC >= tail_k) tailmask |= 1 << i;
+            voff_tail[i] = c * C::EPC >= tail_k ? OOB_VOFFSET : voff[i];
         }
     }
 
@@ -339,12 +338,11 @@ struct LoaderDirect {
     template <int PART, int NPARTS>
     PEAK_DEVM void issue(char *lds_tile, int ktile, bool tail, int wave) const
     {
-        const int bits = tail ? tailmask : 0;
 #pragma unroll
         for (int i = 0; i < PER_WAVE; ++i) {
             const int j = wave + C::NW * i;
             if (i % NPARTS == PART && (NINST % C::NW == 0 || j < NINST)) {
-                const int vo = (bits >> i) & 1 ? OOB_VOFFSET : voff[i];
+                const int vo = tail ? voff_tail[i] : voff[i];         // one select on a uniform condition
                 __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc, (__attribute__((address_space(3))) void *)(lds_tile + j * 1024),
                                                          16, vo, ktile * C::RB, 0, 0);
             }
@@ -373,8 +371,8 @@ struct LoaderDirectKN {
     static_assert(1024 % ROWB == 0 && C::BK % RPI == 0, "whole rows per instruction");
     __amdgpu_buffer_rsrc_t rsrc;
     int voff[PER_WAVE];
+    int voff_tail[PER_WAVE];                                      // for the last K tile: out of range where the k-row lies past K
     int step_bytes;                                               // BK rows of the stored matrix
-    int tailmask;                                                 // bit i: instruction i's k-row lies past K in the last K tile
 
     PEAK_DEVM void init(const void *base, int64_t ld, int64_t n0, int64_t N, int64_t k0, int64_t K, int tail_k, int wave, int lane)
     {
@@ -385,7 +383,6 @@ struct LoaderDirectKN {
         rsrc = __builtin_amdgcn_make_buffer_rsrc((void *)panel_u, 0, __builtin_amdgcn_readfirstlane((int)bytes), 0x00020000);
         step_bytes = __builtin_amdgcn_readfirstlane((int)(C::BK * ld * C::ESZ));
         const int last_chunk = (int)((N - n0) / C::EPC) - 1;                  // >= 0: N and n0 are multiples of EPC
-        tailmask = 0;
 #pragma unroll
         for (int i = 0; i < PER_WAVE; ++i) {
             const int j = wave + C::NW * i;
@@ -394,19 +391,18 @@ struct LoaderDirectKN {
             int c = C::DT == DT_F32 ? pos : pos ^ (4 * (row & 3));           // fp32 reads are row-wise: no swizzle
             if (c > last_chunk) c = last_chunk;
             voff[i] = (int)((row * ld + (int64_t)c * C::EPC) * C::ESZ);
-            if (row >= tail_k) tailmask |= 1 << i;
+            voff_tail[i] = row >= tail_k ? OOB_VOFFSET : voff[i];
         }
     }
 
     template <int PART, int NPARTS>
     PEAK_DEVM void issue(char *lds_tile, int ktile, bool tail, int wave) const
     {
-        const int bits = tail ? tailmask : 0;
 #pragma unroll
         for (int i = 0; i < PER_WAVE; ++i) {
             const int j = wave + C::NW * i;
             if (i % NPARTS == PART && (NINST % C::NW == 0 || j < NINST)) {
-                const int vo = (bits >> i) & 1 ? OOB_VOFFSET : voff[i];
+                const int vo = tail ? voff_tail[i] : voff[i];
                 __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc, (__attribute__((address_space(3))) void *)(lds_tile + j * 1024),
                                                          16, vo, ktile * step_bytes, 0, 0);
             }
