@@ -1201,8 +1201,9 @@ __global__ __launch_bounds__(C::NT) void gemm_kernel(const GemmArgs p)
             for (int ni = 0; ni < C::NI; ++ni)
 #pragma unroll
                 for (int vq = 0; vq < 4; ++vq) {
-                    f32x4 v = {p.alpha * acc[mi][ni][vq * 4 + 0], p.alpha * acc[mi][ni][vq * 4 + 1],
-                               p.alpha * acc[mi][ni][vq * 4 + 2], p.alpha * acc[mi][ni][vq * 4 + 3]};
+                    // (raw accumulators: alpha is applied on the way back, so that accumulators held in
+                    // AGPRs can go to LDS without passing through the ordinary registers)
+                    f32x4 v = {acc[mi][ni][vq * 4 + 0], acc[mi][ni][vq * 4 + 1], acc[mi][ni][vq * 4 + 2], acc[mi][ni][vq * 4 + 3]};
                     *(f32x4 *)(scr + r32 * SROW + (ni * 32 + vq * 8 + half * 4) * 4) = v;
                 }
             asm volatile("" ::: "memory");
@@ -1215,6 +1216,7 @@ __global__ __launch_bounds__(C::NT) void gemm_kernel(const GemmArgs p)
                 const char *src = scr + row * SROW + ocol * 4;
                 if (C::DT == DT_F32) {
                     f32x4 o = *(const f32x4 *)src;
+                    o[0] *= p.alpha; o[1] *= p.alpha; o[2] *= p.alpha; o[3] *= p.alpha;
                     float *dst = (float *)p.C + m * p.ldc + n;
                     if (p.beta != 0.0f) {
                         const f32x4 c = *(const f32x4 *)dst;
@@ -1223,7 +1225,8 @@ __global__ __launch_bounds__(C::NT) void gemm_kernel(const GemmArgs p)
                     *(f32x4 *)dst = o;
                 } else {
                     const f32x4 lo = *(const f32x4 *)src, hi = *(const f32x4 *)(src + 16);
-                    float o[8] = {lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
+                    float o[8] = {p.alpha * lo[0], p.alpha * lo[1], p.alpha * lo[2], p.alpha * lo[3],
+                                  p.alpha * hi[0], p.alpha * hi[1], p.alpha * hi[2], p.alpha * hi[3]};
                     uint16_t *dst = (uint16_t *)p.C + m * p.ldc + n;
                     union { u32x4 u; _Float16 h[8]; __bf16 b[8]; } pk;
                     if (p.beta != 0.0f) {
