@@ -1181,13 +1181,16 @@ __global__ __launch_bounds__(C::NT) void gemm_kernel(const GemmArgs p)
     const bool c_vec = p.flags & GF_C_VEC, ws_vec = p.flags & GF_WS_VEC;
     float *wsl = p.split > 1 ? p.ws + (int64_t)slice * p.M * p.N : nullptr;
     const bool interior = m0 + C::BM <= p.M && n0 + C::BN <= p.N;      // whole tile inside C: no masks
-    // Interior tiles with 16-byte aligned C rows: each wave turns its 32-row slabs
-    // around in LDS (fp32, padded rows) so that a store instruction writes whole
-    // row segments of the wave tile (16 bytes per lane, WTN elements per row)
-    // instead of 32 scattered 8-byte pieces.
+    // Each wave turns its 32-row slabs around in LDS (fp32, padded rows) so that a
+    // store instruction writes whole row segments of the wave tile (16 bytes per
+    // lane, WTN elements per row) instead of 32 scattered 8-byte pieces.  Interior
+    // tiles with 16-byte aligned C rows store vectors; edge tiles, unaligned rows and
+    // split-K partials leave through the same turnaround with masked stores, so the
+    // accumulators have one way out and never wait in ordinary registers.
     constexpr int SROW = C::WTN * 4 + 16;                              // scratch row stride, bytes
     constexpr bool STAGED_OK = 32 * SROW * C::NW <= C::LDS_BYTES;
-    if (STAGED_OK && interior && !wsl && (p.flags & GF_C_VEC16)) {
+    if constexpr (STAGED_OK) {
+        const bool fast = interior && !wsl && (p.flags & GF_C_VEC16);
         lds_barrier();                                                 // nobody still reads the last stage
         char *scr = lds + wave * (32 * SROW);
         constexpr int OUT_ROW = C::WTN * C::ESZ;                       // bytes of one output row of the wave tile
@@ -1214,7 +1217,21 @@ __global__ __launch_bounds__(C::NT) void gemm_kernel(const GemmArgs p)
                 const int64_t m = m0 + wm * C::WTM + mi * 32 + row;
                 const int64_t n = n0 + wn * C::WTN + ocol;
                 const char *src = scr + row * SROW + ocol * 4;
-                if (C::DT == DT_F32) {
+                if (!fast) {
+                    if (m < p.M) {
+#pragma unroll
+                        for (int q = 0; q < 4 / C::ESZ; ++q) {         // 4 elements at a time
+                            const int64_t nn = n + q * 4, left = p.N - nn;
+                            if (left > 0) {
+                                const int nvalid = left >= 4 ? 4 : (int)left;
+                                const f32x4 t = *(const f32x4 *)(src + q * 16);
+                                const float x[4] = {t[0], t[1], t[2], t[3]};
+                                if (wsl) store4<DT_F32>(wsl, m * p.N + nn, x, 1.0f, 0.0f, ws_vec, nvalid);
+                                else     store4<C::DT>(p.C, m * p.ldc + nn, x, p.alpha, p.beta, c_vec, nvalid);
+                            }
+                        }
+                    }
+                } else if (C::DT == DT_F32) {
                     f32x4 o = *(const f32x4 *)src;
                     o[0] *= p.alpha; o[1] *= p.alpha; o[2] *= p.alpha; o[3] *= p.alpha;
                     float *dst = (float *)p.C + m * p.ldc + n;
@@ -1246,7 +1263,7 @@ __global__ __launch_bounds__(C::NT) void gemm_kernel(const GemmArgs p)
             __builtin_amdgcn_sched_barrier(0);
         }
         return;
-    }
+    } else {
     if (interior && !wsl && c_vec) {
 #pragma unroll
         for (int mi = 0; mi < C::MI; ++mi) {
@@ -1284,6 +1301,7 @@ __global__ __launch_bounds__(C::NT) void gemm_kernel(const GemmArgs p)
                 }
             }
         }
+    }
     }
 #endif
 }
