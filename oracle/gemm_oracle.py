@@ -7,7 +7,9 @@ the GPU library.
 ``gemm`` returns the fp64 reference of C = alpha*op(A)*op(B) + beta*C_in for
 stored arrays (Section 2.2 of the paper: C = A x B, row-major, one dot product
 per output element; widened to the BLAS form).  ``rel_frobenius`` is the
-acceptance measure: ||C_gpu - ref||_F / ||ref||_F.
+acceptance measure: ||C_gpu - ref||_F / ||ref||_F.  ``bias_act`` is the fused
+output step act(ref + bias) (Section 1.2: a MatMul open to fusion-style
+modifications), in fp64, on a finished reference.
 """
 from __future__ import annotations
 
@@ -21,6 +23,8 @@ _LIB_PATH = os.path.join(_HERE, "liboracle_gemm.so")
 _lib = None
 
 F32, F16, BF16 = 0, 1, 2
+BIAS_NONE, BIAS_PER_COLUMN, BIAS_PER_ROW = 0, 1, 2
+ACT_NONE, ACT_RELU, ACT_GELU_TANH = 0, 1, 2
 
 
 def _load():
@@ -39,6 +43,9 @@ def _load():
             ctypes.c_double, ctypes.c_void_p, ctypes.c_int64,
             ctypes.c_void_p, ctypes.c_int64,
             ctypes.c_void_p, ctypes.c_int, ctypes.c_int]
+        lib.oracle_bias_act.restype = ctypes.c_int
+        lib.oracle_bias_act.argtypes = [ctypes.c_int64, ctypes.c_int64, ctypes.c_void_p, ctypes.c_int64,
+                                        ctypes.c_void_p, ctypes.c_int, ctypes.c_void_p, ctypes.c_int]
         lib.oracle_decode_f16.restype = ctypes.c_double
         lib.oracle_decode_f16.argtypes = [ctypes.c_uint16]
         lib.oracle_decode_bf16.restype = ctypes.c_double
@@ -106,6 +113,35 @@ def gemm(dtype: int, transA: int, transB: int, M: int, N: int, K: int,
     if rc != 0:
         raise ValueError("oracle_gemm rejected its arguments")
     return ref
+
+
+def bias_act(ref: np.ndarray, M: int, bias_kind: int = BIAS_NONE, bias: np.ndarray | None = None,
+             act: int = ACT_NONE, rows=None) -> np.ndarray:
+    """act(ref + bias) in fp64, in a new array.  ``ref`` is what ``gemm`` returned for
+    an M-row problem (all rows, or the logical rows listed in ``rows``); ``bias`` holds
+    fp32 values, one per column (BIAS_PER_COLUMN) or per logical row (BIAS_PER_ROW)."""
+    lib = _load()
+    out = np.array(ref, dtype=np.float64, order="C", copy=True)
+    if out.ndim != 2:
+        raise ValueError("ref must be 2-D")
+    N = out.shape[1]
+    bptr = None
+    if bias_kind != BIAS_NONE:
+        if bias is None or bias.dtype != np.float32 or bias.ndim != 1 or not bias.flags.c_contiguous:
+            raise ValueError("bias must be a contiguous 1-D float32 array")
+        if bias.size < (N if bias_kind == BIAS_PER_COLUMN else M):
+            raise ValueError("bias is too short")
+        bptr = bias.ctypes.data
+    rptr, nrows = None, 0
+    if rows is not None:
+        rows = np.ascontiguousarray(rows, dtype=np.int64)
+        rptr, nrows = rows.ctypes.data, rows.size
+    if out.shape[0] != (nrows if rows is not None else M):
+        raise ValueError("ref has the wrong number of rows")
+    rc = lib.oracle_bias_act(M, N, rptr, nrows, out.ctypes.data, int(bias_kind), bptr, int(act))
+    if rc != 0:
+        raise ValueError("oracle_bias_act rejected its arguments")
+    return out
 
 
 def rel_frobenius(c: np.ndarray, ref: np.ndarray) -> float:

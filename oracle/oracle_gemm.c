@@ -35,6 +35,14 @@
  * (AB)^T = B^T A^T, transpose-flag equivalence, linearity in alpha/beta,
  * numpy's fp64 product, and the element decoders against numpy/torch for
  * all 65536 bit patterns.
+ *
+ * oracle_bias_act is the fused output step some callers ask for (the kind of
+ * incremental modification "such as those done in kernel fusion" that Section
+ * 1.2 wants a MatMul to stay open to): ref <- act(ref + bias), in fp64, applied
+ * to the finished alpha*op(A)*op(B) + beta*C_in.  Pins: hand cases where the
+ * order of bias and activation matters, row- against column-bias on a
+ * non-square zero product, row subsets, torch's fp64 tanh-form GELU, the
+ * identity gelu(x) - gelu(-x) = x.
  */
 #include <math.h>
 #include <pthread.h>
@@ -193,5 +201,41 @@ int oracle_gemm(int dtype, int transA, int transB,
     }
     for (int t = 0; t < nthreads; ++t) pthread_create(&th[t], NULL, worker, &jobs[t]);
     for (int t = 0; t < nthreads; ++t) pthread_join(th[t], NULL);
+    return 0;
+}
+
+
+enum { OR_BIAS_NONE = 0, OR_BIAS_PER_COLUMN = 1, OR_BIAS_PER_ROW = 2 };
+enum { OR_ACT_NONE = 0, OR_ACT_RELU = 1, OR_ACT_GELU_TANH = 2 };
+
+/*
+ * ref(i,j) <- act(ref(i,j) + b(i,j)) for the rows oracle_gemm produced.
+ *   bias_kind  PER_COLUMN: b(i,j) = bias[j] (N fp32 values, one per column of C)
+ *              PER_ROW:    b(i,j) = bias[i] (M fp32 values, i the logical row of C)
+ *   act        RELU:       x > 0 ? x : 0
+ *              GELU_TANH:  x/2 * (1 + tanh( sqrt(2/pi) * (x + 0.044715 x^3) ))
+ *                          (the tanh form of Hendrycks and Gimpel's GELU)
+ * rows/nrows as in oracle_gemm.  Returns 0 on success, 1 on bad arguments.
+ */
+int oracle_bias_act(int64_t M, int64_t N, const int64_t *rows, int64_t nrows, double *ref,
+                    int bias_kind, const float *bias, int act)
+{
+    if (M < 0 || N < 0 || !ref) return 1;
+    if (bias_kind < 0 || bias_kind > 2 || act < 0 || act > 2) return 1;
+    if (bias_kind != OR_BIAS_NONE && !bias) return 1;
+    if (!rows) nrows = M;
+    const double c = sqrt(2.0 / acos(-1.0));
+    for (int64_t r = 0; r < nrows; ++r) {
+        const int64_t i = rows ? rows[r] : r;
+        if (i < 0 || i >= M) return 1;
+        for (int64_t j = 0; j < N; ++j) {
+            double x = ref[r * N + j];
+            if (bias_kind == OR_BIAS_PER_COLUMN) x += (double)bias[j];
+            if (bias_kind == OR_BIAS_PER_ROW) x += (double)bias[i];
+            if (act == OR_ACT_RELU) x = x > 0.0 ? x : 0.0;
+            if (act == OR_ACT_GELU_TANH) x = 0.5 * x * (1.0 + tanh(c * (x + 0.044715 * x * x * x)));
+            ref[r * N + j] = x;
+        }
+    }
     return 0;
 }

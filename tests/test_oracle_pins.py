@@ -273,3 +273,79 @@ def test_rel_frobenius_measure(oracle):
     assert oracle.rel_frobenius(np.array([[np.nan, 4.0]]), ref) == float("inf")
     assert oracle.rel_frobenius(np.zeros((1, 2)), np.zeros((1, 2))) == 0.0
     assert oracle.rel_frobenius(np.ones((1, 2)), np.zeros((1, 2))) == float("inf")
+
+
+# ---------------------------------------------------------------------------
+# The fused output step act(ref + bias)
+# ---------------------------------------------------------------------------
+
+def test_bias_act_hand_cases_fix_the_order_of_the_steps(oracle):
+    # bias first, activation second: relu(-1 + 2) = 1, whereas relu(-1) + 2 = 2
+    ref = np.array([[-1.0, 3.0], [-4.0, 0.5]])
+    bias = np.array([2.0, -1.0], dtype=np.float32)
+    out = oracle.bias_act(ref, 2, oracle.BIAS_PER_COLUMN, bias, oracle.ACT_RELU)
+    assert out.tolist() == [[1.0, 2.0], [0.0, 0.0]]
+    out = oracle.bias_act(ref, 2, oracle.BIAS_PER_ROW, bias, oracle.ACT_RELU)
+    assert out.tolist() == [[1.0, 5.0], [0.0, 0.0]]
+    # nothing asked for: unchanged, and the input is not written
+    assert oracle.bias_act(ref, 2).tolist() == ref.tolist()
+    assert ref.tolist() == [[-1.0, 3.0], [-4.0, 0.5]]
+
+
+def test_bias_kinds_on_a_non_square_zero_product(oracle):
+    # alpha = 0: the reference is all zero and the step leaves the broadcast bias behind
+    M, N = 3, 5
+    z = np.zeros((M, N))
+    bc = np.arange(1, N + 1, dtype=np.float32)
+    br = np.arange(10, 10 + M, dtype=np.float32)
+    out = oracle.bias_act(z, M, oracle.BIAS_PER_COLUMN, bc)
+    for i in range(M):
+        assert out[i].tolist() == bc.tolist()
+    out = oracle.bias_act(z, M, oracle.BIAS_PER_ROW, br)
+    for j in range(N):
+        assert out[:, j].tolist() == br.tolist()
+
+
+def test_row_bias_follows_the_logical_row_of_a_subset(oracle):
+    M, N = 6, 2
+    br = np.arange(100, 100 + M, dtype=np.float32)
+    rows = [4, 1, 5]
+    out = oracle.bias_act(np.zeros((3, N)), M, oracle.BIAS_PER_ROW, br, rows=rows)
+    assert out[:, 0].tolist() == [104.0, 101.0, 105.0]
+    with pytest.raises(ValueError):
+        oracle.bias_act(np.zeros((3, N)), M, oracle.BIAS_PER_ROW, br, rows=[0, 6, 1])
+
+
+def test_relu_keeps_positives_and_clears_the_rest(oracle):
+    x = np.array([[-2.5, -0.0, 0.0, 1e-300, 7.0, -1e-300]])
+    out = oracle.bias_act(x, 1, act=oracle.ACT_RELU)
+    assert out.tolist() == [[0.0, 0.0, 0.0, 1e-300, 7.0, 0.0]]
+
+
+def test_gelu_tanh_against_torch_fp64_and_its_symmetry(oracle):
+    rng = np.random.default_rng(5)
+    x = np.concatenate([rng.normal(0, 2, 500), np.linspace(-12, 12, 97), [0.0]]).reshape(1, -1)
+    out = oracle.bias_act(x, 1, act=oracle.ACT_GELU_TANH)
+    want = torch.nn.functional.gelu(torch.from_numpy(x), approximate="tanh").numpy()
+    np.testing.assert_allclose(out, want, rtol=1e-13, atol=1e-300)
+    # tanh is odd, so gelu(x) - gelu(-x) = x
+    neg = oracle.bias_act(-x, 1, act=oracle.ACT_GELU_TANH)
+    np.testing.assert_allclose(out - neg, x, rtol=1e-13, atol=1e-15)
+    # far tails: identity on the right, zero on the left; and gelu(0) = 0
+    tails = oracle.bias_act(np.array([[30.0, -30.0, 0.0]]), 1, act=oracle.ACT_GELU_TANH)
+    assert tails.tolist() == [[30.0, 0.0, 0.0]]          # (-0.0 == 0.0)
+
+
+def test_bias_act_composes_with_gemm_on_integers(oracle):
+    # exact small-integer product, then bias and relu by hand
+    M, N, K = 4, 3, 5
+    rng = np.random.default_rng(11)
+    a = rng.integers(-3, 4, (M, K)).astype(np.float32)
+    b = rng.integers(-3, 4, (K, N)).astype(np.float32)
+    bias = rng.integers(-5, 6, N).astype(np.float32)
+    ref = oracle.gemm(oracle.F32, 0, 0, M, N, K, 2.0, a, b)
+    out = oracle.bias_act(ref, M, oracle.BIAS_PER_COLUMN, bias, oracle.ACT_RELU)
+    for i in range(M):
+        for j in range(N):
+            s = 2 * sum(int(a[i, k]) * int(b[k, j]) for k in range(K)) + int(bias[j])
+            assert out[i, j] == max(s, 0)
