@@ -111,6 +111,49 @@ peak_status_t peak_gemm_run(peak_gemm_plan_t *plan, float alpha,
                             void *workspace, size_t workspace_bytes,
                             void *hip_stream);
 
+/*
+ * Fused output step.  Section 1.2 argues for a MatMul that stays open to
+ * incremental modifications "such as those done in kernel fusion" (and the
+ * Limitations paragraph of Section 3.1 names fusion as the case a single-kernel
+ * optimiser meets ready-made); this is that slot.  With an epilogue the run
+ * computes, in fp32 and before the one rounding to the storage type,
+ *
+ *      C = act( alpha * op(A) * op(B) + beta * C + bias )
+ *
+ *   bias_kind  PEAK_BIAS_PER_COLUMN: bias[n] is added to column n (N values);
+ *              PEAK_BIAS_PER_ROW:    bias[m] is added to row m (M values);
+ *              PEAK_BIAS_NONE:       `bias` is ignored.
+ *   bias       DEVICE pointer to fp32 values, 4-byte aligned, read-only, owned
+ *              by the caller; must not overlap C.
+ *   act        PEAK_ACT_RELU:       x > 0 ? x : 0  (a NaN becomes 0);
+ *              PEAK_ACT_GELU_TANH:  x/2 * (1 + tanh(sqrt(2/pi) * (x + 0.044715 x^3))),
+ *                                   evaluated as x / (1 + exp(-2u)) with the
+ *                                   hardware exponential (relative error of a few
+ *                                   ulp of fp32, far inside the GEMM tolerances).
+ * The struct itself is HOST memory and is read before the call returns.
+ */
+typedef enum { PEAK_BIAS_NONE = 0, PEAK_BIAS_PER_COLUMN = 1, PEAK_BIAS_PER_ROW = 2 } peak_bias_t;
+typedef enum { PEAK_ACT_NONE = 0, PEAK_ACT_RELU = 1, PEAK_ACT_GELU_TANH = 2 } peak_act_t;
+typedef struct {
+    const void *bias;
+    int32_t bias_kind;          /* a peak_bias_t value */
+    int32_t act;                /* a peak_act_t value */
+} peak_gemm_epilogue_t;
+
+/*
+ * peak_gemm_run with the fused output step: same arguments, same rules, same
+ * kernels (the step is applied where C is stored: in the GEMM kernel's
+ * epilogue, or in the reduction kernel when K is split, or in the scaling
+ * kernel when alpha == 0 or K == 0, where C = act(beta*C + bias)).
+ * epilogue == NULL, or PEAK_BIAS_NONE with PEAK_ACT_NONE, is peak_gemm_run.
+ * PEAK_ERR_INVALID_ARG for an unknown enum value or a missing or misaligned bias.
+ */
+peak_status_t peak_gemm_run_fused(peak_gemm_plan_t *plan, float alpha,
+                                  const void *A, const void *B, float beta, void *C,
+                                  const peak_gemm_epilogue_t *epilogue,
+                                  void *workspace, size_t workspace_bytes,
+                                  void *hip_stream);
+
 /* Frees the plan (host memory only).  NULL is accepted. */
 peak_status_t peak_gemm_destroy(peak_gemm_plan_t *plan);
 

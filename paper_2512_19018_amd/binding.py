@@ -13,6 +13,9 @@ PEAK_DT_F32, PEAK_DT_F16, PEAK_DT_BF16 = 0, 1, 2
 (PEAK_OK, PEAK_ERR_INVALID_ARG, PEAK_ERR_UNSUPPORTED, PEAK_ERR_WORKSPACE,
  PEAK_ERR_HIP, PEAK_ERR_ALLOC) = range(6)
 
+PEAK_BIAS_NONE, PEAK_BIAS_PER_COLUMN, PEAK_BIAS_PER_ROW = 0, 1, 2
+PEAK_ACT_NONE, PEAK_ACT_RELU, PEAK_ACT_GELU_TANH = 0, 1, 2
+
 _HERE = os.path.dirname(os.path.abspath(__file__))
 _LIB = None
 
@@ -22,6 +25,10 @@ class PeakGemmDesc(ctypes.Structure):
                 ("lda", ctypes.c_int64), ("ldb", ctypes.c_int64), ("ldc", ctypes.c_int64),
                 ("transA", ctypes.c_int32), ("transB", ctypes.c_int32),
                 ("dtype", ctypes.c_int32), ("flags", ctypes.c_uint32)]
+
+
+class PeakGemmEpilogue(ctypes.Structure):
+    _fields_ = [("bias", ctypes.c_void_p), ("bias_kind", ctypes.c_int32), ("act", ctypes.c_int32)]
 
 
 class PeakError(RuntimeError):
@@ -52,6 +59,8 @@ def load_library():
         lib.peak_gemm_workspace_bytes.argtypes = [P]
         lib.peak_gemm_run.restype = ctypes.c_int
         lib.peak_gemm_run.argtypes = [P, ctypes.c_float, P, P, ctypes.c_float, P, P, ctypes.c_size_t, P]
+        lib.peak_gemm_run_fused.restype = ctypes.c_int
+        lib.peak_gemm_run_fused.argtypes = [P, ctypes.c_float, P, P, ctypes.c_float, P, P, P, ctypes.c_size_t, P]
         lib.peak_gemm_destroy.restype = ctypes.c_int
         lib.peak_gemm_destroy.argtypes = [P]
         lib.peak_status_string.restype = ctypes.c_char_p
@@ -114,6 +123,14 @@ def peak_gemm_run(plan, alpha: float, A: int, B: int, beta: float, C: int,
                                         workspace or None, int(workspace_bytes), stream or None)
 
 
+def peak_gemm_run_fused(plan, alpha: float, A: int, B: int, beta: float, C: int, epilogue,
+                        workspace: int = 0, workspace_bytes: int = 0, stream: int = 0) -> int:
+    """As peak_gemm_run, with a PeakGemmEpilogue (or None) describing the fused output step."""
+    ep = ctypes.addressof(epilogue) if epilogue is not None else None     # host struct, read during the call
+    return load_library().peak_gemm_run_fused(plan, float(alpha), A or None, B or None, float(beta), C or None, ep,
+                                              workspace or None, int(workspace_bytes), stream or None)
+
+
 def peak_gemm_destroy(plan) -> int:
     return load_library().peak_gemm_destroy(plan)
 
@@ -145,6 +162,13 @@ class Plan:
         st = peak_gemm_run(self.handle, alpha, A, B, beta, C, workspace, workspace_bytes, stream)
         if st != PEAK_OK:
             raise PeakError(st, "peak_gemm_run")
+
+    def run_fused(self, alpha, A, B, beta, C, bias_kind=PEAK_BIAS_NONE, bias=0, act=PEAK_ACT_NONE,
+                  workspace=0, workspace_bytes=0, stream=0):
+        ep = PeakGemmEpilogue(bias or None, bias_kind, act)
+        st = peak_gemm_run_fused(self.handle, alpha, A, B, beta, C, ep, workspace, workspace_bytes, stream)
+        if st != PEAK_OK:
+            raise PeakError(st, "peak_gemm_run_fused")
 
     def close(self):
         if self.handle is not None:

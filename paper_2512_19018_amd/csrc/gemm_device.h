@@ -38,6 +38,16 @@ enum {
     GF_C_VEC16 = 16    // C base and row stride are 16-byte aligned
 };
 
+// Fused output step: v <- act(v + bias), applied to alpha*acc + beta*C in fp32
+// before the one rounding to the storage type.
+enum { BIAS_NONE = 0, BIAS_PER_COLUMN = 1, BIAS_PER_ROW = 2 };
+enum { ACT_NONE = 0, ACT_RELU = 1, ACT_GELU_TANH = 2 };
+struct Hook {
+    const float *bias;        // device, fp32: N values (per column) or M values (per row)
+    int32_t bias_kind;
+    int32_t act;
+};
+
 struct GemmArgs {
     const void *A;
     const void *B;
@@ -53,6 +63,7 @@ struct GemmArgs {
     int32_t group_m;          // tile rows per band of the tile order
     int32_t rot_m, rot_n;     // K rotation per tile row / tile column within an XCD's patch of tiles
     uint32_t flags;
+    Hook hook;
 };
 
 #define PEAK_DEV static __device__ __forceinline__
@@ -452,24 +463,58 @@ PEAK_DEV void float_to_elem(void *p, int64_t idx, float x)
     else ((__bf16 *)p)[idx] = (__bf16)x;                             // round to nearest even
 }
 
-// Four consecutive outputs of one row: out = alpha*acc + beta*C_in, rounded once.
-template <int DT>
-PEAK_DEV void store4(void *C, int64_t idx, const float x[4], float alpha, float beta, bool vec, int nvalid)
+// The fused output step on NE consecutive values of row m, from column n on.
+// (The choices are made outside the element loops, which then unroll.)
+template <int NE>
+PEAK_DEV void hook_apply(const Hook &h, float (&v)[NE], int64_t m, int64_t n)
 {
+    if (h.bias_kind == BIAS_PER_COLUMN) {
+#pragma unroll
+        for (int e = 0; e < NE; ++e) v[e] += h.bias[n + e];
+    } else if (h.bias_kind == BIAS_PER_ROW) {
+        const float b = h.bias[m];
+#pragma unroll
+        for (int e = 0; e < NE; ++e) v[e] += b;
+    }
+    if (h.act == ACT_RELU) {
+#pragma unroll
+        for (int e = 0; e < NE; ++e) v[e] = v[e] > 0.0f ? v[e] : 0.0f;
+    } else if (h.act == ACT_GELU_TANH) {
+        // v/2 * (1 + tanh(u)) = v / (1 + exp(-2u)),  u = sqrt(2/pi) * (v + 0.044715 v^3)
+#pragma unroll
+        for (int e = 0; e < NE; ++e) {
+            const float u = 0.7978845608028654f * (v[e] + 0.044715f * v[e] * v[e] * v[e]);
+            v[e] = v[e] / (1.0f + __expf(-2.0f * u));
+        }
+    }
+}
+
+PEAK_DEV bool hook_active(const Hook &h) { return (h.bias_kind | h.act) != 0; }
+
+// Stores nvalid (1..4) consecutive elements of one row of C, rounded once:
+// C[idx + e] = hook(alpha * x[e] + beta * C[idx + e]); (m, n) are the row and first
+// column, which only the hook's bias looks at.
+template <int DT>
+PEAK_DEV void store4(void *C, int64_t idx, const float x[4], float alpha, float beta, bool vec, int nvalid,
+                     const Hook hk = Hook{nullptr, 0, 0}, int64_t m = 0, int64_t n = 0)
+{
+    const bool hooked = hook_active(hk);
     if (vec && nvalid == 4) {
+        float o[4] = {alpha * x[0], alpha * x[1], alpha * x[2], alpha * x[3]};
         if (DT == DT_F32) {
-            f32x4 o = {alpha * x[0], alpha * x[1], alpha * x[2], alpha * x[3]};
             if (beta != 0.0f) {
                 const f32x4 c = *(const f32x4 *)((const float *)C + idx);
                 o[0] += beta * c[0]; o[1] += beta * c[1]; o[2] += beta * c[2]; o[3] += beta * c[3];
             }
-            *(f32x4 *)((float *)C + idx) = o;
+            if (hooked) hook_apply(hk, o, m, n);
+            const f32x4 ov = {o[0], o[1], o[2], o[3]};
+            *(f32x4 *)((float *)C + idx) = ov;
         } else {
-            float o[4] = {alpha * x[0], alpha * x[1], alpha * x[2], alpha * x[3]};
             if (beta != 0.0f) {
 #pragma unroll
                 for (int e = 0; e < 4; ++e) o[e] += beta * elem_to_float<DT>(C, idx + e);
             }
+            if (hooked) hook_apply(hk, o, m, n);
             union { u32x2 u; _Float16 h[4]; __bf16 b[4]; } pk;
 #pragma unroll
             for (int e = 0; e < 4; ++e) {
@@ -484,6 +529,11 @@ PEAK_DEV void store4(void *C, int64_t idx, const float x[4], float alpha, float 
             if (e < nvalid) {
                 float o = alpha * x[e];
                 if (beta != 0.0f) o += beta * elem_to_float<DT>(C, idx + e);
+                if (hooked) {
+                    float o1[1] = {o};
+                    hook_apply(hk, o1, m, n + e);
+                    o = o1[0];
+                }
                 float_to_elem<DT>(C, idx + e, o);
             }
         }
@@ -1188,9 +1238,9 @@ __global__ __launch_bounds__(C::NT) void gemm_kernel(const GemmArgs p)
     // split-K partials leave through the same turnaround with masked stores, so the
     // accumulators have one way out and never wait in ordinary registers.
     constexpr int SROW = C::WTN * 4 + 16;                              // scratch row stride, bytes
-    constexpr bool STAGED_OK = 32 * SROW * C::NW <= C::LDS_BYTES;
-    if constexpr (STAGED_OK) {
-        const bool fast = interior && !wsl && (p.flags & GF_C_VEC16);
+    static_assert(32 * SROW * C::NW <= C::LDS_BYTES, "the staging buffers are large enough for the turnaround");
+    {
+        const bool fast = interior && !wsl && (p.flags & GF_C_VEC16) && !hook_active(p.hook);
         lds_barrier();                                                 // nobody still reads the last stage
         char *scr = lds + wave * (32 * SROW);
         constexpr int OUT_ROW = C::WTN * C::ESZ;                       // bytes of one output row of the wave tile
@@ -1211,13 +1261,14 @@ __global__ __launch_bounds__(C::NT) void gemm_kernel(const GemmArgs p)
                 }
             asm volatile("" ::: "memory");
             __builtin_amdgcn_sched_barrier(0);         // one slab's accumulators out of the accumulation registers at a time
-#pragma unroll
-            for (int g = 0; g < 32 / RPI; ++g) {
-                const int row = g * RPI + orow;
-                const int64_t m = m0 + wm * C::WTM + mi * 32 + row;
-                const int64_t n = n0 + wn * C::WTN + ocol;
-                const char *src = scr + row * SROW + ocol * 4;
-                if (!fast) {
+            if (!fast) {
+                // masked 4-element stores; also the way out for runs with a fused output step
+#pragma unroll 1
+                for (int g = 0; g < 32 / RPI; ++g) {
+                    const int row = g * RPI + orow;
+                    const int64_t m = m0 + wm * C::WTM + mi * 32 + row;
+                    const int64_t n = n0 + wn * C::WTN + ocol;
+                    const char *src = scr + row * SROW + ocol * 4;
                     if (m < p.M) {
 #pragma unroll
                         for (int q = 0; q < 4 / C::ESZ; ++q) {         // 4 elements at a time
@@ -1227,81 +1278,50 @@ __global__ __launch_bounds__(C::NT) void gemm_kernel(const GemmArgs p)
                                 const f32x4 t = *(const f32x4 *)(src + q * 16);
                                 const float x[4] = {t[0], t[1], t[2], t[3]};
                                 if (wsl) store4<DT_F32>(wsl, m * p.N + nn, x, 1.0f, 0.0f, ws_vec, nvalid);
-                                else     store4<C::DT>(p.C, m * p.ldc + nn, x, p.alpha, p.beta, c_vec, nvalid);
+                                else     store4<C::DT>(p.C, m * p.ldc + nn, x, p.alpha, p.beta, c_vec, nvalid, p.hook, m, nn);
                             }
                         }
                     }
-                } else if (C::DT == DT_F32) {
-                    f32x4 o = *(const f32x4 *)src;
-                    o[0] *= p.alpha; o[1] *= p.alpha; o[2] *= p.alpha; o[3] *= p.alpha;
-                    float *dst = (float *)p.C + m * p.ldc + n;
-                    if (p.beta != 0.0f) {
-                        const f32x4 c = *(const f32x4 *)dst;
-                        o[0] += p.beta * c[0]; o[1] += p.beta * c[1]; o[2] += p.beta * c[2]; o[3] += p.beta * c[3];
-                    }
-                    *(f32x4 *)dst = o;
-                } else {
-                    const f32x4 lo = *(const f32x4 *)src, hi = *(const f32x4 *)(src + 16);
-                    float o[8] = {p.alpha * lo[0], p.alpha * lo[1], p.alpha * lo[2], p.alpha * lo[3],
-                                  p.alpha * hi[0], p.alpha * hi[1], p.alpha * hi[2], p.alpha * hi[3]};
-                    uint16_t *dst = (uint16_t *)p.C + m * p.ldc + n;
-                    union { u32x4 u; _Float16 h[8]; __bf16 b[8]; } pk;
-                    if (p.beta != 0.0f) {
-                        pk.u = *(const u32x4 *)dst;
+                }
+            } else {
 #pragma unroll
-                        for (int e = 0; e < 8; ++e) o[e] += p.beta * (C::DT == DT_F16 ? (float)pk.h[e] : (float)pk.b[e]);
-                    }
+                for (int g = 0; g < 32 / RPI; ++g) {
+                    const int row = g * RPI + orow;
+                    const int64_t m = m0 + wm * C::WTM + mi * 32 + row;
+                    const int64_t n = n0 + wn * C::WTN + ocol;
+                    const char *src = scr + row * SROW + ocol * 4;
+                    if (C::DT == DT_F32) {
+                        f32x4 o = *(const f32x4 *)src;
+                        o[0] *= p.alpha; o[1] *= p.alpha; o[2] *= p.alpha; o[3] *= p.alpha;
+                        float *dst = (float *)p.C + m * p.ldc + n;
+                        if (p.beta != 0.0f) {
+                            const f32x4 c = *(const f32x4 *)dst;
+                            o[0] += p.beta * c[0]; o[1] += p.beta * c[1]; o[2] += p.beta * c[2]; o[3] += p.beta * c[3];
+                        }
+                        *(f32x4 *)dst = o;
+                    } else {
+                        const f32x4 lo = *(const f32x4 *)src, hi = *(const f32x4 *)(src + 16);
+                        float o[8] = {p.alpha * lo[0], p.alpha * lo[1], p.alpha * lo[2], p.alpha * lo[3],
+                                      p.alpha * hi[0], p.alpha * hi[1], p.alpha * hi[2], p.alpha * hi[3]};
+                        uint16_t *dst = (uint16_t *)p.C + m * p.ldc + n;
+                        union { u32x4 u; _Float16 h[8]; __bf16 b[8]; } pk;
+                        if (p.beta != 0.0f) {
+                            pk.u = *(const u32x4 *)dst;
 #pragma unroll
-                    for (int e = 0; e < 8; ++e) {
-                        if (C::DT == DT_F16) pk.h[e] = (_Float16)o[e];
-                        else pk.b[e] = (__bf16)o[e];
+                            for (int e = 0; e < 8; ++e) o[e] += p.beta * (C::DT == DT_F16 ? (float)pk.h[e] : (float)pk.b[e]);
+                        }
+#pragma unroll
+                        for (int e = 0; e < 8; ++e) {
+                            if (C::DT == DT_F16) pk.h[e] = (_Float16)o[e];
+                            else pk.b[e] = (__bf16)o[e];
+                        }
+                        *(u32x4 *)dst = pk.u;
                     }
-                    *(u32x4 *)dst = pk.u;
                 }
             }
             asm volatile("" ::: "memory");
             __builtin_amdgcn_sched_barrier(0);
         }
-        return;
-    } else {
-    if (interior && !wsl && c_vec) {
-#pragma unroll
-        for (int mi = 0; mi < C::MI; ++mi) {
-            const int64_t m = m0 + wm * C::WTM + mi * 32 + r32;
-#pragma unroll
-            for (int ni = 0; ni < C::NI; ++ni) {
-#pragma unroll
-                for (int vq = 0; vq < 4; ++vq) {
-                    const int64_t n = n0 + wn * C::WTN + ni * 32 + vq * 8 + half * 4;
-                    const float x[4] = {acc[mi][ni][vq * 4 + 0], acc[mi][ni][vq * 4 + 1],
-                                        acc[mi][ni][vq * 4 + 2], acc[mi][ni][vq * 4 + 3]};
-                    store4<C::DT>(p.C, m * p.ldc + n, x, p.alpha, p.beta, true, 4);
-                }
-            }
-        }
-        return;
-    }
-#pragma unroll
-    for (int mi = 0; mi < C::MI; ++mi) {
-        const int64_t m = m0 + wm * C::WTM + mi * 32 + r32;
-        if (m < p.M) {
-#pragma unroll
-            for (int ni = 0; ni < C::NI; ++ni) {
-#pragma unroll
-                for (int vq = 0; vq < 4; ++vq) {
-                    const int64_t n = n0 + wn * C::WTN + ni * 32 + vq * 8 + half * 4;
-                    const int64_t left = p.N - n;
-                    if (left > 0) {
-                        const int nvalid = left >= 4 ? 4 : (int)left;
-                        const float x[4] = {acc[mi][ni][vq * 4 + 0], acc[mi][ni][vq * 4 + 1],
-                                            acc[mi][ni][vq * 4 + 2], acc[mi][ni][vq * 4 + 3]};
-                        if (wsl) store4<DT_F32>(wsl, m * p.N + n, x, 1.0f, 0.0f, ws_vec, nvalid);
-                        else     store4<C::DT>(p.C, m * p.ldc + n, x, p.alpha, p.beta, c_vec, nvalid);
-                    }
-                }
-            }
-        }
-    }
     }
 #endif
 }
@@ -1331,10 +1351,10 @@ __global__ __launch_bounds__(256) void splitk_reduce_kernel(const GemmArgs p)
                 if (e < nvalid) x[e] += w[e];
         }
     }
-    store4<DT>(p.C, m * p.ldc + n, x, p.alpha, p.beta, p.flags & GF_C_VEC, nvalid);
+    store4<DT>(p.C, m * p.ldc + n, x, p.alpha, p.beta, p.flags & GF_C_VEC, nvalid, p.hook, m, n);
 }
 
-// C = beta * C (alpha == 0 or K == 0).  beta == 0 writes zeros without reading.
+// C = hook(beta * C) (alpha == 0 or K == 0).  beta == 0 writes without reading.
 template <int DT>
 __global__ __launch_bounds__(256) void scale_c_kernel(const GemmArgs p)
 {
@@ -1343,6 +1363,11 @@ __global__ __launch_bounds__(256) void scale_c_kernel(const GemmArgs p)
     const int64_t m = e / p.N, n = e % p.N;
     float o = 0.0f;
     if (p.beta != 0.0f) o = p.beta * elem_to_float<DT>(p.C, m * p.ldc + n);
+    if (hook_active(p.hook)) {
+        float o1[1] = {o};
+        hook_apply(p.hook, o1, m, n);
+        o = o1[0];
+    }
     float_to_elem<DT>(p.C, m * p.ldc + n, o);
 }
 

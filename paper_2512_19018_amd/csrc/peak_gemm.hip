@@ -529,8 +529,8 @@ int peak_gemm_plan_info(const peak_gemm_plan_t *p, char *buf, size_t n)
                     (long long)p->tiles_m * p->tiles_n * p->split, p->tiles_m, p->tiles_n, p->group_m, p->ws_bytes);
 }
 
-peak_status_t peak_gemm_run(peak_gemm_plan_t *p, float alpha, const void *A, const void *B, float beta, void *C,
-                            void *workspace, size_t workspace_bytes, void *hip_stream)
+static peak_status_t run_plan(peak_gemm_plan_t *p, float alpha, const void *A, const void *B, float beta, void *C,
+                              const Hook &hook, void *workspace, size_t workspace_bytes, void *hip_stream)
 {
     if (!p) return PEAK_ERR_INVALID_ARG;
     const peak_gemm_desc_t &d = p->d;
@@ -546,13 +546,14 @@ peak_status_t peak_gemm_run(peak_gemm_plan_t *p, float alpha, const void *A, con
     a.M = d.M; a.N = d.N; a.K = d.K;
     a.lda = d.lda; a.ldb = d.ldb; a.ldc = d.ldc;
     a.alpha = alpha; a.beta = beta;
+    a.hook = hook;
     a.split = 1;
     if ((uintptr_t)C % (4 * es) == 0 && (d.ldc * es) % (4 * es) == 0) a.flags |= GF_C_VEC;
     if ((uintptr_t)C % 16 == 0 && (d.ldc * es) % 16 == 0) a.flags |= GF_C_VEC16;
 
     const bool no_product = (d.K == 0 || alpha == 0.0f);
     if (no_product) {
-        if (beta == 1.0f) return PEAK_OK;
+        if (beta == 1.0f && !(hook.bias_kind | hook.act)) return PEAK_OK;
         const int64_t blocks = cdiv(d.M * d.N, 256);
         if (blocks > 0x7FFFFFFF) return PEAK_ERR_UNSUPPORTED;
         dim3 grid((unsigned)blocks);
@@ -601,6 +602,32 @@ peak_status_t peak_gemm_run(peak_gemm_plan_t *p, float alpha, const void *A, con
         if (hipGetLastError() != hipSuccess) return PEAK_ERR_HIP;
     }
     return PEAK_OK;
+}
+
+peak_status_t peak_gemm_run(peak_gemm_plan_t *plan, float alpha, const void *A, const void *B, float beta, void *C,
+                            void *workspace, size_t workspace_bytes, void *hip_stream)
+{
+    return run_plan(plan, alpha, A, B, beta, C, Hook{nullptr, BIAS_NONE, ACT_NONE}, workspace, workspace_bytes, hip_stream);
+}
+
+peak_status_t peak_gemm_run_fused(peak_gemm_plan_t *plan, float alpha, const void *A, const void *B, float beta, void *C,
+                                  const peak_gemm_epilogue_t *epilogue,
+                                  void *workspace, size_t workspace_bytes, void *hip_stream)
+{
+    Hook hook{nullptr, BIAS_NONE, ACT_NONE};
+    if (epilogue) {
+        static_assert(PEAK_BIAS_PER_COLUMN == BIAS_PER_COLUMN && PEAK_BIAS_PER_ROW == BIAS_PER_ROW &&
+                      PEAK_ACT_RELU == ACT_RELU && PEAK_ACT_GELU_TANH == ACT_GELU_TANH, "interface and kernel enums agree");
+        if (epilogue->bias_kind < PEAK_BIAS_NONE || epilogue->bias_kind > PEAK_BIAS_PER_ROW) return PEAK_ERR_INVALID_ARG;
+        if (epilogue->act < PEAK_ACT_NONE || epilogue->act > PEAK_ACT_GELU_TANH) return PEAK_ERR_INVALID_ARG;
+        if (epilogue->bias_kind != PEAK_BIAS_NONE) {
+            if (!epilogue->bias || (uintptr_t)epilogue->bias % sizeof(float)) return PEAK_ERR_INVALID_ARG;
+            hook.bias = (const float *)epilogue->bias;
+        }
+        hook.bias_kind = epilogue->bias_kind;
+        hook.act = epilogue->act;
+    }
+    return run_plan(plan, alpha, A, B, beta, C, hook, workspace, workspace_bytes, hip_stream);
 }
 
 peak_status_t peak_gemm_destroy(peak_gemm_plan_t *plan)

@@ -154,7 +154,7 @@ __global__ __launch_bounds__(C::NT) void skinny_kernel(const GemmArgs p)
         if (p.split > 1)
             store4<DT_F32>(p.ws + (int64_t)slice * p.M * p.N, m * p.N + n, x, 1.0f, 0.0f, p.flags & GF_WS_VEC, nvalid);
         else
-            store4<C::DT>(p.C, m * p.ldc + n, x, p.alpha, p.beta, p.flags & GF_C_VEC, nvalid);
+            store4<C::DT>(p.C, m * p.ldc + n, x, p.alpha, p.beta, p.flags & GF_C_VEC, nvalid, p.hook, m, n);
     }
 }
 
@@ -254,7 +254,7 @@ __global__ __launch_bounds__(C::NT) void skinny_reg_kernel(const GemmArgs p)
         if (p.split > 1)
             store4<DT_F32>(p.ws + (int64_t)slice * p.M * p.N, m * p.N + n, x, 1.0f, 0.0f, p.flags & GF_WS_VEC, nvalid);
         else
-            store4<C::DT>(p.C, m * p.ldc + n, x, p.alpha, p.beta, p.flags & GF_C_VEC, nvalid);
+            store4<C::DT>(p.C, m * p.ldc + n, x, p.alpha, p.beta, p.flags & GF_C_VEC, nvalid, p.hook, m, n);
     }
 }
 

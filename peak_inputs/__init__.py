@@ -230,6 +230,14 @@ WORKLOADS = {
 }
 
 
+def bias_vector(seed: int, length: int, ints: bool = False, scale: float = 1.0) -> np.ndarray:
+    """fp32 bias of the fused output step (stream 3 of the seed): U[-scale, scale),
+    or small integers in [-4, 4] when ``ints``."""
+    if ints:
+        return small_int_matrix(seed, 3, 1, length, -4, 4, F32).reshape(length).copy()
+    return logical_matrix(seed, 3, 1, length, "uniform", scale, F32).reshape(length).copy()
+
+
 def small_int_matrix(seed: int, stream: int, rows: int, cols: int, lo: int, hi: int, dtype: int) -> np.ndarray:
     """Integer-valued logical matrix with entries in [lo, hi] (exact in every dtype
     for |v| <= 256)."""

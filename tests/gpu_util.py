@@ -28,19 +28,28 @@ def nan_fill(rows: int, cols: int, dtype: int) -> np.ndarray:
     return np.full((rows, cols), 0x7FC1 if dtype == pi.BF16 else 0x7E01, dtype=np.uint16)
 
 
-def run_gemm(dtype, transA, transB, M, N, K, alpha, beta, A, B, C0, flags=0, repeat=1, a_off=0, b_off=0):
+def run_gemm(dtype, transA, transB, M, N, K, alpha, beta, A, B, C0, flags=0, repeat=1, a_off=0, b_off=0,
+             fused=None):
     """A, B, C0: stored host arrays (2-D; row length = leading dimension).  C0 is
-    the initial content of C (C_in, or a NaN fill when beta == 0).  Returns
-    (C values as fp64 [M, N], raw stored C after the run, plan info)."""
+    the initial content of C (C_in, or a NaN fill when beta == 0).  ``fused``:
+    None for peak_gemm_run, or (bias_kind, fp32 bias array or None, act) for
+    peak_gemm_run_fused.  Returns (C values as fp64 [M, N], raw stored C after
+    the run, plan info)."""
     lda, ldb, ldc = A.shape[1], B.shape[1], C0.shape[1]
     dA, dB, dC = to_dev(A), to_dev(B), to_dev(C0)
     stream = torch.cuda.current_stream().cuda_stream
     with pg.Plan(M, N, K, dtype, transA, transB, lda, ldb, ldc, flags) as plan:
         info = plan.info()
         ws = torch.empty(max(plan.workspace_bytes, 256), dtype=torch.uint8, device="cuda")
+        dbias = to_dev(fused[1]) if fused is not None and fused[1] is not None else None
         for _ in range(repeat):
-            plan.run(alpha, dA.data_ptr() + a_off, dB.data_ptr() + b_off, beta, dC.data_ptr(),
-                     ws.data_ptr(), plan.workspace_bytes, stream)
+            if fused is None:
+                plan.run(alpha, dA.data_ptr() + a_off, dB.data_ptr() + b_off, beta, dC.data_ptr(),
+                         ws.data_ptr(), plan.workspace_bytes, stream)
+            else:
+                plan.run_fused(alpha, dA.data_ptr() + a_off, dB.data_ptr() + b_off, beta, dC.data_ptr(),
+                               fused[0], dbias.data_ptr() if dbias is not None else 0, fused[2],
+                               ws.data_ptr(), plan.workspace_bytes, stream)
         torch.cuda.synchronize()
     raw = from_dev(dC, dtype)
     vals = pi.to_f64(np.ascontiguousarray(raw[:M, :N]), dtype) if M and N else np.zeros((M, N))

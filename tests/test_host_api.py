@@ -208,3 +208,17 @@ def test_tuner_enumerates_only_accepted_settings():
     assert len({(c[0], c[2]) for c in cands}) == len(cands)        # each (variant, effective split) once
     line = tune.table_line(pg.PEAK_DT_BF16, 0, 1, 256, 512, 1024, "bf16_d256x256w8_nt", 4, 12.5)
     assert line.split()[:8] == ["bf16", "0", "1", "256", "512", "1024", "bf16_d256x256w8_nt", "4"]
+
+
+def test_fused_run_checks_its_epilogue_before_anything_else():
+    # no device is touched: the epilogue is validated first, and M == 0 launches nothing
+    with pg.Plan(0, 8, 8, pg.PEAK_DT_F32) as plan:
+        assert pg.peak_gemm_run_fused(plan.handle, 1.0, 0, 0, 0.0, 0, None) == pg.PEAK_OK
+        ok = pg.PeakGemmEpilogue(None, pg.PEAK_BIAS_NONE, pg.PEAK_ACT_GELU_TANH)
+        assert pg.peak_gemm_run_fused(plan.handle, 1.0, 0, 0, 0.0, 0, ok) == pg.PEAK_OK
+        for bad in (pg.PeakGemmEpilogue(None, pg.PEAK_BIAS_PER_COLUMN, 0),      # bias missing
+                    pg.PeakGemmEpilogue(0x1002, pg.PEAK_BIAS_PER_ROW, 0),       # bias not 4-byte aligned
+                    pg.PeakGemmEpilogue(None, 3, 0), pg.PeakGemmEpilogue(None, -1, 0),
+                    pg.PeakGemmEpilogue(None, 0, 3), pg.PeakGemmEpilogue(None, 0, -1)):
+            assert pg.peak_gemm_run_fused(plan.handle, 1.0, 0, 0, 0.0, 0, bad) == pg.PEAK_ERR_INVALID_ARG
+    assert pg.peak_gemm_run_fused(None, 1.0, 0, 0, 0.0, 0, None) == pg.PEAK_ERR_INVALID_ARG
