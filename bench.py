@@ -50,6 +50,8 @@ def main():
     ap.add_argument("--no-torch", action="store_true", help="skip the torch.matmul context rows")
     ap.add_argument("--variant", default=None, help="force a kernel variant, by id or name (sweeps)")
     ap.add_argument("--split", type=int, default=None, help="force a K split (sweeps)")
+    ap.add_argument("--fused", choices=["gelu", "relu"], default=None,
+                    help="time peak_gemm_run_fused (bias per column + tanh-form GELU or ReLU) instead of peak_gemm_run")
     ap.add_argument("--fast-inputs", action="store_true",
                     help="sweeps only: random device-generated inputs instead of the seeded host generator")
     ap.add_argument("--constant-inputs", action="store_true",
@@ -129,10 +131,20 @@ def main():
             res["plan"] = plan.info()
             ws = torch.empty(max(plan.workspace_bytes, 256), dtype=torch.uint8, device="cuda")
 
+            if args.fused:
+                res["fused"] = "bias per column + " + args.fused
+                act = pg.PEAK_ACT_GELU_TANH if args.fused == "gelu" else pg.PEAK_ACT_RELU
+                dbias = (torch.rand(w.N, device="cuda", dtype=torch.float32) - 0.5)
+
             def step(i):
                 s = i % nset
-                plan.run(w.alpha, dA[s].data_ptr(), dB[s].data_ptr(), w.beta, dC[s].data_ptr(),
-                         ws.data_ptr(), plan.workspace_bytes, stream.cuda_stream)
+                if args.fused:
+                    plan.run_fused(w.alpha, dA[s].data_ptr(), dB[s].data_ptr(), w.beta, dC[s].data_ptr(),
+                                   pg.PEAK_BIAS_PER_COLUMN, dbias.data_ptr(), act,
+                                   ws.data_ptr(), plan.workspace_bytes, stream.cuda_stream)
+                else:
+                    plan.run(w.alpha, dA[s].data_ptr(), dB[s].data_ptr(), w.beta, dC[s].data_ptr(),
+                             ws.data_ptr(), plan.workspace_bytes, stream.cuda_stream)
 
             for i in range(warmup):
                 step(i)

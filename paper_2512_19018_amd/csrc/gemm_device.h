@@ -463,42 +463,51 @@ PEAK_DEV void float_to_elem(void *p, int64_t idx, float x)
     else ((__bf16 *)p)[idx] = (__bf16)x;                             // round to nearest even
 }
 
-// The fused output step on NE consecutive values of row m, from column n on.
+// The fused output step on NE values: v <- act(v + b).
 // (The choices are made outside the element loops, which then unroll.)
 template <int NE>
-PEAK_DEV void hook_apply(const Hook &h, float (&v)[NE], int64_t m, int64_t n)
+PEAK_DEV void hook_apply(int act, bool has_bias, float (&v)[NE], const float (&b)[NE])
 {
-    if (h.bias_kind == BIAS_PER_COLUMN) {
+    if (has_bias) {
 #pragma unroll
-        for (int e = 0; e < NE; ++e) v[e] += h.bias[n + e];
-    } else if (h.bias_kind == BIAS_PER_ROW) {
-        const float b = h.bias[m];
-#pragma unroll
-        for (int e = 0; e < NE; ++e) v[e] += b;
+        for (int e = 0; e < NE; ++e) v[e] += b[e];
     }
-    if (h.act == ACT_RELU) {
+    if (act == ACT_RELU) {
 #pragma unroll
         for (int e = 0; e < NE; ++e) v[e] = v[e] > 0.0f ? v[e] : 0.0f;
-    } else if (h.act == ACT_GELU_TANH) {
-        // v/2 * (1 + tanh(u)) = v / (1 + exp(-2u)),  u = sqrt(2/pi) * (v + 0.044715 v^3)
+    } else if (act == ACT_GELU_TANH) {
+        // v/2 * (1 + tanh(u)) = v / (1 + exp(-2u)),  u = sqrt(2/pi) * (v + 0.044715 v^3);
+        // -2u*log2(e) = v * (c1 + c3 v^2), one hardware exp2 and one hardware reciprocal (1 ulp each)
 #pragma unroll
         for (int e = 0; e < NE; ++e) {
-            const float u = 0.7978845608028654f * (v[e] + 0.044715f * v[e] * v[e] * v[e]);
-            v[e] = v[e] / (1.0f + __expf(-2.0f * u));
+            const float t = v[e] * (-2.302208198f + -0.1029432396f * v[e] * v[e]);
+            v[e] = v[e] * __builtin_amdgcn_rcpf(1.0f + __builtin_amdgcn_exp2f(t));
         }
     }
 }
 
 PEAK_DEV bool hook_active(const Hook &h) { return (h.bias_kind | h.act) != 0; }
 
+// Bias of nvalid (1..4) consecutive outputs of row m, from column n on.
+PEAK_DEV void hook_bias4(const Hook &h, int64_t m, int64_t n, int nvalid, float (&b)[4])
+{
+    b[0] = b[1] = b[2] = b[3] = 0.0f;
+    if (h.bias_kind == BIAS_PER_COLUMN) {
+#pragma unroll
+        for (int e = 0; e < 4; ++e)
+            if (e < nvalid) b[e] = h.bias[n + e];
+    } else if (h.bias_kind == BIAS_PER_ROW) {
+        b[0] = b[1] = b[2] = b[3] = h.bias[m];
+    }
+}
+
 // Stores nvalid (1..4) consecutive elements of one row of C, rounded once:
-// C[idx + e] = hook(alpha * x[e] + beta * C[idx + e]); (m, n) are the row and first
-// column, which only the hook's bias looks at.
+// C[idx + e] = act(alpha * x[e] + beta * C[idx + e] + b[e]); the fused step (act, b)
+// only with `hooked`.
 template <int DT>
 PEAK_DEV void store4(void *C, int64_t idx, const float x[4], float alpha, float beta, bool vec, int nvalid,
-                     const Hook hk = Hook{nullptr, 0, 0}, int64_t m = 0, int64_t n = 0)
+                     bool hooked, int act, bool has_bias, const float (&b)[4])
 {
-    const bool hooked = hook_active(hk);
     if (vec && nvalid == 4) {
         float o[4] = {alpha * x[0], alpha * x[1], alpha * x[2], alpha * x[3]};
         if (DT == DT_F32) {
@@ -506,7 +515,7 @@ PEAK_DEV void store4(void *C, int64_t idx, const float x[4], float alpha, float 
                 const f32x4 c = *(const f32x4 *)((const float *)C + idx);
                 o[0] += beta * c[0]; o[1] += beta * c[1]; o[2] += beta * c[2]; o[3] += beta * c[3];
             }
-            if (hooked) hook_apply(hk, o, m, n);
+            if (hooked) hook_apply(act, has_bias, o, b);
             const f32x4 ov = {o[0], o[1], o[2], o[3]};
             *(f32x4 *)((float *)C + idx) = ov;
         } else {
@@ -514,7 +523,7 @@ PEAK_DEV void store4(void *C, int64_t idx, const float x[4], float alpha, float 
 #pragma unroll
                 for (int e = 0; e < 4; ++e) o[e] += beta * elem_to_float<DT>(C, idx + e);
             }
-            if (hooked) hook_apply(hk, o, m, n);
+            if (hooked) hook_apply(act, has_bias, o, b);
             union { u32x2 u; _Float16 h[4]; __bf16 b[4]; } pk;
 #pragma unroll
             for (int e = 0; e < 4; ++e) {
@@ -527,17 +536,32 @@ PEAK_DEV void store4(void *C, int64_t idx, const float x[4], float alpha, float 
 #pragma unroll
         for (int e = 0; e < 4; ++e) {
             if (e < nvalid) {
-                float o = alpha * x[e];
-                if (beta != 0.0f) o += beta * elem_to_float<DT>(C, idx + e);
-                if (hooked) {
-                    float o1[1] = {o};
-                    hook_apply(hk, o1, m, n + e);
-                    o = o1[0];
-                }
-                float_to_elem<DT>(C, idx + e, o);
+                float o1[1] = {alpha * x[e]};
+                if (beta != 0.0f) o1[0] += beta * elem_to_float<DT>(C, idx + e);
+                const float b1[1] = {b[e]};
+                if (hooked) hook_apply(act, has_bias, o1, b1);
+                float_to_elem<DT>(C, idx + e, o1[0]);
             }
         }
     }
+}
+
+// ... without a fused step (split-K partials)
+template <int DT>
+PEAK_DEV void store4(void *C, int64_t idx, const float x[4], float alpha, float beta, bool vec, int nvalid)
+{
+    const float none[4] = {0.0f, 0.0f, 0.0f, 0.0f};
+    store4<DT>(C, idx, x, alpha, beta, vec, nvalid, false, ACT_NONE, false, none);
+}
+
+// ... with the fused step of `hk` for row m, columns n.. (fetches the bias itself)
+template <int DT>
+PEAK_DEV void store4(void *C, int64_t idx, const float x[4], float alpha, float beta, bool vec, int nvalid,
+                     const Hook hk, int64_t m, int64_t n)
+{
+    float b[4];
+    hook_bias4(hk, m, n, nvalid, b);
+    store4<DT>(C, idx, x, alpha, beta, vec, nvalid, hook_active(hk), hk.act, hk.bias_kind != BIAS_NONE, b);
 }
 
 // Tile order (the paper's Block-Swizzle, made XCD-aware): consecutive workgroup
@@ -1240,7 +1264,6 @@ __global__ __launch_bounds__(C::NT) void gemm_kernel(const GemmArgs p)
     constexpr int SROW = C::WTN * 4 + 16;                              // scratch row stride, bytes
     static_assert(32 * SROW * C::NW <= C::LDS_BYTES, "the staging buffers are large enough for the turnaround");
     {
-        const bool fast = interior && !wsl && (p.flags & GF_C_VEC16) && !hook_active(p.hook);
         lds_barrier();                                                 // nobody still reads the last stage
         char *scr = lds + wave * (32 * SROW);
         constexpr int OUT_ROW = C::WTN * C::ESZ;                       // bytes of one output row of the wave tile
@@ -1248,8 +1271,25 @@ __global__ __launch_bounds__(C::NT) void gemm_kernel(const GemmArgs p)
         constexpr int RPI = 64 / LPR;                                  // rows per store instruction
         static_assert(OUT_ROW % 16 == 0 && 64 % LPR == 0 && 32 % RPI == 0, "wave tile rows split into 16-byte pieces");
         const int orow = lane / LPR, ocol = (lane % LPR) * (16 / C::ESZ);   // row within the group, first column (elements)
+        // fused step: a lane stores the same columns of every row, so their bias is fetched once
+        const bool hooked = !wsl && hook_active(p.hook), has_bias = p.hook.bias_kind != BIAS_NONE;
+        constexpr int EPL = 16 / C::ESZ;                               // elements per lane and row
+        float bcol[EPL];
+#pragma unroll
+        for (int e = 0; e < EPL; ++e) bcol[e] = 0.0f;
+        if (hooked && p.hook.bias_kind == BIAS_PER_COLUMN) {
+            const int64_t n = n0 + wn * C::WTN + ocol;
+#pragma unroll
+            for (int e = 0; e < EPL; ++e)
+                if (n + e < p.N) bcol[e] = p.hook.bias[n + e];
+        }
 #pragma unroll
         for (int mi = 0; mi < C::MI; ++mi) {
+            float brow = 0.0f;                                         // per-row bias of slab row (lane % 32)
+            if (hooked && p.hook.bias_kind == BIAS_PER_ROW) {
+                const int64_t m = m0 + wm * C::WTM + mi * 32 + (lane & 31);
+                if (m < p.M) brow = p.hook.bias[m];
+            }
 #pragma unroll
             for (int ni = 0; ni < C::NI; ++ni)
 #pragma unroll
@@ -1261,14 +1301,15 @@ __global__ __launch_bounds__(C::NT) void gemm_kernel(const GemmArgs p)
                 }
             asm volatile("" ::: "memory");
             __builtin_amdgcn_sched_barrier(0);         // one slab's accumulators out of the accumulation registers at a time
-            if (!fast) {
-                // masked 4-element stores; also the way out for runs with a fused output step
+            if (!(interior && !wsl && (p.flags & GF_C_VEC16))) {
+                // masked 4-element stores
 #pragma unroll 1
                 for (int g = 0; g < 32 / RPI; ++g) {
                     const int row = g * RPI + orow;
                     const int64_t m = m0 + wm * C::WTM + mi * 32 + row;
                     const int64_t n = n0 + wn * C::WTN + ocol;
                     const char *src = scr + row * SROW + ocol * 4;
+                    const float br = __shfl(brow, row);                // (every lane takes part)
                     if (m < p.M) {
 #pragma unroll
                         for (int q = 0; q < 4 / C::ESZ; ++q) {         // 4 elements at a time
@@ -1278,7 +1319,13 @@ __global__ __launch_bounds__(C::NT) void gemm_kernel(const GemmArgs p)
                                 const f32x4 t = *(const f32x4 *)(src + q * 16);
                                 const float x[4] = {t[0], t[1], t[2], t[3]};
                                 if (wsl) store4<DT_F32>(wsl, m * p.N + nn, x, 1.0f, 0.0f, ws_vec, nvalid);
-                                else     store4<C::DT>(p.C, m * p.ldc + nn, x, p.alpha, p.beta, c_vec, nvalid, p.hook, m, nn);
+                                else {
+                                    const bool per_row = p.hook.bias_kind == BIAS_PER_ROW;
+                                    const float b[4] = {per_row ? br : bcol[q * 4 + 0], per_row ? br : bcol[q * 4 + 1],
+                                                        per_row ? br : bcol[q * 4 + 2], per_row ? br : bcol[q * 4 + 3]};
+                                    store4<C::DT>(p.C, m * p.ldc + nn, x, p.alpha, p.beta, c_vec, nvalid,
+                                                  hooked, p.hook.act, has_bias, b);
+                                }
                             }
                         }
                     }
@@ -1290,13 +1337,24 @@ __global__ __launch_bounds__(C::NT) void gemm_kernel(const GemmArgs p)
                     const int64_t m = m0 + wm * C::WTM + mi * 32 + row;
                     const int64_t n = n0 + wn * C::WTN + ocol;
                     const char *src = scr + row * SROW + ocol * 4;
-                    if (C::DT == DT_F32) {
+                    float b[EPL];                                      // this row's bias, if any
+                    if (hooked) {
+                        const float br = __shfl(brow, row);
+#pragma unroll
+                        for (int e = 0; e < EPL; ++e) b[e] = p.hook.bias_kind == BIAS_PER_ROW ? br : bcol[e];
+                    }
+                    if constexpr (C::DT == DT_F32) {
                         f32x4 o = *(const f32x4 *)src;
                         o[0] *= p.alpha; o[1] *= p.alpha; o[2] *= p.alpha; o[3] *= p.alpha;
                         float *dst = (float *)p.C + m * p.ldc + n;
                         if (p.beta != 0.0f) {
                             const f32x4 c = *(const f32x4 *)dst;
                             o[0] += p.beta * c[0]; o[1] += p.beta * c[1]; o[2] += p.beta * c[2]; o[3] += p.beta * c[3];
+                        }
+                        if (hooked) {
+                            float oh[4] = {o[0], o[1], o[2], o[3]};
+                            hook_apply(p.hook.act, has_bias, oh, b);
+                            o[0] = oh[0]; o[1] = oh[1]; o[2] = oh[2]; o[3] = oh[3];
                         }
                         *(f32x4 *)dst = o;
                     } else {
@@ -1310,6 +1368,7 @@ __global__ __launch_bounds__(C::NT) void gemm_kernel(const GemmArgs p)
 #pragma unroll
                             for (int e = 0; e < 8; ++e) o[e] += p.beta * (C::DT == DT_F16 ? (float)pk.h[e] : (float)pk.b[e]);
                         }
+                        if (hooked) hook_apply(p.hook.act, has_bias, o, b);
 #pragma unroll
                         for (int e = 0; e < 8; ++e) {
                             if (C::DT == DT_F16) pk.h[e] = (_Float16)o[e];
@@ -1364,8 +1423,10 @@ __global__ __launch_bounds__(256) void scale_c_kernel(const GemmArgs p)
     float o = 0.0f;
     if (p.beta != 0.0f) o = p.beta * elem_to_float<DT>(p.C, m * p.ldc + n);
     if (hook_active(p.hook)) {
-        float o1[1] = {o};
-        hook_apply(p.hook, o1, m, n);
+        float o1[1] = {o}, b4[4];
+        hook_bias4(p.hook, m, n, 1, b4);
+        const float b1[1] = {b4[0]};
+        hook_apply(p.hook.act, p.hook.bias_kind != BIAS_NONE, o1, b1);
         o = o1[0];
     }
     float_to_elem<DT>(p.C, m * p.ldc + n, o);
