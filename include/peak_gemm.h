@@ -173,7 +173,7 @@ int peak_gemm_variant_count(void);
 const char *peak_gemm_variant_name(int id);
 
 /* Selector table from an offline sweep (the exhaustive search over tuning
- * parameters of the paper's Section 3.4, "performance evaluators": enumerate
+ * parameters of the paper's Section 3.3, "performance evaluators": enumerate
  * the valid parameter settings, time them, keep the best).
  *
  * `path` names a text file in host memory's file system, one entry per line:

@@ -1,6 +1,6 @@
 """Offline exhaustive sweep over the library's kernel variants and K splits.
 
-The paper's "performance evaluators" (Section 3.4) enumerate the valid values
+The paper's "performance evaluators" (Section 3.3) enumerate the valid values
 of a kernel's tuning parameters, time each setting and keep the best; settings
 the kernel context rejects are skipped (Section 3.1, the invalid-configuration
 sentinel).  Here the tuning parameters are the kernel variant (tile, waves,

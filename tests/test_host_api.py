@@ -222,3 +222,34 @@ def test_fused_run_checks_its_epilogue_before_anything_else():
                     pg.PeakGemmEpilogue(None, 0, 3), pg.PeakGemmEpilogue(None, 0, -1)):
             assert pg.peak_gemm_run_fused(plan.handle, 1.0, 0, 0, 0.0, 0, bad) == pg.PEAK_ERR_INVALID_ARG
     assert pg.peak_gemm_run_fused(None, 1.0, 0, 0, 0.0, 0, None) == pg.PEAK_ERR_INVALID_ARG
+
+
+def test_validator_sampling_is_seeded_and_keeps_a_plain_reference():
+    from paper_2512_19018_amd import validate as val
+    from paper_2512_19018_amd.tune import candidates
+    cands = candidates(pg.PEAK_DT_BF16, 0, 1, 300, 520, 1000)
+    assert len(cands) > 20
+    assert val.sample_settings(cands, None) == cands and val.sample_settings(cands, 10 ** 6) == cands
+    a, b = val.sample_settings(cands, 7, seed=1), val.sample_settings(cands, 7, seed=1)
+    assert a == b and len(a) == 7 and len(set(a)) == 7 and all(x in cands for x in a)
+    assert val.sample_settings(cands, 7, seed=2) != a
+    ref = val.reference_setting(cands)
+    assert "_r64x64_" in ref[1] and ref[2] == 1
+
+
+def test_validator_guard_bands_notice_a_stray_write():
+    # on host tensors: the check itself, with the mistake planted by the test
+    import torch
+    from paper_2512_19018_amd import validate as val
+    for tdt, dt in ((torch.float32, pg.PEAK_DT_F32), (torch.bfloat16, pg.PEAK_DT_BF16), (torch.float16, pg.PEAK_DT_F16)):
+        g = val._Guarded(torch, 3, 5, tdt, dt, torch.ones(3, 5, dtype=tdt), device="cpu")
+        assert g.guards_intact()
+        assert bool(torch.isnan(g.buf[:g.g].float()).all()) and bool(torch.isnan(g.buf[g.g + g.n:].float()).all())
+        g.body.fill_(2.0)                         # inside: allowed
+        assert g.guards_intact()
+        g.buf[g.g + g.n] = 1.0                    # first element after the body
+        assert not g.guards_intact()
+        g = val._Guarded(torch, 3, 5, tdt, dt, None, device="cpu")
+        assert bool(torch.isnan(g.body.float()).all())     # unfilled body is poisoned too
+        g.buf[g.g - 1] = 0.0                      # last element before the body
+        assert not g.guards_intact()
