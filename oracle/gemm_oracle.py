@@ -43,6 +43,8 @@ def _load():
             ctypes.c_double, ctypes.c_void_p, ctypes.c_int64,
             ctypes.c_void_p, ctypes.c_int64,
             ctypes.c_void_p, ctypes.c_int, ctypes.c_int]
+        lib.oracle_gemm_c.restype = ctypes.c_int
+        lib.oracle_gemm_c.argtypes = [ctypes.c_int] + lib.oracle_gemm.argtypes
         lib.oracle_bias_act.restype = ctypes.c_int
         lib.oracle_bias_act.argtypes = [ctypes.c_int64, ctypes.c_int64, ctypes.c_void_p, ctypes.c_int64,
                                         ctypes.c_void_p, ctypes.c_int, ctypes.c_void_p, ctypes.c_int]
@@ -78,10 +80,11 @@ def _check_storage(x: np.ndarray, dtype: int, name: str):
 def gemm(dtype: int, transA: int, transB: int, M: int, N: int, K: int,
          alpha: float, A: np.ndarray, B: np.ndarray, beta: float = 0.0,
          Cin: np.ndarray | None = None, rows=None, order: int = -1,
-         threads: int | None = None) -> np.ndarray:
+         threads: int | None = None, cdtype: int | None = None) -> np.ndarray:
     """fp64 reference.  A, B, Cin are the arrays *as stored* (2-D, their row
     length is the leading dimension).  ``rows``: optional list of logical row
-    indices of C; the result then has one row per entry."""
+    indices of C; the result then has one row per entry.  ``cdtype``: storage
+    type of Cin when it differs from that of A and B."""
     lib = _load()
     _check_storage(A, dtype, "A")
     _check_storage(B, dtype, "B")
@@ -89,7 +92,7 @@ def gemm(dtype: int, transA: int, transB: int, M: int, N: int, K: int,
     ldc = 0
     cptr = None
     if Cin is not None:
-        _check_storage(Cin, dtype, "Cin")
+        _check_storage(Cin, dtype if cdtype is None else cdtype, "Cin")
         ldc = Cin.shape[1]
         cptr = Cin.ctypes.data
     a_rows_needed = K if transA else M
@@ -106,7 +109,7 @@ def gemm(dtype: int, transA: int, transB: int, M: int, N: int, K: int,
     ref = np.empty((out_rows, N), dtype=np.float64)
     a32 = float(np.float32(alpha))
     b32 = float(np.float32(beta))
-    rc = lib.oracle_gemm(dtype, int(transA), int(transB), M, N, K,
+    rc = lib.oracle_gemm_c(dtype, dtype if cdtype is None else int(cdtype), int(transA), int(transB), M, N, K,
                          a32, A.ctypes.data, lda, B.ctypes.data, ldb,
                          b32, cptr, ldc, rptr, nrows,
                          ref.ctypes.data, order, threads or default_threads())

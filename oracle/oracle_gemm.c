@@ -93,7 +93,7 @@ static double load_elem(const void *p, int64_t idx, int dtype)
 }
 
 typedef struct {
-    int dtype, transA, transB, order;
+    int dtype, cdtype, transA, transB, order;
     int64_t M, N, K, lda, ldb, ldc;
     double alpha, beta;
     const void *A, *B, *Cin;
@@ -147,7 +147,7 @@ scale:
         for (int64_t j = 0; j < N; ++j) {
             double v = jb->alpha == 0.0 ? 0.0 : jb->alpha * out[j];
             if (jb->beta != 0.0)
-                v += jb->beta * load_elem(jb->Cin, i * jb->ldc + j, jb->dtype);
+                v += jb->beta * load_elem(jb->Cin, i * jb->ldc + j, jb->cdtype);
             out[j] = v;
         }
     }
@@ -162,16 +162,18 @@ scale:
  * rows/nrows: optional subset of logical rows of C to compute (rows == NULL: all M rows,
  * nrows is then ignored).  ref must hold (rows ? nrows : M) * N doubles.
  * alpha and beta are the fp32 scalars of the interface, widened by the caller.
+ * cdtype is the storage type of C_in, which may differ from that of A and B
+ * (16-bit operands with an fp32 C); ldc counts elements of that type.
  */
-int oracle_gemm(int dtype, int transA, int transB,
-                int64_t M, int64_t N, int64_t K,
-                double alpha, const void *A, int64_t lda,
-                const void *B, int64_t ldb,
-                double beta, const void *Cin, int64_t ldc,
-                const int64_t *rows, int64_t nrows,
-                double *ref, int order, int nthreads)
+int oracle_gemm_c(int dtype, int cdtype, int transA, int transB,
+                  int64_t M, int64_t N, int64_t K,
+                  double alpha, const void *A, int64_t lda,
+                  const void *B, int64_t ldb,
+                  double beta, const void *Cin, int64_t ldc,
+                  const int64_t *rows, int64_t nrows,
+                  double *ref, int order, int nthreads)
 {
-    if (dtype < 0 || dtype > 2 || M < 0 || N < 0 || K < 0 || !ref) return 1;
+    if (dtype < 0 || dtype > 2 || cdtype < 0 || cdtype > 2 || M < 0 || N < 0 || K < 0 || !ref) return 1;
     if (lda < (transA ? M : K) || ldb < (transB ? K : N)) return 1;
     if (beta != 0.0 && (!Cin || ldc < N)) return 1;
     if (K > 0 && M > 0 && N > 0 && alpha != 0.0 && (!A || !B)) return 1;
@@ -190,7 +192,7 @@ int oracle_gemm(int dtype, int transA, int transB,
     pthread_t th[256];
     for (int t = 0; t < nthreads; ++t) {
         job_t *jb = &jobs[t];
-        jb->dtype = dtype; jb->transA = transA; jb->transB = transB; jb->order = order;
+        jb->dtype = dtype; jb->cdtype = cdtype; jb->transA = transA; jb->transB = transB; jb->order = order;
         jb->M = M; jb->N = N; jb->K = K; jb->lda = lda; jb->ldb = ldb; jb->ldc = ldc;
         jb->alpha = alpha; jb->beta = beta; jb->A = A; jb->B = B; jb->Cin = Cin;
         jb->rows = rows; jb->nrows = nrows; jb->ref = ref; jb->tid = t; jb->nthreads = nthreads;
@@ -204,6 +206,19 @@ int oracle_gemm(int dtype, int transA, int transB,
     return 0;
 }
 
+
+/* A, B and C_in share one storage type. */
+int oracle_gemm(int dtype, int transA, int transB,
+                int64_t M, int64_t N, int64_t K,
+                double alpha, const void *A, int64_t lda,
+                const void *B, int64_t ldb,
+                double beta, const void *Cin, int64_t ldc,
+                const int64_t *rows, int64_t nrows,
+                double *ref, int order, int nthreads)
+{
+    return oracle_gemm_c(dtype, dtype, transA, transB, M, N, K, alpha, A, lda, B, ldb, beta, Cin, ldc,
+                         rows, nrows, ref, order, nthreads);
+}
 
 enum { OR_BIAS_NONE = 0, OR_BIAS_PER_COLUMN = 1, OR_BIAS_PER_ROW = 2 };
 enum { OR_ACT_NONE = 0, OR_ACT_RELU = 1, OR_ACT_GELU_TANH = 2 };

@@ -349,3 +349,22 @@ def test_bias_act_composes_with_gemm_on_integers(oracle):
         for j in range(N):
             s = 2 * sum(int(a[i, k]) * int(b[k, j]) for k in range(K)) + int(bias[j])
             assert out[i, j] == max(s, 0)
+
+
+def test_c_in_of_another_storage_type(oracle):
+    """16-bit operands with an fp32 C_in: exact integers against the int64 brute force,
+    and a C_in value that only fp32 can hold must arrive unrounded."""
+    M, N, K = 5, 7, 9
+    for dtype in (pi.F16, pi.BF16):
+        A = pi.small_int_matrix(40, 0, M, K, -3, 3, dtype)
+        B = pi.small_int_matrix(40, 1, K, N, -3, 3, dtype)
+        Cin = pi.small_int_matrix(40, 2, M, N + 2, -9, 9, pi.F32)
+        got = oracle.gemm(dtype, 0, 0, M, N, K, 2.0, A, B, -3.0, Cin, cdtype=pi.F32)
+        want = _brute_int(0, 0, M, N, K, 2, _int_values(A, dtype).ravel(), K, _int_values(B, dtype).ravel(), N,
+                          -3, Cin.astype(np.int64).ravel(), N + 2)
+        assert np.array_equal(got, want.astype(np.float64))
+        fine = np.full((M, N), 1.0 + 2.0 ** -20, dtype=np.float32)        # not representable in 16 bits
+        got = oracle.gemm(dtype, 0, 0, M, N, K, 0.0, A, B, 1.0, fine, cdtype=pi.F32)
+        assert np.array_equal(got, fine.astype(np.float64))
+        with pytest.raises(ValueError):
+            oracle.gemm(dtype, 0, 0, M, N, K, 1.0, A, B, 1.0, fine)       # storage check still on
