@@ -29,7 +29,7 @@
 extern "C" {
 #endif
 
-/* Element storage type of A, B and C (they share it).  Section 2.2 names fp32
+/* Element storage type of A, B and C (they share it, unless PEAK_GEMM_C_F32 is set).  Section 2.2 names fp32
  * and fp16; bfloat16 is the third 16-bit storage the graded workloads use. */
 typedef enum {
     PEAK_DT_F32 = 0,
@@ -63,9 +63,14 @@ typedef struct peak_gemm_plan peak_gemm_plan_t;
  * flags: bits 0..7 = 0 lets the selector choose; a non-zero value forces kernel
  * variant number (value - 1) for tests and tuning sweeps (PEAK_ERR_UNSUPPORTED
  * if that variant cannot run the problem).  Bits 8..15 = 0 lets the selector
- * choose the split of K; a non-zero value forces that many K slices.  Other bits
- * must be zero.
+ * choose the split of K; a non-zero value forces that many K slices.
+ * PEAK_GEMM_C_F32 (bit 16): C is stored as fp32 while A and B keep `dtype`
+ * (16-bit operands, full-precision result: the accumulators are fp32 anyway, so
+ * alpha*acc + beta*C is then stored unrounded); ldc counts fp32 elements and C
+ * must be 4-byte aligned.  With dtype == PEAK_DT_F32 the bit changes nothing.
+ * Other bits must be zero.
  */
+#define PEAK_GEMM_C_F32 0x10000u
 typedef struct {
     int64_t M, N, K;
     int64_t lda, ldb, ldc;

@@ -15,6 +15,7 @@ PEAK_DT_F32, PEAK_DT_F16, PEAK_DT_BF16 = 0, 1, 2
 
 PEAK_BIAS_NONE, PEAK_BIAS_PER_COLUMN, PEAK_BIAS_PER_ROW = 0, 1, 2
 PEAK_ACT_NONE, PEAK_ACT_RELU, PEAK_ACT_GELU_TANH = 0, 1, 2
+PEAK_GEMM_C_F32 = 0x10000
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
 _LIB = None
@@ -54,7 +55,7 @@ def load_library():
         lib = ctypes.CDLL(path)
         P = ctypes.c_void_p
         lib.peak_gemm_create.restype = ctypes.c_int
-        lib.peak_gemm_create.argtypes = [ctypes.POINTER(PeakGemmDesc), ctypes.POINTER(P)]
+        lib.peak_gemm_create.argtypes = [P, ctypes.POINTER(P)]
         lib.peak_gemm_workspace_bytes.restype = ctypes.c_size_t
         lib.peak_gemm_workspace_bytes.argtypes = [P]
         lib.peak_gemm_run.restype = ctypes.c_int
@@ -95,9 +96,9 @@ def peak_gemm_load_tuning(path) -> int:
     return load_library().peak_gemm_load_tuning(None if path is None else os.fsencode(path))
 
 
-def force_flags(variant: int | None = None, split: int | None = None) -> int:
-    """Descriptor flags that force a variant id and/or a K split."""
-    f = 0
+def force_flags(variant: int | None = None, split: int | None = None, c_f32: bool = False) -> int:
+    """Descriptor flags that force a variant id and/or a K split, and ask for an fp32 C."""
+    f = PEAK_GEMM_C_F32 if c_f32 else 0
     if variant is not None:
         f |= (variant + 1) & 0xFF
     if split is not None:
@@ -108,7 +109,7 @@ def force_flags(variant: int | None = None, split: int | None = None) -> int:
 def peak_gemm_create(desc: PeakGemmDesc):
     """Returns (status, plan handle or None)."""
     h = ctypes.c_void_p()
-    st = load_library().peak_gemm_create(ctypes.byref(desc), ctypes.byref(h))
+    st = load_library().peak_gemm_create(ctypes.addressof(desc), ctypes.byref(h))
     return st, (h if st == PEAK_OK else None)
 
 

@@ -35,7 +35,8 @@ enum {
     GF_B_VEC = 2,      // B likewise
     GF_C_VEC = 4,      // C rows allow 4-element vector access
     GF_WS_VEC = 8,     // workspace rows (N floats) allow 16-byte access
-    GF_C_VEC16 = 16    // C base and row stride are 16-byte aligned
+    GF_C_VEC16 = 16,   // C base and row stride are 16-byte aligned
+    GF_C_F32 = 32      // C is stored as fp32 although A and B are 16-bit
 };
 
 // Fused output step: v <- act(v + bias), applied to alpha*acc + beta*C in fp32
@@ -1273,6 +1274,7 @@ __global__ __launch_bounds__(C::NT) void gemm_kernel(const GemmArgs p)
         const int orow = lane / LPR, ocol = (lane % LPR) * (16 / C::ESZ);   // row within the group, first column (elements)
         // fused step: a lane stores the same columns of every row, so their bias is fetched once
         const bool hooked = !wsl && hook_active(p.hook), has_bias = p.hook.bias_kind != BIAS_NONE;
+        const bool c_f32 = C::DT != DT_F32 && (p.flags & GF_C_F32);    // fp32 C of a 16-bit kernel: masked readout
         constexpr int EPL = 16 / C::ESZ;                               // elements per lane and row
         float bcol[EPL];
 #pragma unroll
@@ -1301,7 +1303,7 @@ __global__ __launch_bounds__(C::NT) void gemm_kernel(const GemmArgs p)
                 }
             asm volatile("" ::: "memory");
             __builtin_amdgcn_sched_barrier(0);         // one slab's accumulators out of the accumulation registers at a time
-            if (!(interior && !wsl && (p.flags & GF_C_VEC16))) {
+            if (!(interior && !wsl && (p.flags & GF_C_VEC16) && !c_f32)) {
                 // masked 4-element stores
 #pragma unroll 1
                 for (int g = 0; g < 32 / RPI; ++g) {
@@ -1323,8 +1325,12 @@ __global__ __launch_bounds__(C::NT) void gemm_kernel(const GemmArgs p)
                                     const bool per_row = p.hook.bias_kind == BIAS_PER_ROW;
                                     const float b[4] = {per_row ? br : bcol[q * 4 + 0], per_row ? br : bcol[q * 4 + 1],
                                                         per_row ? br : bcol[q * 4 + 2], per_row ? br : bcol[q * 4 + 3]};
-                                    store4<C::DT>(p.C, m * p.ldc + nn, x, p.alpha, p.beta, c_vec, nvalid,
-                                                  hooked, p.hook.act, has_bias, b);
+                                    if (c_f32)
+                                        store4<DT_F32>(p.C, m * p.ldc + nn, x, p.alpha, p.beta, c_vec, nvalid,
+                                                       hooked, p.hook.act, has_bias, b);
+                                    else
+                                        store4<C::DT>(p.C, m * p.ldc + nn, x, p.alpha, p.beta, c_vec, nvalid,
+                                                      hooked, p.hook.act, has_bias, b);
                                 }
                             }
                         }

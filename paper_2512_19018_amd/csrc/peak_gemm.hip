@@ -440,7 +440,7 @@ peak_status_t peak_gemm_create(const peak_gemm_desc_t *desc, peak_gemm_plan_t **
     if (d.M < 0 || d.N < 0 || d.K < 0) return PEAK_ERR_INVALID_ARG;
     if (d.dtype != PEAK_DT_F32 && d.dtype != PEAK_DT_F16 && d.dtype != PEAK_DT_BF16) return PEAK_ERR_INVALID_ARG;
     if ((d.transA != 0 && d.transA != 1) || (d.transB != 0 && d.transB != 1)) return PEAK_ERR_INVALID_ARG;
-    if (d.flags & ~0xFFFFu) return PEAK_ERR_INVALID_ARG;
+    if (d.flags & ~(0xFFFFu | PEAK_GEMM_C_F32)) return PEAK_ERR_INVALID_ARG;
     const int64_t min_lda = d.transA ? d.M : d.K, min_ldb = d.transB ? d.K : d.N;
     if (d.lda < (min_lda > 1 ? min_lda : 1) || d.ldb < (min_ldb > 1 ? min_ldb : 1) || d.ldc < (d.N > 1 ? d.N : 1))
         return PEAK_ERR_INVALID_ARG;
@@ -537,7 +537,9 @@ static peak_status_t run_plan(peak_gemm_plan_t *p, float alpha, const void *A, c
     if (d.M == 0 || d.N == 0) return PEAK_OK;
     if (!C) return PEAK_ERR_INVALID_ARG;
     const int es = esize_of(d.dtype);
-    if ((uintptr_t)C % es) return PEAK_ERR_INVALID_ARG;
+    const int c_dt = (d.flags & PEAK_GEMM_C_F32) ? PEAK_DT_F32 : d.dtype;      // storage type of C
+    const int es_c = esize_of(c_dt);
+    if ((uintptr_t)C % es_c) return PEAK_ERR_INVALID_ARG;
     hipStream_t stream = (hipStream_t)hip_stream;
 
     GemmArgs a;
@@ -548,8 +550,9 @@ static peak_status_t run_plan(peak_gemm_plan_t *p, float alpha, const void *A, c
     a.alpha = alpha; a.beta = beta;
     a.hook = hook;
     a.split = 1;
-    if ((uintptr_t)C % (4 * es) == 0 && (d.ldc * es) % (4 * es) == 0) a.flags |= GF_C_VEC;
-    if ((uintptr_t)C % 16 == 0 && (d.ldc * es) % 16 == 0) a.flags |= GF_C_VEC16;
+    if ((uintptr_t)C % (4 * es_c) == 0 && (d.ldc * es_c) % (4 * es_c) == 0) a.flags |= GF_C_VEC;
+    if ((uintptr_t)C % 16 == 0 && (d.ldc * es_c) % 16 == 0) a.flags |= GF_C_VEC16;
+    if (c_dt != d.dtype) a.flags |= GF_C_F32;
 
     const bool no_product = (d.K == 0 || alpha == 0.0f);
     if (no_product) {
@@ -557,8 +560,8 @@ static peak_status_t run_plan(peak_gemm_plan_t *p, float alpha, const void *A, c
         const int64_t blocks = cdiv(d.M * d.N, 256);
         if (blocks > 0x7FFFFFFF) return PEAK_ERR_UNSUPPORTED;
         dim3 grid((unsigned)blocks);
-        if (d.dtype == PEAK_DT_F32) hipLaunchKernelGGL(scale_c_kernel<DT_F32>, grid, dim3(256), 0, stream, a);
-        else if (d.dtype == PEAK_DT_F16) hipLaunchKernelGGL(scale_c_kernel<DT_F16>, grid, dim3(256), 0, stream, a);
+        if (c_dt == PEAK_DT_F32) hipLaunchKernelGGL(scale_c_kernel<DT_F32>, grid, dim3(256), 0, stream, a);
+        else if (c_dt == PEAK_DT_F16) hipLaunchKernelGGL(scale_c_kernel<DT_F16>, grid, dim3(256), 0, stream, a);
         else hipLaunchKernelGGL(scale_c_kernel<DT_BF16>, grid, dim3(256), 0, stream, a);
         return hipGetLastError() == hipSuccess ? PEAK_OK : PEAK_ERR_HIP;
     }
@@ -596,8 +599,8 @@ static peak_status_t run_plan(peak_gemm_plan_t *p, float alpha, const void *A, c
     if (p->split > 1) {
         const int64_t quads = d.M * cdiv(d.N, 4);
         dim3 rgrid((unsigned)cdiv(quads, 256));
-        if (d.dtype == PEAK_DT_F32) hipLaunchKernelGGL(splitk_reduce_kernel<DT_F32>, rgrid, dim3(256), 0, stream, a);
-        else if (d.dtype == PEAK_DT_F16) hipLaunchKernelGGL(splitk_reduce_kernel<DT_F16>, rgrid, dim3(256), 0, stream, a);
+        if (c_dt == PEAK_DT_F32) hipLaunchKernelGGL(splitk_reduce_kernel<DT_F32>, rgrid, dim3(256), 0, stream, a);
+        else if (c_dt == PEAK_DT_F16) hipLaunchKernelGGL(splitk_reduce_kernel<DT_F16>, rgrid, dim3(256), 0, stream, a);
         else hipLaunchKernelGGL(splitk_reduce_kernel<DT_BF16>, rgrid, dim3(256), 0, stream, a);
         if (hipGetLastError() != hipSuccess) return PEAK_ERR_HIP;
     }

@@ -153,8 +153,12 @@ __global__ __launch_bounds__(C::NT) void skinny_kernel(const GemmArgs p)
         const float x[4] = {acc[0], acc[1], acc[2], acc[3]};
         if (p.split > 1)
             store4<DT_F32>(p.ws + (int64_t)slice * p.M * p.N, m * p.N + n, x, 1.0f, 0.0f, p.flags & GF_WS_VEC, nvalid);
-        else
-            store4<C::DT>(p.C, m * p.ldc + n, x, p.alpha, p.beta, p.flags & GF_C_VEC, nvalid, p.hook, m, n);
+        else {
+            if (p.flags & GF_C_F32)
+                store4<DT_F32>(p.C, m * p.ldc + n, x, p.alpha, p.beta, p.flags & GF_C_VEC, nvalid, p.hook, m, n);
+            else
+                store4<C::DT>(p.C, m * p.ldc + n, x, p.alpha, p.beta, p.flags & GF_C_VEC, nvalid, p.hook, m, n);
+        }
     }
 }
 
@@ -253,8 +257,12 @@ __global__ __launch_bounds__(C::NT) void skinny_reg_kernel(const GemmArgs p)
         const float x[4] = {acc0[0] + acc1[0], acc0[1] + acc1[1], acc0[2] + acc1[2], acc0[3] + acc1[3]};
         if (p.split > 1)
             store4<DT_F32>(p.ws + (int64_t)slice * p.M * p.N, m * p.N + n, x, 1.0f, 0.0f, p.flags & GF_WS_VEC, nvalid);
-        else
-            store4<C::DT>(p.C, m * p.ldc + n, x, p.alpha, p.beta, p.flags & GF_C_VEC, nvalid, p.hook, m, n);
+        else {
+            if (p.flags & GF_C_F32)
+                store4<DT_F32>(p.C, m * p.ldc + n, x, p.alpha, p.beta, p.flags & GF_C_VEC, nvalid, p.hook, m, n);
+            else
+                store4<C::DT>(p.C, m * p.ldc + n, x, p.alpha, p.beta, p.flags & GF_C_VEC, nvalid, p.hook, m, n);
+        }
     }
 }
 

@@ -29,15 +29,21 @@ def nan_fill(rows: int, cols: int, dtype: int) -> np.ndarray:
 
 
 def run_gemm(dtype, transA, transB, M, N, K, alpha, beta, A, B, C0, flags=0, repeat=1, a_off=0, b_off=0,
-             fused=None):
+             fused=None, cdtype=None):
     """A, B, C0: stored host arrays (2-D; row length = leading dimension).  C0 is
     the initial content of C (C_in, or a NaN fill when beta == 0).  ``fused``:
     None for peak_gemm_run, or (bias_kind, fp32 bias array or None, act) for
-    peak_gemm_run_fused.  Returns (C values as fp64 [M, N], raw stored C after
+    peak_gemm_run_fused.  ``cdtype``: storage type of C0 when it is not that of
+    A and B (sets PEAK_GEMM_C_F32).  Returns (C values as fp64 [M, N], raw stored C after
     the run, plan info)."""
     lda, ldb, ldc = A.shape[1], B.shape[1], C0.shape[1]
     dA, dB, dC = to_dev(A), to_dev(B), to_dev(C0)
     stream = torch.cuda.current_stream().cuda_stream
+    if cdtype is not None and cdtype != dtype:
+        assert cdtype == pi.F32
+        flags |= pg.PEAK_GEMM_C_F32
+    else:
+        cdtype = dtype
     with pg.Plan(M, N, K, dtype, transA, transB, lda, ldb, ldc, flags) as plan:
         info = plan.info()
         ws = torch.empty(max(plan.workspace_bytes, 256), dtype=torch.uint8, device="cuda")
@@ -51,8 +57,8 @@ def run_gemm(dtype, transA, transB, M, N, K, alpha, beta, A, B, C0, flags=0, rep
                                fused[0], dbias.data_ptr() if dbias is not None else 0, fused[2],
                                ws.data_ptr(), plan.workspace_bytes, stream)
         torch.cuda.synchronize()
-    raw = from_dev(dC, dtype)
-    vals = pi.to_f64(np.ascontiguousarray(raw[:M, :N]), dtype) if M and N else np.zeros((M, N))
+    raw = from_dev(dC, cdtype)
+    vals = pi.to_f64(np.ascontiguousarray(raw[:M, :N]), cdtype) if M and N else np.zeros((M, N))
     return vals, raw, info
 
 

@@ -253,3 +253,16 @@ def test_validator_guard_bands_notice_a_stray_write():
         assert bool(torch.isnan(g.body.float()).all())     # unfilled body is poisoned too
         g.buf[g.g - 1] = 0.0                      # last element before the body
         assert not g.guards_intact()
+
+
+def test_fp32_c_flag_is_accepted_and_other_high_bits_are_not():
+    st, h = pg.peak_gemm_create(_desc(flags=pg.PEAK_GEMM_C_F32))
+    assert st == pg.PEAK_OK
+    pg.peak_gemm_destroy(h)
+    st, h = pg.peak_gemm_create(_desc(dtype=pg.PEAK_DT_F32, flags=pg.PEAK_GEMM_C_F32))
+    assert st == pg.PEAK_OK
+    pg.peak_gemm_destroy(h)
+    for bad in (0x20000, 0x80000000, pg.PEAK_GEMM_C_F32 | 0x40000):
+        st, h = pg.peak_gemm_create(_desc(flags=bad))
+        assert st == pg.PEAK_ERR_INVALID_ARG and h is None
+    assert pg.force_flags(3, 2, c_f32=True) == (4 | (2 << 8) | pg.PEAK_GEMM_C_F32)
