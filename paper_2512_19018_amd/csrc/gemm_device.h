@@ -1337,52 +1337,65 @@ __global__ __launch_bounds__(C::NT) void gemm_kernel(const GemmArgs p)
                     }
                 }
             } else {
+                // All rows of the slab are fetched from LDS first, so that one LDS latency is
+                // paid per slab and not per row; PLAIN (beta == 0, no fused step) is straight-line.
+                auto vector_readout = [&](auto plain_c) {
+                    constexpr bool PLAIN = decltype(plain_c)::value != 0;
+                    constexpr int G = 32 / RPI;
+                    f32x4 lo[G], hi[G];
 #pragma unroll
-                for (int g = 0; g < 32 / RPI; ++g) {
-                    const int row = g * RPI + orow;
-                    const int64_t m = m0 + wm * C::WTM + mi * 32 + row;
-                    const int64_t n = n0 + wn * C::WTN + ocol;
-                    const char *src = scr + row * SROW + ocol * 4;
-                    float b[EPL];                                      // this row's bias, if any
-                    if (hooked) {
-                        const float br = __shfl(brow, row);
-#pragma unroll
-                        for (int e = 0; e < EPL; ++e) b[e] = p.hook.bias_kind == BIAS_PER_ROW ? br : bcol[e];
+                    for (int g = 0; g < G; ++g) {
+                        const char *src = scr + (g * RPI + orow) * SROW + ocol * 4;
+                        lo[g] = *(const f32x4 *)src;
+                        if constexpr (C::DT != DT_F32) hi[g] = *(const f32x4 *)(src + 16);
                     }
-                    if constexpr (C::DT == DT_F32) {
-                        f32x4 o = *(const f32x4 *)src;
-                        o[0] *= p.alpha; o[1] *= p.alpha; o[2] *= p.alpha; o[3] *= p.alpha;
-                        float *dst = (float *)p.C + m * p.ldc + n;
-                        if (p.beta != 0.0f) {
-                            const f32x4 c = *(const f32x4 *)dst;
-                            o[0] += p.beta * c[0]; o[1] += p.beta * c[1]; o[2] += p.beta * c[2]; o[3] += p.beta * c[3];
-                        }
-                        if (hooked) {
-                            float oh[4] = {o[0], o[1], o[2], o[3]};
-                            hook_apply(p.hook.act, has_bias, oh, b);
-                            o[0] = oh[0]; o[1] = oh[1]; o[2] = oh[2]; o[3] = oh[3];
-                        }
-                        *(f32x4 *)dst = o;
-                    } else {
-                        const f32x4 lo = *(const f32x4 *)src, hi = *(const f32x4 *)(src + 16);
-                        float o[8] = {p.alpha * lo[0], p.alpha * lo[1], p.alpha * lo[2], p.alpha * lo[3],
-                                      p.alpha * hi[0], p.alpha * hi[1], p.alpha * hi[2], p.alpha * hi[3]};
-                        uint16_t *dst = (uint16_t *)p.C + m * p.ldc + n;
-                        union { u32x4 u; _Float16 h[8]; __bf16 b[8]; } pk;
-                        if (p.beta != 0.0f) {
-                            pk.u = *(const u32x4 *)dst;
 #pragma unroll
-                            for (int e = 0; e < 8; ++e) o[e] += p.beta * (C::DT == DT_F16 ? (float)pk.h[e] : (float)pk.b[e]);
-                        }
-                        if (hooked) hook_apply(p.hook.act, has_bias, o, b);
+                    for (int g = 0; g < G; ++g) {
+                        const int row = g * RPI + orow;
+                        const int64_t m = m0 + wm * C::WTM + mi * 32 + row;
+                        const int64_t n = n0 + wn * C::WTN + ocol;
+                        float b[EPL];                                  // this row's bias, if any
+                        if (!PLAIN && hooked) {
+                            const float br = __shfl(brow, row);
 #pragma unroll
-                        for (int e = 0; e < 8; ++e) {
-                            if (C::DT == DT_F16) pk.h[e] = (_Float16)o[e];
-                            else pk.b[e] = (__bf16)o[e];
+                            for (int e = 0; e < EPL; ++e) b[e] = p.hook.bias_kind == BIAS_PER_ROW ? br : bcol[e];
                         }
-                        *(u32x4 *)dst = pk.u;
+                        if constexpr (C::DT == DT_F32) {
+                            f32x4 o = lo[g];
+                            o[0] *= p.alpha; o[1] *= p.alpha; o[2] *= p.alpha; o[3] *= p.alpha;
+                            float *dst = (float *)p.C + m * p.ldc + n;
+                            if (!PLAIN && p.beta != 0.0f) {
+                                const f32x4 c = *(const f32x4 *)dst;
+                                o[0] += p.beta * c[0]; o[1] += p.beta * c[1]; o[2] += p.beta * c[2]; o[3] += p.beta * c[3];
+                            }
+                            if (!PLAIN && hooked) {
+                                float oh[4] = {o[0], o[1], o[2], o[3]};
+                                hook_apply(p.hook.act, has_bias, oh, b);
+                                o[0] = oh[0]; o[1] = oh[1]; o[2] = oh[2]; o[3] = oh[3];
+                            }
+                            *(f32x4 *)dst = o;
+                        } else {
+                            float o[8] = {p.alpha * lo[g][0], p.alpha * lo[g][1], p.alpha * lo[g][2], p.alpha * lo[g][3],
+                                          p.alpha * hi[g][0], p.alpha * hi[g][1], p.alpha * hi[g][2], p.alpha * hi[g][3]};
+                            uint16_t *dst = (uint16_t *)p.C + m * p.ldc + n;
+                            union { u32x4 u; _Float16 h[8]; __bf16 b[8]; } pk;
+                            if (!PLAIN && p.beta != 0.0f) {
+                                pk.u = *(const u32x4 *)dst;
+#pragma unroll
+                                for (int e = 0; e < 8; ++e) o[e] += p.beta * (C::DT == DT_F16 ? (float)pk.h[e] : (float)pk.b[e]);
+                            }
+                            if (!PLAIN && hooked) hook_apply(p.hook.act, has_bias, o, b);
+#pragma unroll
+                            for (int e = 0; e < 8; ++e) {
+                                if (C::DT == DT_F16) pk.h[e] = (_Float16)o[e];
+                                else pk.b[e] = (__bf16)o[e];
+                            }
+                            *(u32x4 *)dst = pk.u;
+                        }
                     }
-                }
+                };
+                if (p.beta == 0.0f && !hooked) vector_readout(IC<1>{});
+                else vector_readout(IC<0>{});
             }
             asm volatile("" ::: "memory");
             __builtin_amdgcn_sched_barrier(0);
