@@ -251,3 +251,35 @@ def test_two_workgroups_per_cu_with_assembly_issued_reads(gu, oracle, dtype):
             err = oracle.rel_frobenius(got[rows], ref)
             assert err <= gu.TOL[dtype], (info, rep, err)
             assert np.isfinite(got).all(), info
+
+
+@pytest.mark.parametrize("dtype", DTYPES)
+def test_more_tiles_than_workgroups(gu, oracle, dtype):
+    """Kernels that hold a CU alone run one workgroup per CU and loop over their tiles.
+    Shapes with more tiles than the chip has CUs (and not a multiple of it), exact
+    integers, checked on sampled rows including the first and last tile rows."""
+    import torch
+    cus = torch.cuda.get_device_properties(0).multi_processor_count
+    M, N, K = 4352 + 40, 4352 + 8, 128                       # 18 x 18 tiles of 256 x 256
+    rows = sorted({0, 1, 255, 256, 2047, 2048, 4351, 4352, M - 1} | {int(x) for x in np.random.default_rng(1).integers(0, M, 16)})
+    for transA, transB in [(0, 1), (0, 0), (1, 0)]:
+        ran = 0
+        A, B, C = _stored(9000 + transA * 2 + transB, dtype, M, N, K, transA, transB, ints=True, amp=1)
+        ref = oracle.gemm(dtype, transA, transB, M, N, K, 1.0, A, B, 2.0, C, rows=rows)
+        for vid, name in gu.variants_for(dtype, transA, transB):
+            try:
+                with gu.pg.Plan(M, N, K, dtype, transA, transB, flags=gu.pg.force_flags(variant=vid, split=1)) as plan:
+                    info = plan.info()
+            except gu.pg.PeakError as e:
+                assert e.status == gu.pg.PEAK_ERR_UNSUPPORTED
+                continue
+            lds = int(re.search(r"lds=(\d+)", info).group(1))
+            grid = int(re.search(r"grid=(\d+)", info).group(1))
+            if "skinny" in name or lds <= 80 * 1024:
+                continue
+            assert grid > cus, info
+            got, raw, info = gu.run_gemm(dtype, transA, transB, M, N, K, 1.0, 2.0, A, B, C,
+                                         flags=gu.pg.force_flags(variant=vid, split=1))
+            assert np.array_equal(got[rows], ref), (name, info)
+            ran += 1
+        assert ran >= 1, (dtype, transA, transB)
