@@ -64,7 +64,6 @@ struct GemmArgs {
     int32_t group_m;          // tile rows per band of the tile order
     int32_t rot_m, rot_n;     // K rotation per tile row / tile column within an XCD's patch of tiles
     uint32_t flags;
-    int32_t nblocks;          // tiles x K slices; a launch may have fewer workgroups than that
     Hook hook;
 };
 
@@ -586,10 +585,10 @@ PEAK_DEV void tile_of_block(int t, int tiles_m, int tiles_n, int group_m, int &t
 }
 
 // ---------------------------------------------------------------------------
-// The GEMM kernel: one output tile (of one K slice) per call of gemm_tile.
+// The GEMM kernel.
 // ---------------------------------------------------------------------------
 template <class C>
-PEAK_DEVM void gemm_tile(const GemmArgs &p, const int bid)
+__global__ __launch_bounds__(C::NT) void gemm_kernel(const GemmArgs p)
 {
 #if defined(__HIP_DEVICE_COMPILE__)   // the host pass only needs the kernel's symbol; the body uses device-only builtins
     __shared__ __attribute__((aligned(1024))) char lds[C::LDS_BYTES];
@@ -600,6 +599,7 @@ PEAK_DEVM void gemm_tile(const GemmArgs &p, const int bid)
     const int r32 = lane & 31, half = lane >> 5;
 
     const int tiles = p.tiles_m * p.tiles_n;
+    const int bid = blockIdx.x;
     const int slice = __builtin_amdgcn_readfirstlane(bid / tiles);
     int tm, tn;
     tile_of_block(bid - slice * tiles, p.tiles_m, p.tiles_n, p.group_m, tm, tn);
@@ -1400,22 +1400,6 @@ PEAK_DEVM void gemm_tile(const GemmArgs &p, const int bid)
             asm volatile("" ::: "memory");
             __builtin_amdgcn_sched_barrier(0);
         }
-    }
-#endif
-}
-
-// Workgroup b works on tiles b, b + gridDim.x, ... (p.nblocks of them).  With as
-// many workgroups as the chip holds at once this is the order the hardware would
-// dispatch them in anyway, minus the wait for a workgroup's stores to drain and
-// for its successor to be launched: the next tile's loads are issued while the
-// stores of the last are still in flight.
-template <class C>
-__global__ __launch_bounds__(C::NT) void gemm_kernel(const GemmArgs p)
-{
-#if defined(__HIP_DEVICE_COMPILE__)
-    for (int bid = blockIdx.x; bid < p.nblocks; bid += gridDim.x) {
-        gemm_tile<C>(p, bid);
-        lds_barrier();                  // the staging buffers double as the epilogue's scratch
     }
 #endif
 }

@@ -529,26 +529,6 @@ int peak_gemm_plan_info(const peak_gemm_plan_t *p, char *buf, size_t n)
                     (long long)p->tiles_m * p->tiles_n * p->split, p->tiles_m, p->tiles_n, p->group_m, p->ws_bytes);
 }
 
-static bool persist_enabled()
-{
-    static const bool on = [] { const char *e = getenv("PEAK_GEMM_PERSIST"); return !(e && e[0] == '0'); }();
-    return on;
-}
-
-// CUs of the current device (0 if the query fails); asked once per device.
-static int cu_count()
-{
-    static int cached[64];
-    int dev = 0;
-    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return 0;
-    if (cached[dev] == 0) {
-        int n = 0;
-        if (hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n <= 0) n = -1;
-        cached[dev] = n;
-    }
-    return cached[dev] > 0 ? cached[dev] : 0;
-}
-
 static peak_status_t run_plan(peak_gemm_plan_t *p, float alpha, const void *A, const void *B, float beta, void *C,
                               const Hook &hook, void *workspace, size_t workspace_bytes, void *hip_stream)
 {
@@ -613,13 +593,6 @@ static peak_status_t run_plan(peak_gemm_plan_t *p, float alpha, const void *A, c
 
     int64_t nblocks = (int64_t)p->tiles_m * p->tiles_n * p->split;
     if (v.kind == KIND_SKINNY_REG) nblocks = cdiv((int64_t)p->tiles_n * p->split, v.nt / 64);   // one wave per row group and slice
-    a.nblocks = (int32_t)nblocks;
-    // Tiled kernels whose LDS leaves room for one workgroup per CU run as many workgroups as
-    // there are CUs, each looping over its tiles (PEAK_GEMM_PERSIST=0: one workgroup per tile).
-    if (v.kind == KIND_TILED && v.lds > LDS_LIMIT / 2 && persist_enabled()) {
-        const int cus = cu_count();
-        if (cus > 0 && nblocks > cus) nblocks = cus;
-    }
     dim3 grid((unsigned)nblocks);
     if (v.launch(a, grid, stream) != hipSuccess) return PEAK_ERR_HIP;
 
