@@ -1285,6 +1285,21 @@ __global__ __launch_bounds__(C::NT) void gemm_kernel(const GemmArgs p)
             for (int e = 0; e < EPL; ++e)
                 if (n + e < p.N) bcol[e] = p.hook.bias[n + e];
         }
+        // (raw accumulators: alpha is applied on the way back, so that accumulators held in
+        // AGPRs can go to LDS without passing through the ordinary registers)
+        auto write_slab = [&](int mi) {
+#pragma unroll
+            for (int ni = 0; ni < C::NI; ++ni)
+#pragma unroll
+                for (int vq = 0; vq < 4; ++vq) {
+                    f32x4 v = {acc[mi][ni][vq * 4 + 0], acc[mi][ni][vq * 4 + 1], acc[mi][ni][vq * 4 + 2], acc[mi][ni][vq * 4 + 3]};
+                    *(f32x4 *)(scr + r32 * SROW + (ni * 32 + vq * 8 + half * 4) * 4) = v;
+                }
+        };
+        // A wave's LDS instructions execute in the order issued, so the next slab may be
+        // written into the same scratch as soon as this slab's reads are issued: the writes
+        // then run while this slab is converted and stored.
+        write_slab(0);
 #pragma unroll
         for (int mi = 0; mi < C::MI; ++mi) {
             float brow = 0.0f;                                         // per-row bias of slab row (lane % 32)
@@ -1292,15 +1307,6 @@ __global__ __launch_bounds__(C::NT) void gemm_kernel(const GemmArgs p)
                 const int64_t m = m0 + wm * C::WTM + mi * 32 + (lane & 31);
                 if (m < p.M) brow = p.hook.bias[m];
             }
-#pragma unroll
-            for (int ni = 0; ni < C::NI; ++ni)
-#pragma unroll
-                for (int vq = 0; vq < 4; ++vq) {
-                    // (raw accumulators: alpha is applied on the way back, so that accumulators held in
-                    // AGPRs can go to LDS without passing through the ordinary registers)
-                    f32x4 v = {acc[mi][ni][vq * 4 + 0], acc[mi][ni][vq * 4 + 1], acc[mi][ni][vq * 4 + 2], acc[mi][ni][vq * 4 + 3]};
-                    *(f32x4 *)(scr + r32 * SROW + (ni * 32 + vq * 8 + half * 4) * 4) = v;
-                }
             asm volatile("" ::: "memory");
             __builtin_amdgcn_sched_barrier(0);         // one slab's accumulators out of the accumulation registers at a time
             if (!(interior && !wsl && (p.flags & GF_C_VEC16) && !c_f32)) {
@@ -1336,6 +1342,7 @@ __global__ __launch_bounds__(C::NT) void gemm_kernel(const GemmArgs p)
                         }
                     }
                 }
+                if (mi + 1 < C::MI) write_slab(mi + 1);
             } else {
                 // All rows of the slab are fetched from LDS first, so that one LDS latency is
                 // paid per slab and not per row; PLAIN (beta == 0, no fused step) is straight-line.
@@ -1349,6 +1356,7 @@ __global__ __launch_bounds__(C::NT) void gemm_kernel(const GemmArgs p)
                         lo[g] = *(const f32x4 *)src;
                         if constexpr (C::DT != DT_F32) hi[g] = *(const f32x4 *)(src + 16);
                     }
+                    if (mi + 1 < C::MI) write_slab(mi + 1);
 #pragma unroll
                     for (int g = 0; g < G; ++g) {
                         const int row = g * RPI + orow;
