@@ -32,7 +32,7 @@ PEAK_HBM_GBS = 8000.0
 # counter reads for a plain 1 GiB device copy (FETCH_SIZE reads half the bytes:
 # factor 2.0; WRITE_SIZE factor 1.0).  Summed over the kernels of one launch.
 # None where not measured.
-MEASURED_TRAFFIC = {"C3": 1.895e9, "C5": 5.423e8, "C2": 8.97e8, "C4": 7.67e8}
+MEASURED_TRAFFIC = {"C3": 1.753e9, "C5": 5.423e8, "C2": 9.21e8, "C4": 7.43e8}
 
 
 def log(*a):
