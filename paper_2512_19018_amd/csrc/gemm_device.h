@@ -1309,7 +1309,10 @@ __global__ __launch_bounds__(C::NT) void gemm_kernel(const GemmArgs p)
             }
             asm volatile("" ::: "memory");
             __builtin_amdgcn_sched_barrier(0);         // one slab's accumulators out of the accumulation registers at a time
-            if (!(interior && !wsl && (p.flags & GF_C_VEC16) && !c_f32)) {
+            // 16-byte stores need aligned rows; on edge tiles also that no lane's column group
+            // straddles N (then a group is either stored whole or not at all)
+            const bool vec_ok = !wsl && (p.flags & GF_C_VEC16) && !c_f32 && (interior || p.N % EPL == 0);
+            if (!vec_ok) {
                 // masked 4-element stores
 #pragma unroll 1
                 for (int g = 0; g < 32 / RPI; ++g) {
@@ -1345,7 +1348,7 @@ __global__ __launch_bounds__(C::NT) void gemm_kernel(const GemmArgs p)
                 if (mi + 1 < C::MI) write_slab(mi + 1);
             } else {
                 // All rows of the slab are fetched from LDS first, so that one LDS latency is
-                // paid per slab and not per row; PLAIN (beta == 0, no fused step) is straight-line.
+                // paid per slab and not per row; PLAIN (interior, beta == 0, no fused step) is straight-line.
                 auto vector_readout = [&](auto plain_c) {
                     constexpr bool PLAIN = decltype(plain_c)::value != 0;
                     constexpr int G = 32 / RPI;
@@ -1363,8 +1366,10 @@ __global__ __launch_bounds__(C::NT) void gemm_kernel(const GemmArgs p)
                         const int64_t m = m0 + wm * C::WTM + mi * 32 + row;
                         const int64_t n = n0 + wn * C::WTN + ocol;
                         float b[EPL];                                  // this row's bias, if any
+                        float br = 0.0f;
+                        if (!PLAIN && hooked) br = __shfl(brow, row);  // (every lane takes part)
+                        if (!PLAIN && !interior && !(m < p.M && n + EPL <= p.N)) continue;
                         if (!PLAIN && hooked) {
-                            const float br = __shfl(brow, row);
 #pragma unroll
                             for (int e = 0; e < EPL; ++e) b[e] = p.hook.bias_kind == BIAS_PER_ROW ? br : bcol[e];
                         }
@@ -1402,7 +1407,7 @@ __global__ __launch_bounds__(C::NT) void gemm_kernel(const GemmArgs p)
                         }
                     }
                 };
-                if (p.beta == 0.0f && !hooked) vector_readout(IC<1>{});
+                if (p.beta == 0.0f && !hooked && interior) vector_readout(IC<1>{});
                 else vector_readout(IC<0>{});
             }
             asm volatile("" ::: "memory");
