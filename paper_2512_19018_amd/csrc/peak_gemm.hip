@@ -273,13 +273,15 @@ static double tiled_cost(const Variant &v, const peak_gemm_desc_t &d, int split)
     const int64_t tiles = cdiv(d.M, v.bm) * cdiv(d.N, v.bn) * split;
     const int64_t rounds = cdiv(tiles, NUM_CU);
     const double ktiles = (double)cdiv(cdiv(d.K, v.bk), split);
-    const double tile_work = (double)v.bm * v.bn * v.bk * ktiles;
+    // one unit = one multiply-add at the 16-bit MFMA rate; an fp32 one takes 16 of them (2500 vs 157 TFLOP/s)
+    const double tile_work = (double)v.bm * v.bn * v.bk * ktiles * (v.dt == DT_F32 ? 16.0 : 1.0);
     // small tiles pay more LDS/L2 traffic per flop; direct loads overlap better.
     // The constants come from the measured sweeps on the graded shapes.
     double eff = 1.0;
     if (v.dt == DT_F32) {                               // fp32 MFMA is slow enough that tile size hardly matters
         if (v.bm * v.bn >= 256 * 128) eff = 0.86;
         else if (v.bm * v.bn >= 128 * 128) eff = 0.95;
+        else if (v.bm * v.bn >= 128 * 64) eff = 0.8;    // as good per multiply-add as 128x128 while few workgroups run
         else eff = 0.5;
     } else {
         if (v.bm * v.bn >= 256 * 256) eff = 1.0;
@@ -303,11 +305,11 @@ static int choose_split(const Variant &v, const peak_gemm_desc_t &d)
 {
     const int64_t tiles = cdiv(d.M, v.bm) * cdiv(d.N, v.bn);
     const int64_t ktiles = cdiv(d.K, v.bk);
-    if (tiles >= NUM_CU / 2 || ktiles < 8) return 1;
+    if (tiles > NUM_CU / 2 || ktiles < 4) return 1;
     int best = 1;
     double best_cost = tiled_cost(v, d, 1);
     for (int s = 2; s <= 16; ++s) {
-        if (ktiles / s < 4) break;
+        if (ktiles / s < 2) break;
         const double c = tiled_cost(v, d, s);
         if (c < best_cost * 0.9) { best_cost = c; best = s; }
     }

@@ -129,13 +129,16 @@ def test_null_epilogue_is_the_plain_run_and_bad_ones_are_rejected(gu, oracle):
     assert np.array_equal(raw0.view(np.uint8), raw1.view(np.uint8))
     dA, dB, dC = gu.to_dev(A), gu.to_dev(B), gu.to_dev(C)
     with pg.Plan(M, N, K, pi.BF16, 0, 1) as plan:
-        st = pg.peak_gemm_run_fused(plan.handle, 1.0, dA.data_ptr(), dB.data_ptr(), 0.5, dC.data_ptr(), None, 0, 0, 0)
+        ws = torch.empty(max(plan.workspace_bytes, 256), dtype=torch.uint8, device="cuda")
+        st = pg.peak_gemm_run_fused(plan.handle, 1.0, dA.data_ptr(), dB.data_ptr(), 0.5, dC.data_ptr(), None,
+                                    ws.data_ptr(), plan.workspace_bytes, 0)
         assert st == pg.PEAK_OK
         torch.cuda.synchronize()
         assert np.array_equal(gu.from_dev(dC, pi.BF16).view(np.uint8), raw0.view(np.uint8))
         for ep in (pg.PeakGemmEpilogue(None, pg.PEAK_BIAS_PER_ROW, 0), pg.PeakGemmEpilogue(None, 3, 0),
                    pg.PeakGemmEpilogue(None, 0, 7), pg.PeakGemmEpilogue(dA.data_ptr() + 2, pg.PEAK_BIAS_PER_COLUMN, 0)):
-            st = pg.peak_gemm_run_fused(plan.handle, 1.0, dA.data_ptr(), dB.data_ptr(), 0.0, dC.data_ptr(), ep, 0, 0, 0)
+            st = pg.peak_gemm_run_fused(plan.handle, 1.0, dA.data_ptr(), dB.data_ptr(), 0.0, dC.data_ptr(), ep,
+                                        ws.data_ptr(), plan.workspace_bytes, 0)
             assert st == pg.PEAK_ERR_INVALID_ARG
 
 
