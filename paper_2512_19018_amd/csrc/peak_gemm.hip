@@ -296,8 +296,11 @@ static double tiled_cost(const Variant &v, const peak_gemm_desc_t &d, int split)
     if (v.atr) eff *= 1.5;                              // likewise A; the alternative is the register-staged general tile
     if (v.dt == DT_F32 && v.ns == 3) eff *= 0.97;
     const double fixed = 12.0e6;                    // prologue + epilogue of one tile, same units
-    // K slices write and re-read fp32 partials: about 9 units per element and slice
-    const double reduce = split > 1 ? 9.0 * (double)split * (double)d.M * (double)d.N : 0.0;
+    // K slices write and re-read fp32 partials: about 9 units per element and slice when they go
+    // through HBM, half of that while the workspace stays in the last-level cache
+    const double ws_bytes = 4.0 * (double)split * (double)d.M * (double)d.N;
+    // ... plus the launch of the reduction kernel (about 3 us)
+    const double reduce = split > 1 ? (ws_bytes <= 64.0e6 ? 4.5 : 9.0) * (double)split * (double)d.M * (double)d.N + 8.0e6 : 0.0;
     return rounds * (tile_work / eff + fixed) + reduce;
 }
 
