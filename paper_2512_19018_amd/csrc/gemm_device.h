@@ -1359,6 +1359,14 @@ __global__ __launch_bounds__(C::NT) void gemm_kernel(const GemmArgs p)
                         lo[g] = *(const f32x4 *)src;
                         if constexpr (C::DT != DT_F32) hi[g] = *(const f32x4 *)(src + 16);
                     }
+                    // per-row bias of the rows this lane stores, handed round (every lane takes part)
+                    // before the next slab's writes queue up behind the shuffles
+                    float brs[G];
+                    const bool per_row = !PLAIN && hooked && p.hook.bias_kind == BIAS_PER_ROW;
+                    if (per_row) {
+#pragma unroll
+                        for (int g = 0; g < G; ++g) brs[g] = __shfl(brow, g * RPI + orow);
+                    }
                     if (mi + 1 < C::MI) write_slab(mi + 1);
 #pragma unroll
                     for (int g = 0; g < G; ++g) {
@@ -1366,12 +1374,10 @@ __global__ __launch_bounds__(C::NT) void gemm_kernel(const GemmArgs p)
                         const int64_t m = m0 + wm * C::WTM + mi * 32 + row;
                         const int64_t n = n0 + wn * C::WTN + ocol;
                         float b[EPL];                                  // this row's bias, if any
-                        float br = 0.0f;
-                        if (!PLAIN && hooked) br = __shfl(brow, row);  // (every lane takes part)
                         if (!PLAIN && !interior && !(m < p.M && n + EPL <= p.N)) continue;
                         if (!PLAIN && hooked) {
 #pragma unroll
-                            for (int e = 0; e < EPL; ++e) b[e] = p.hook.bias_kind == BIAS_PER_ROW ? br : bcol[e];
+                            for (int e = 0; e < EPL; ++e) b[e] = per_row ? brs[g] : bcol[e];
                         }
                         if constexpr (C::DT == DT_F32) {
                             f32x4 o = lo[g];
