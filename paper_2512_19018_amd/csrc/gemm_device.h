@@ -1285,6 +1285,62 @@ __global__ __launch_bounds__(C::NT) void gemm_kernel(const GemmArgs p)
             for (int e = 0; e < EPL; ++e)
                 if (n + e < p.N) bcol[e] = p.hook.bias[n + e];
         }
+        // Plain runs of the 16-bit kernels on interior tiles (beta == 0, no fused step): the slab
+        // goes through LDS already scaled and rounded, 8 bytes per lane and 4-column group, which
+        // halves the LDS traffic of the turnaround; the way back is a 16-byte read and the store.
+        // Rows r and r + 16 would meet in the same banks (row stride = 4 banks mod 64), so the
+        // 8-byte groups of rows 16..31 swap places pairwise; the reader swaps them back.
+        if constexpr (C::DT != DT_F32) {
+            if (interior && !wsl && (p.flags & GF_C_VEC16) && !c_f32 && p.beta == 0.0f && !hooked) {
+                constexpr int SROW16 = C::WTN * 2 + 16;
+                constexpr int G = 32 / RPI;
+                char *scr16 = lds + wave * (32 * SROW16);
+                auto write16 = [&](int mi) {
+#pragma unroll
+                    for (int ni = 0; ni < C::NI; ++ni)
+#pragma unroll
+                        for (int vq = 0; vq < 4; ++vq) {
+                            float x[4];
+#pragma unroll
+                            for (int j = 0; j < 4; ++j) {
+                                if constexpr (C::ACC_AGPR) {
+                                    // copied out of the accumulation registers here, group by group (left to
+                                    // itself the compiler copies all of them ahead of the branch and spills)
+                                    asm volatile("v_accvgpr_read_b32 %0, %1" : "=v"(x[j]) : "a"(acc[mi][ni][vq * 4 + j]));
+                                } else {
+                                    x[j] = acc[mi][ni][vq * 4 + j];
+                                }
+                                x[j] *= p.alpha;
+                            }
+                            union { u32x2 u; _Float16 h[4]; __bf16 b[4]; } pk;
+#pragma unroll
+                            for (int j = 0; j < 4; ++j) {
+                                if (C::DT == DT_F16) pk.h[j] = (_Float16)x[j];
+                                else pk.b[j] = (__bf16)x[j];
+                            }
+                            const int grp = (ni * 8 + vq * 2 + half) ^ (r32 >> 4);
+                            *(u32x2 *)(scr16 + r32 * SROW16 + grp * 8) = pk.u;
+                        }
+                };
+                write16(0);
+#pragma unroll
+                for (int mi = 0; mi < C::MI; ++mi) {
+                    u32x4 v[G];
+#pragma unroll
+                    for (int g = 0; g < G; ++g)
+                        v[g] = *(const u32x4 *)(scr16 + (g * RPI + orow) * SROW16 + ocol * 2);
+                    if (mi + 1 < C::MI) write16(mi + 1);      // in-order LDS: lands after the reads above
+#pragma unroll
+                    for (int g = 0; g < G; ++g) {
+                        const int64_t m = m0 + wm * C::WTM + mi * 32 + g * RPI + orow;
+                        const int64_t n = n0 + wn * C::WTN + ocol;
+                        const u32x4 o = (((g * RPI) >> 4) & 1) ? u32x4{v[g][2], v[g][3], v[g][0], v[g][1]} : v[g];
+                        *(u32x4 *)((uint16_t *)p.C + m * p.ldc + n) = o;
+                    }
+                }
+                return;
+            }
+        }
         // (raw accumulators: alpha is applied on the way back, so that accumulators held in
         // AGPRs can go to LDS without passing through the ordinary registers)
         auto write_slab = [&](int mi) {
