@@ -266,3 +266,11 @@ def test_fp32_c_flag_is_accepted_and_other_high_bits_are_not():
         st, h = pg.peak_gemm_create(_desc(flags=bad))
         assert st == pg.PEAK_ERR_INVALID_ARG and h is None
     assert pg.force_flags(3, 2, c_f32=True) == (4 | (2 << 8) | pg.PEAK_GEMM_C_F32)
+
+
+def test_bench_refuses_more_than_one_gpu():
+    import subprocess
+    import sys
+    r = subprocess.run([sys.executable, os.path.join(ROOT, "bench.py"), "--gpus", "2"], capture_output=True, text=True, timeout=120)
+    assert r.returncode != 0
+    assert "one GPU" in r.stderr and r.stdout.strip() == ""
