@@ -148,6 +148,8 @@ struct Cfg {
     static constexpr bool A_TR = ATR_;
     static_assert(!ATR_ || (DIRECT_ && A_T_ && RB_ == 128 && AX_ == 0 && !PP_), "A kept as [k][m] rows in LDS: A stored K x M, direct");
     static_assert(!TR_ || (DIRECT_ && B_T_ && (!A_T_ || ATR_) && RB_ == 128), "B kept as [k][n] rows in LDS: B stored K x N, direct");
+    // the chunk swizzle of the 16-bit [k][n] and [k][m] rows moves a chunk by up to 12 places within its row
+    static_assert(DT_ == DT_F32 || ((!TR_ || BN_ >= 128) && (!ATR_ || BM_ >= 128)), "16-bit rows kept as [k][n] need at least 16 chunks");
     static constexpr int A_BYTES = BM_ * RB_;
     static constexpr int B_BYTES = BN_ * RB_;
     // LDS: NSA stages of the A tile, then NSB stages of the B tile.  AX extra A

@@ -206,6 +206,10 @@ static const Variant g_variants[] = {
     // ... or straight into registers (no LDS, no barriers)
     SKINNY_REG("bf16_skinnyreg_d8_nt", DT_BF16, 8, 4),
     SKINNY_REG("f16_skinnyreg_d8_nt", DT_F16, 8, 4),
+
+    // 16-bit 128x64 tiles (48 KB of LDS: three workgroups share a CU) for problems with few tiles
+    TILED("bf16_d128x64w4_nt", DT_BF16, 128, 64, 128, 2, 2, 2, false, false, true),
+    TILED("f16_d128x64w4_nt", DT_F16, 128, 64, 128, 2, 2, 2, false, false, true),
 };
 constexpr int NUM_VARIANTS = (int)(sizeof(g_variants) / sizeof(g_variants[0]));
 
@@ -287,6 +291,7 @@ static double tiled_cost(const Variant &v, const peak_gemm_desc_t &d, int split)
         if (v.bm * v.bn >= 256 * 256) eff = 1.0;
         else if (v.bm * v.bn >= 256 * 128) eff = 0.85;
         else if (v.bm * v.bn >= 128 * 128) eff = 0.85;   // 64 KB of LDS: two workgroups share a CU
+        else if (v.bm * v.bn >= 128 * 64 && v.direct) eff = 0.7;   // 48 KB: three; ahead while the tiles are few
         else eff = 0.3;
     }
     if (!v.direct) eff *= 0.7;
