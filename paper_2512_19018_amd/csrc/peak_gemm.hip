@@ -210,6 +210,9 @@ static const Variant g_variants[] = {
     // 16-bit 128x64 tiles (48 KB of LDS: three workgroups share a CU) for problems with few tiles
     TILED("bf16_d128x64w4_nt", DT_BF16, 128, 64, 128, 2, 2, 2, false, false, true),
     TILED("f16_d128x64w4_nt", DT_F16, 128, 64, 128, 2, 2, 2, false, false, true),
+    // ... and with B kept as [k][n] rows (which need 128 columns): 64x128
+    TILED_TR("bf16_t64x128w4_nn", DT_BF16, 64, 128, 128, 2, 2, 2),
+    TILED_TR("f16_t64x128w4_nn", DT_F16, 64, 128, 128, 2, 2, 2),
 };
 constexpr int NUM_VARIANTS = (int)(sizeof(g_variants) / sizeof(g_variants[0]));
 
@@ -319,7 +322,7 @@ static int choose_split(const Variant &v, const peak_gemm_desc_t &d)
     for (int s = 2; s <= 16; ++s) {
         if (ktiles / s < 2) break;
         const double c = tiled_cost(v, d, s);
-        if (c < best_cost * 0.9) { best_cost = c; best = s; }
+        if (c < best_cost * 0.95) { best_cost = c; best = s; }
     }
     return best;
 }
