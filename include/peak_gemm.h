@@ -75,14 +75,19 @@ typedef struct {
     int64_t M, N, K;
     int64_t lda, ldb, ldc;
     int32_t transA, transB;
-    int32_t dtype;              /* a peak_dtype_t value */
+    int32_t dtype;              /* a peak_dtype_t value; a fixed-width field, because the size of an enum type
+                                   is the compiler's choice and this struct is read by ctypes and other ABIs */
     uint32_t flags;
 } peak_gemm_desc_t;
 
 /*
  * Validates the description, chooses the kernel variant, tile shape, split of
  * K, grid and workspace size (Section 3.1: tuning parameters and execution
- * parameters; Section 2.2: t_m, t_n, t_k, w_m, w_n).  Touches no device.
+ * parameters; Section 2.2: t_m, t_n, t_k, w_m, w_n).  A shape listed in the
+ * selector table (see peak_gemm_load_tuning) gets the table's variant and split,
+ * any other the cost model's.  Launches nothing and allocates nothing on the
+ * device; the first call reads the compute-unit count of the current device, if
+ * there is one (else, or with PEAK_GEMM_NUM_CU set, that value or 256 is used).
  * On success *out_plan is a new plan; on any error *out_plan is NULL.
  * Degenerate sizes (M, N or K equal to 0) are valid.
  */
@@ -96,7 +101,19 @@ size_t peak_gemm_workspace_bytes(const peak_gemm_plan_t *plan);
 /*
  * Enqueues C = alpha*op(A)*op(B) + beta*C on `hip_stream` (a hipStream_t
  * passed as void*; NULL = the default stream) and returns without waiting.
+ * This is the kernel execution of Section 3.1 (the driver runs the kernel on
+ * given inputs with given execution parameters) for the MatMul of Section 2.2;
+ * the steps it runs are the transformed kernel of Section 4.1, Table 2: tile
+ * order (Block-Swizzle), staging into LDS (Pipelining, Register-Staging,
+ * Transpose, Offset), MFMA tiles (Tensor-Core, Warp-Tiling, Tensor-Tiling),
+ * K slices and their ordered sum (Split-K), output.
  *
+ *   A, B         need element alignment only.  Plans are made from the leading
+ *                dimensions; when those suit the 16-byte copies of the fast
+ *                kernels but a base address does not (a view one element into
+ *                a larger matrix), the run uses the plan's register-staged
+ *                stand-in variant (named after "unaligned=" by
+ *                peak_gemm_plan_info): same result within the tolerance, slower.
  *   A, B, C      device pointers, aligned to the element size; C must not
  *                overlap A or B.  With beta == 0 C is write-only: whatever it
  *                holds, NaN included, does not reach the result.  With
@@ -117,10 +134,10 @@ peak_status_t peak_gemm_run(peak_gemm_plan_t *plan, float alpha,
                             void *hip_stream);
 
 /*
- * Fused output step.  Section 1.2 argues for a MatMul that stays open to
- * incremental modifications "such as those done in kernel fusion" (and the
- * Limitations paragraph of Section 3.1 names fusion as the case a single-kernel
- * optimiser meets ready-made); this is that slot.  With an epilogue the run
+ * Fused output step.  Section 1.2 wants an optimised MatMul to stay open to
+ * small later changes and gives kernel fusion as the example (the Limitations
+ * paragraph of Section 3.1 names fusion as the case a single-kernel optimiser
+ * meets ready-made); this is that slot.  With an epilogue the run
  * computes, in fp32 and before the one rounding to the storage type,
  *
  *      C = act( alpha * op(A) * op(B) + beta * C + bias )
@@ -159,21 +176,28 @@ peak_status_t peak_gemm_run_fused(peak_gemm_plan_t *plan, float alpha,
                                   void *workspace, size_t workspace_bytes,
                                   void *hip_stream);
 
-/* Frees the plan (host memory only).  NULL is accepted. */
+/* Frees the plan made by peak_gemm_create (host memory only; the kernel context of Section 3.1 owns nothing
+ * on the device).  NULL is accepted.  Always PEAK_OK. */
 peak_status_t peak_gemm_destroy(peak_gemm_plan_t *plan);
 
-/* Static, NUL-terminated description of a status code. */
+/* Static, NUL-terminated description of a status code (PEAK_ERR_UNSUPPORTED is the "invalid configuration"
+ * sentinel of Section 3.1; the others are the argument checks that section's input validation stands for). */
 const char *peak_status_string(peak_status_t s);
 
 /*
- * Writes a one-line, NUL-terminated description of the plan (variant name,
- * tile, waves, stages, K split, grid, LDS bytes, workspace) into buf and
- * returns the length it would need (like snprintf).  For logs and the bench.
+ * Writes a one-line, NUL-terminated description of the plan into buf and
+ * returns the length it would need (like snprintf): the values chosen for the
+ * tuning and execution parameters of Section 3.1 (variant name, tile t_m x t_n x
+ * t_k of Section 2.2, threads, stages, K split, grid, tile order band, LDS
+ * bytes, workspace, and the stand-in variant for unaligned operand bases).  For
+ * logs, the bench and the tests.
  */
 int peak_gemm_plan_info(const peak_gemm_plan_t *plan, char *buf, size_t n);
 
 /* Number of kernel variants the library holds, and the name of variant `id`
- * (NULL if out of range).  Variant ids are what `flags` bits 0..7 force. */
+ * (NULL if out of range).  Variant ids are what `flags` bits 0..7 force.  The
+ * variants are the points of the tuning-parameter space of Section 3.1 that the
+ * library was built with; enumerating them is what the sweep of Section 3.3 needs. */
 int peak_gemm_variant_count(void);
 const char *peak_gemm_variant_name(int id);
 
@@ -190,8 +214,11 @@ const char *peak_gemm_variant_name(int id);
  * model decides as before.  The table replaces any table loaded earlier;
  * path == NULL clears it.  Returns the number of entries now held, or -1 if
  * the file cannot be read or a line is malformed or names an unknown variant
- * (the previous table is then kept).  The file named by the environment
- * variable PEAK_GEMM_TUNING, if set, is loaded at the first peak_gemm_create().
+ * (the previous table is then kept).  Unless this function was called first,
+ * the first peak_gemm_create() loads the file named by the environment variable
+ * PEAK_GEMM_TUNING, or, when that is unset, the table that ships with the
+ * library (peak_gemm_tuning.txt beside the shared object); PEAK_GEMM_TUNING set
+ * to the empty string turns both off.
  * Not thread-safe against concurrent peak_gemm_create() calls. */
 int peak_gemm_load_tuning(const char *path);
 

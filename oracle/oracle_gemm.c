@@ -36,9 +36,9 @@
  * numpy's fp64 product, and the element decoders against numpy/torch for
  * all 65536 bit patterns.
  *
- * oracle_bias_act is the fused output step some callers ask for (the kind of
- * incremental modification "such as those done in kernel fusion" that Section
- * 1.2 wants a MatMul to stay open to): ref <- act(ref + bias), in fp64, applied
+ * oracle_bias_act is the fused output step some callers ask for (kernel fusion
+ * is the example Section 1.2 gives of the small changes an optimised MatMul has
+ * to stay open to): ref <- act(ref + bias), in fp64, applied
  * to the finished alpha*op(A)*op(B) + beta*C_in.  Pins: hand cases where the
  * order of bias and activation matters, row- against column-bias on a
  * non-square zero product, row subsets, torch's fp64 tanh-form GELU, the

@@ -1,7 +1,7 @@
 """MI355X (gfx950) dense GEMM, C = alpha*op(A)*op(B) + beta*C, behind a C ABI.
 
 The arithmetic lives in the HIP library ``libpeak_gemm.so`` (see
-``include/peak_gemm.h``); this package only marshals arguments.  There is no
+``include/peak_gemm.h`` and ``include/peak_calib.h``); this package only marshals arguments.  There is no
 CPU fallback: if the library is not built, importing the binding raises.
 """
 from .binding import (  # noqa: F401
@@ -11,5 +11,5 @@ from .binding import (  # noqa: F401
     PeakGemmDesc, PeakGemmEpilogue, PeakError, lib_path, load_library,
     peak_gemm_create, peak_gemm_workspace_bytes, peak_gemm_run, peak_gemm_run_fused, peak_gemm_destroy,
     peak_status_string, peak_gemm_plan_info, peak_gemm_variant_count, peak_gemm_variant_name,
-    peak_gemm_load_tuning, force_flags, Plan,
+    peak_gemm_load_tuning, peak_calib_mfma, peak_calib_read, force_flags, Plan,
 )

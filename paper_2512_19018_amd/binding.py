@@ -74,6 +74,10 @@ def load_library():
         lib.peak_gemm_variant_name.argtypes = [ctypes.c_int]
         lib.peak_gemm_load_tuning.restype = ctypes.c_int
         lib.peak_gemm_load_tuning.argtypes = [ctypes.c_char_p]
+        lib.peak_calib_mfma.restype = ctypes.c_int
+        lib.peak_calib_mfma.argtypes = [ctypes.c_int32, ctypes.c_int32, ctypes.c_int32, P, P, ctypes.POINTER(ctypes.c_double)]
+        lib.peak_calib_read.restype = ctypes.c_int
+        lib.peak_calib_read.argtypes = [P, ctypes.c_size_t, P, P]
         _LIB = lib
     return _LIB
 
@@ -130,6 +134,19 @@ def peak_gemm_run_fused(plan, alpha: float, A: int, B: int, beta: float, C: int,
     ep = ctypes.addressof(epilogue) if epilogue is not None else None     # host struct, read during the call
     return load_library().peak_gemm_run_fused(plan, float(alpha), A or None, B or None, float(beta), C or None, ep,
                                               workspace or None, int(workspace_bytes), stream or None)
+
+
+def peak_calib_mfma(dtype: int, random_operands: bool, iters: int, out_dev: int, stream: int = 0):
+    """include/peak_calib.h: enqueues the MFMA-only loop; returns (status, flops of one launch)."""
+    flops = ctypes.c_double(0.0)
+    st = load_library().peak_calib_mfma(int(dtype), 1 if random_operands else 0, int(iters), out_dev or None,
+                                        stream or None, ctypes.byref(flops))
+    return st, flops.value
+
+
+def peak_calib_read(src_dev: int, nbytes: int, out_dev: int, stream: int = 0) -> int:
+    """include/peak_calib.h: enqueues the read-only stream over [src_dev, src_dev + nbytes)."""
+    return load_library().peak_calib_read(src_dev or None, int(nbytes), out_dev or None, stream or None)
 
 
 def peak_gemm_destroy(plan) -> int:

@@ -10,232 +10,70 @@
 #include <new>
 #include <vector>
 
+#include <dlfcn.h>
+
+#include <mutex>
+#include <string>
+
 #include "gemm_device.h"
 #include "skinny_device.h"
+#include "variant.h"
 
 namespace peak {
 
-constexpr int NUM_CU = 256;           // MI355X
 constexpr int LDS_LIMIT = 160 * 1024; // bytes per workgroup on gfx950
 
-typedef hipError_t (*launch_fn)(const GemmArgs &, dim3 grid, hipStream_t);
-
-template <class C>
-static hipError_t launch_gemm(const GemmArgs &a, dim3 grid, hipStream_t s)
+// The variant table: the groups of the other translation units, joined in a fixed order.
+static const std::vector<Variant> &variants()
 {
-    hipLaunchKernelGGL((gemm_kernel<C>), grid, dim3(C::NT), 0, s, a);
-    return hipGetLastError();
+    static const std::vector<Variant> table = [] {
+        std::vector<Variant> t;
+        const VariantGroup groups[] = {variants_general(), variants_bf16_nt(), variants_f16_nt(), variants_bf16_nn(),
+                                       variants_f16_nn(),  variants_f32(),     variants_ta(),     variants_skinny()};
+        for (const VariantGroup &g : groups) t.insert(t.end(), g.rows, g.rows + g.count);
+        return t;
+    }();
+    return table;
 }
+#define g_variants (variants())
+#define NUM_VARIANTS ((int)variants().size())
 
-template <class C>
-static hipError_t launch_skinny(const GemmArgs &a, dim3 grid, hipStream_t s)
+// Compute units of the device the plans are made for: PEAK_GEMM_NUM_CU, else the
+// current device's count, else (no device visible) that of the MI355X.
+static int num_cu()
 {
-    hipLaunchKernelGGL((skinny_kernel<C>), grid, dim3(C::NT), 0, s, a);
-    return hipGetLastError();
-}
-
-template <class C>
-static hipError_t launch_skinny_reg(const GemmArgs &a, dim3 grid, hipStream_t s)
-{
-    hipLaunchKernelGGL((skinny_reg_kernel<C>), grid, dim3(C::NT), 0, s, a);
-    return hipGetLastError();
-}
-
-enum Kind { KIND_TILED = 0, KIND_SKINNY = 1, KIND_SKINNY_REG = 2 };
-
-struct Variant {
-    const char *name;
-    int kind;
-    int dt;
-    int a_t, b_t;        // operand layouts the kernel was built for (1: stored K rows x M/N)
-    int direct;          // needs 16-byte aligned operand rows (tiled: K a whole number of 16-byte chunks; skinny: K % BK == 0)
-    int bm, bn, bk, nt, ns, lds;
-    int max_m;           // skinny kernels: largest M
-    launch_fn launch;
-    int tr;              // B (K x N) goes to LDS untransposed ([k][n] rows)
-    int atr;             // A (K x M) goes to LDS untransposed ([k][m] rows)
-};
-
-#define TILED(NAME, DT, BM, BN, RB, WMW, WNW, NS, AT, BT, DIR)                                         \
-    {NAME, KIND_TILED, DT, AT, BT, DIR, BM, BN, RB / (DT == DT_F32 ? 4 : 2), WMW * WNW * 64, NS,       \
-     Cfg<DT, BM, BN, RB, WMW, WNW, NS, AT, BT, DIR>::LDS_BYTES, 0,                                     \
-     &launch_gemm<Cfg<DT, BM, BN, RB, WMW, WNW, NS, AT, BT, DIR>>}
-
-#define TILED_AX(NAME, DT, BM, BN, RB, WMW, WNW, NS, AX)                                              \
-    {NAME, KIND_TILED, DT, 0, 0, 1, BM, BN, RB / (DT == DT_F32 ? 4 : 2), WMW * WNW * 64, NS,           \
-     Cfg<DT, BM, BN, RB, WMW, WNW, NS, false, false, true, AX>::LDS_BYTES, 0,                          \
-     &launch_gemm<Cfg<DT, BM, BN, RB, WMW, WNW, NS, false, false, true, AX>>}
-
-#define TILED_AX_TR(NAME, DT, BM, BN, RB, WMW, WNW, NS, AX)                                           \
-    {NAME, KIND_TILED, DT, 0, 1, 1, BM, BN, RB / (DT == DT_F32 ? 4 : 2), WMW * WNW * 64, NS,           \
-     Cfg<DT, BM, BN, RB, WMW, WNW, NS, false, true, true, AX, true>::LDS_BYTES, 0,                     \
-     &launch_gemm<Cfg<DT, BM, BN, RB, WMW, WNW, NS, false, true, true, AX, true>>, 1}
-
-#define TILED_TR(NAME, DT, BM, BN, RB, WMW, WNW, NS)                                                   \
-    {NAME, KIND_TILED, DT, 0, 1, 1, BM, BN, RB / (DT == DT_F32 ? 4 : 2), WMW * WNW * 64, NS,                                \
-     Cfg<DT, BM, BN, RB, WMW, WNW, NS, false, true, true, 0, true>::LDS_BYTES, 0,                      \
-     &launch_gemm<Cfg<DT, BM, BN, RB, WMW, WNW, NS, false, true, true, 0, true>>, 1}
-
-// A stored K x M staged directly as [k][m] rows; B either along K ("_tt") or [k][n] rows as well ("_tn")
-#define TILED_ATR(NAME, DT, BM, BN, RB, WMW, WNW, NS, BTR)                                             \
-    {NAME, KIND_TILED, DT, 1, BTR, 1, BM, BN, RB / (DT == DT_F32 ? 4 : 2), WMW * WNW * 64, NS,         \
-     Cfg<DT, BM, BN, RB, WMW, WNW, NS, true, BTR != 0, true, 0, BTR != 0, false, true>::LDS_BYTES, 0,  \
-     &launch_gemm<Cfg<DT, BM, BN, RB, WMW, WNW, NS, true, BTR != 0, true, 0, BTR != 0, false, true>>, BTR, 1}
-
-#define TILED_PP(NAME, DT, BM, BN, RB, WMW, WNW, NS, TR)                                              \
-    {NAME, KIND_TILED, DT, 0, TR, 1, BM, BN, RB / (DT == DT_F32 ? 4 : 2), WMW * WNW * 64, NS,          \
-     Cfg<DT, BM, BN, RB, WMW, WNW, NS, false, TR != 0, true, 0, TR != 0, true>::LDS_BYTES, 0,          \
-     &launch_gemm<Cfg<DT, BM, BN, RB, WMW, WNW, NS, false, TR != 0, true, 0, TR != 0, true>>, TR}
-
-#define TILED_LAYOUTS(NAME, DT, BM, BN, RB, WMW, WNW, NS)                                              \
-    TILED(NAME "_nt", DT, BM, BN, RB, WMW, WNW, NS, false, false, false),                             \
-    TILED(NAME "_nn", DT, BM, BN, RB, WMW, WNW, NS, false, true, false),                              \
-    TILED(NAME "_tt", DT, BM, BN, RB, WMW, WNW, NS, true, false, false),                              \
-    TILED(NAME "_tn", DT, BM, BN, RB, WMW, WNW, NS, true, true, false)
-
-#define SKINNY(NAME, DT, BN, KSTEP, NS)                                                                \
-    {NAME, KIND_SKINNY, DT, 0, 0, 1, 16, BN, KSTEP, SkinnyCfg<DT, BN, KSTEP, NS>::NT, NS,              \
-     SkinnyCfg<DT, BN, KSTEP, NS>::LDS_BYTES, 16, &launch_skinny<SkinnyCfg<DT, BN, KSTEP, NS>>}
-
-#define SKINNY_REG(NAME, DT, DEPTH, WAVES)                                                             \
-    {NAME, KIND_SKINNY_REG, DT, 0, 0, 1, 16, 16, 64, WAVES * 64, DEPTH, 0, 16,                         \
-     &launch_skinny_reg<SkinnyRegCfg<DT, DEPTH, WAVES>>}
-
-// Layout suffix: first letter is A (n: runs along K, t: stored K x M), second is
-// B as stored (t: N x K, runs along K; n: K x N).  So "_nt" is transA=0,
-// transB=1: both operands K-contiguous.
-static const Variant g_variants[] = {
-    // register-staged tiles: any alignment, any K, all four layouts
-    TILED_LAYOUTS("f32_r128x128", DT_F32, 128, 128, 128, 2, 2, 2),
-    TILED_LAYOUTS("f16_r128x128", DT_F16, 128, 128, 128, 2, 2, 2),
-    TILED_LAYOUTS("bf16_r128x128", DT_BF16, 128, 128, 128, 2, 2, 2),
-    TILED_LAYOUTS("f32_r64x64", DT_F32, 64, 64, 128, 2, 2, 2),
-    TILED_LAYOUTS("f16_r64x64", DT_F16, 64, 64, 128, 2, 2, 2),
-    TILED_LAYOUTS("bf16_r64x64", DT_BF16, 64, 64, 128, 2, 2, 2),
-
-    // 16-bit, both operands along K ("_nt"): direct-to-LDS, two 64-deep stages
-    TILED("bf16_d256x256w8_nt", DT_BF16, 256, 256, 128, 2, 4, 2, false, false, true),
-    TILED("f16_d256x256w8_nt", DT_F16, 256, 256, 128, 2, 4, 2, false, false, true),
-    TILED("bf16_d128x256w8_nt", DT_BF16, 128, 256, 128, 2, 4, 2, false, false, true),
-    TILED("f16_d128x256w8_nt", DT_F16, 128, 256, 128, 2, 4, 2, false, false, true),
-    TILED("bf16_d128x128w4_nt", DT_BF16, 128, 128, 128, 2, 2, 2, false, false, true),
-    TILED("f16_d128x128w4_nt", DT_F16, 128, 128, 128, 2, 2, 2, false, false, true),
-    // one wave per SIMD, 128x128 per wave, accumulators in AGPRs
-    TILED("bf16_d256x256w4_nt", DT_BF16, 256, 256, 128, 2, 2, 2, false, false, true),
-    TILED("f16_d256x256w4_nt", DT_F16, 256, 256, 128, 2, 2, 2, false, false, true),
-    TILED_AX("bf16_d256x256w4a3_nt", DT_BF16, 256, 256, 128, 2, 2, 2, 1),
-    TILED_AX("f16_d256x256w4a3_nt", DT_F16, 256, 256, 128, 2, 2, 2, 1),
-    // three stages
-    TILED("bf16_d256x128w8_nt", DT_BF16, 256, 128, 128, 4, 2, 3, false, false, true),
-    TILED("f16_d256x128w8_nt", DT_F16, 256, 128, 128, 4, 2, 3, false, false, true),
-    // 32-deep K tiles in a ring of 4 or 5 with the run-ahead loop; 8 waves or 4 (one per SIMD)
-    TILED("bf16_d256x256w8k32s4_nt", DT_BF16, 256, 256, 64, 2, 4, 4, false, false, true),
-    TILED("f16_d256x256w8k32s4_nt", DT_F16, 256, 256, 64, 2, 4, 4, false, false, true),
-    TILED("bf16_d256x256w8k32s5_nt", DT_BF16, 256, 256, 64, 2, 4, 5, false, false, true),
-    TILED("f16_d256x256w8k32s5_nt", DT_F16, 256, 256, 64, 2, 4, 5, false, false, true),
-    TILED("bf16_d256x256w4k32s4_nt", DT_BF16, 256, 256, 64, 2, 2, 4, false, false, true),
-    TILED("f16_d256x256w4k32s4_nt", DT_F16, 256, 256, 64, 2, 2, 4, false, false, true),
-    // two B stages, three A stages (160 KB): A's loads run two steps ahead
-    TILED_AX("bf16_d256x256w8a3_nt", DT_BF16, 256, 256, 128, 2, 4, 2, 1),
-    TILED_AX("f16_d256x256w8a3_nt", DT_F16, 256, 256, 128, 2, 4, 2, 1),
-    // the two waves of a SIMD alternate between reading fragments and multiplying
-    TILED_PP("bf16_p256x256w8_nt", DT_BF16, 256, 256, 128, 2, 4, 2, 0),
-    TILED_PP("f16_p256x256w8_nt", DT_F16, 256, 256, 128, 2, 4, 2, 0),
-
-    // 16-bit, B stored K x N ("_nn"): A direct, B transposed through registers ...
-    TILED("bf16_d256x256w8_nn", DT_BF16, 256, 256, 128, 2, 4, 2, false, true, true),
-    TILED("f16_d256x256w8_nn", DT_F16, 256, 256, 128, 2, 4, 2, false, true, true),
-    TILED("bf16_d256x128w8_nn", DT_BF16, 256, 128, 128, 4, 2, 3, false, true, true),
-    TILED("f16_d256x128w8_nn", DT_F16, 256, 128, 128, 4, 2, 3, false, true, true),
-    TILED("bf16_d256x256w8k32s4_nn", DT_BF16, 256, 256, 64, 2, 4, 4, false, true, true),
-    TILED("f16_d256x256w8k32s4_nn", DT_F16, 256, 256, 64, 2, 4, 4, false, true, true),
-    // ... or B staged directly as [k][n] rows and read with transposing LDS reads
-    TILED_TR("bf16_t256x256w8_nn", DT_BF16, 256, 256, 128, 2, 4, 2),
-    TILED_TR("f16_t256x256w8_nn", DT_F16, 256, 256, 128, 2, 4, 2),
-    TILED_AX_TR("bf16_t256x256w4a3_nn", DT_BF16, 256, 256, 128, 2, 2, 2, 1),
-    TILED_AX_TR("f16_t256x256w4a3_nn", DT_F16, 256, 256, 128, 2, 2, 2, 1),
-    TILED_AX_TR("bf16_t256x256w8a3_nn", DT_BF16, 256, 256, 128, 2, 4, 2, 1),
-    TILED_AX_TR("f16_t256x256w8a3_nn", DT_F16, 256, 256, 128, 2, 4, 2, 1),
-    TILED_TR("bf16_t128x256w8_nn", DT_BF16, 128, 256, 128, 2, 4, 2),
-    TILED_TR("f16_t128x256w8_nn", DT_F16, 128, 256, 128, 2, 4, 2),
-    TILED_TR("bf16_t128x128w4_nn", DT_BF16, 128, 128, 128, 2, 2, 2),
-    TILED_TR("f16_t128x128w4_nn", DT_F16, 128, 128, 128, 2, 2, 2),
-    TILED_TR("bf16_t256x128w8_nn", DT_BF16, 256, 128, 128, 4, 2, 3),
-    TILED_TR("f16_t256x128w8_nn", DT_F16, 256, 128, 128, 4, 2, 3),
-    TILED_PP("bf16_pt256x256w8_nn", DT_BF16, 256, 256, 128, 2, 4, 2, 1),
-    TILED_PP("f16_pt256x256w8_nn", DT_F16, 256, 256, 128, 2, 4, 2, 1),
-
-    // fp32: A direct; B through registers ("_d", either layout) or directly as [k][n] rows ("_t": no
-    // transposition needed, one float per lane and MFMA)
-    TILED("f32_d128x128w4_nt", DT_F32, 128, 128, 128, 2, 2, 2, false, false, true),
-    TILED("f32_d128x128w4s3_nt", DT_F32, 128, 128, 128, 2, 2, 3, false, false, true),
-    TILED("f32_d128x128w4_nn", DT_F32, 128, 128, 128, 2, 2, 2, false, true, true),
-    TILED("f32_d128x128w4s3_nn", DT_F32, 128, 128, 128, 2, 2, 3, false, true, true),
-    TILED("f32_d256x128w8_nn", DT_F32, 256, 128, 128, 4, 2, 2, false, true, true),
-    TILED("f32_d256x128w8s3_nn", DT_F32, 256, 128, 128, 4, 2, 3, false, true, true),
-    TILED_TR("f32_t128x128w4_nn", DT_F32, 128, 128, 128, 2, 2, 2),
-    TILED_TR("f32_t128x128w4s3_nn", DT_F32, 128, 128, 128, 2, 2, 3),
-    TILED_TR("f32_t256x128w8_nn", DT_F32, 256, 128, 128, 4, 2, 2),
-    TILED_TR("f32_t256x128w8s3_nn", DT_F32, 256, 128, 128, 4, 2, 3),
-    TILED_TR("f32_t256x128w4_nn", DT_F32, 256, 128, 128, 2, 2, 2),
-    TILED_TR("f32_t128x64w4_nn", DT_F32, 128, 64, 128, 2, 2, 2),
-
-    // A stored K x M ("_t?"): staged directly as [k][m] rows
-    TILED_ATR("bf16_t256x256w8_tt", DT_BF16, 256, 256, 128, 2, 4, 2, 0),
-    TILED_ATR("f16_t256x256w8_tt", DT_F16, 256, 256, 128, 2, 4, 2, 0),
-    TILED_ATR("bf16_t256x256w8_tn", DT_BF16, 256, 256, 128, 2, 4, 2, 1),
-    TILED_ATR("f16_t256x256w8_tn", DT_F16, 256, 256, 128, 2, 4, 2, 1),
-    TILED_ATR("bf16_t128x128w4_tt", DT_BF16, 128, 128, 128, 2, 2, 2, 0),
-    TILED_ATR("f16_t128x128w4_tt", DT_F16, 128, 128, 128, 2, 2, 2, 0),
-    TILED_ATR("bf16_t128x128w4_tn", DT_BF16, 128, 128, 128, 2, 2, 2, 1),
-    TILED_ATR("f16_t128x128w4_tn", DT_F16, 128, 128, 128, 2, 2, 2, 1),
-    TILED_ATR("f32_t128x128w4_tt", DT_F32, 128, 128, 128, 2, 2, 2, 0),
-    TILED_ATR("f32_t128x128w4_tn", DT_F32, 128, 128, 128, 2, 2, 2, 1),
-    TILED_ATR("f32_t256x128w8_tt", DT_F32, 256, 128, 128, 4, 2, 2, 0),
-    TILED_ATR("f32_t256x128w8_tn", DT_F32, 256, 128, 128, 4, 2, 2, 1),
-
-    // M <= 16, both operands along K: B is streamed once.  LDS ring of BN rows x KSTEP ...
-    SKINNY("bf16_skinny16s3_nt", DT_BF16, 64, 128, 3),
-    SKINNY("f16_skinny16s3_nt", DT_F16, 64, 128, 3),
-    SKINNY("bf16_skinny32k512s3_nt", DT_BF16, 32, 512, 3),
-    SKINNY("f16_skinny32k512s3_nt", DT_F16, 32, 512, 3),
-    SKINNY("bf16_skinny64k256s3_nt", DT_BF16, 64, 256, 3),
-    SKINNY("f16_skinny64k256s3_nt", DT_F16, 64, 256, 3),
-    SKINNY("bf16_skinny64k512s2_nt", DT_BF16, 64, 512, 2),
-    SKINNY("f16_skinny64k512s2_nt", DT_F16, 64, 512, 2),
-    // ... or straight into registers (no LDS, no barriers)
-    SKINNY_REG("bf16_skinnyreg_d8_nt", DT_BF16, 8, 4),
-    SKINNY_REG("f16_skinnyreg_d8_nt", DT_F16, 8, 4),
-
-    // 16-bit 128x64 tiles (48 KB of LDS: three workgroups share a CU) for problems with few tiles
-    TILED("bf16_d128x64w4_nt", DT_BF16, 128, 64, 128, 2, 2, 2, false, false, true),
-    TILED("f16_d128x64w4_nt", DT_F16, 128, 64, 128, 2, 2, 2, false, false, true),
-    // ... and with B kept as [k][n] rows (which need 128 columns): 64x128
-    TILED_TR("bf16_t64x128w4_nn", DT_BF16, 64, 128, 128, 2, 2, 2),
-    TILED_TR("f16_t64x128w4_nn", DT_F16, 64, 128, 128, 2, 2, 2),
-};
-constexpr int NUM_VARIANTS = (int)(sizeof(g_variants) / sizeof(g_variants[0]));
-
-// Variants the selector may pick on its own.  The others stay reachable through
-// the force bits of the descriptor, for sweeps.
-static bool variant_selectable(int id)
-{
-    const char *n = g_variants[id].name;
-    if (strstr(n, "_p256") || strstr(n, "_pt256")) return false;
-    if (strstr(n, "k32s4") || strstr(n, "k32s5") || strstr(n, "w4k32") || strstr(n, "d256x256w4_")) return false;
-    return true;
+    static const int n = [] {
+        if (const char *e = getenv("PEAK_GEMM_NUM_CU")) {
+            const int v = atoi(e);
+            if (v >= 1 && v <= 4096) return v;
+        }
+        int dev = 0, v = 0;
+        if (hipGetDevice(&dev) == hipSuccess &&
+            hipDeviceGetAttribute(&v, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && v > 0)
+            return v;
+        (void)hipGetLastError();
+        return 256;
+    }();
+    return n;
 }
 
 }  // namespace peak
 
 using namespace peak;
 
-struct peak_gemm_plan {
-    peak_gemm_desc_t d;
-    int variant;          // index into g_variants, -1: nothing to launch
+// Grid and K split of one variant for the plan's problem.
+struct Geometry {
+    int variant;          // index into the variant table, -1: nothing to launch
     int tiles_m, tiles_n, split, ktiles_total, ktiles_per_slice, group_m, rot_m, rot_n;
     size_t ws_bytes;
-    int max_lds_set;      // hipFuncSetAttribute not needed: LDS is static
+};
+
+struct peak_gemm_plan {
+    peak_gemm_desc_t d;
+    Geometry g;           // the selected variant
+    Geometry alt;         // register-staged stand-in for runs whose A or B base is not 16-byte aligned
+                          // (variant -1 when the selected variant has no alignment needs)
+    size_t ws_bytes;      // the larger of the two workspaces
 };
 
 static int esize_of(int dt) { return dt == PEAK_DT_F32 ? 4 : 2; }
@@ -278,7 +116,7 @@ static int64_t cdiv(int64_t a, int64_t b) { return (a + b - 1) / b; }
 static double tiled_cost(const Variant &v, const peak_gemm_desc_t &d, int split)
 {
     const int64_t tiles = cdiv(d.M, v.bm) * cdiv(d.N, v.bn) * split;
-    const int64_t rounds = cdiv(tiles, NUM_CU);
+    const int64_t rounds = cdiv(tiles, num_cu());
     const double ktiles = (double)cdiv(cdiv(d.K, v.bk), split);
     // one unit = one multiply-add at the 16-bit MFMA rate; an fp32 one takes 16 of them (2500 vs 157 TFLOP/s)
     const double tile_work = (double)v.bm * v.bn * v.bk * ktiles * (v.dt == DT_F32 ? 16.0 : 1.0);
@@ -316,7 +154,7 @@ static int choose_split(const Variant &v, const peak_gemm_desc_t &d)
 {
     const int64_t tiles = cdiv(d.M, v.bm) * cdiv(d.N, v.bn);
     const int64_t ktiles = cdiv(d.K, v.bk);
-    if (tiles > NUM_CU / 2 || ktiles < 4) return 1;
+    if (tiles > num_cu() / 2 || ktiles < 4) return 1;
     int best = 1;
     double best_cost = tiled_cost(v, d, 1);
     for (int s = 2; s <= 16; ++s) {
@@ -327,9 +165,10 @@ static int choose_split(const Variant &v, const peak_gemm_desc_t &d)
     return best;
 }
 
-static void plan_geometry(peak_gemm_plan *p, const Variant &v, int forced_split)
+static void plan_geometry(Geometry *p, const peak_gemm_desc_t &d, int variant, int forced_split)
 {
-    const peak_gemm_desc_t &d = p->d;
+    const Variant &v = g_variants[variant];
+    p->variant = variant;
     p->tiles_m = (int)cdiv(d.M, v.bm);
     p->tiles_n = (int)cdiv(d.N, v.bn);
     p->ktiles_total = (int)cdiv(d.K, v.bk);
@@ -353,6 +192,27 @@ static void plan_geometry(peak_gemm_plan *p, const Variant &v, int forced_split)
         if (sscanf(e, "%d,%d", &a, &b) == 2 && a >= 0 && b >= 0) { p->rot_m = a; p->rot_n = b; }
     }
     p->ws_bytes = p->split > 1 ? (size_t)p->split * (size_t)d.M * (size_t)d.N * sizeof(float) : 0;
+}
+
+// The selector's own choice among the variants that fit (cost model); with
+// `staged_only`, among those that take any operand alignment.
+static int select_variant(const peak_gemm_desc_t &d, bool staged_only)
+{
+    double best = 0.0;
+    int pick = -1, second_stream = -1;
+    for (int i = 0; i < NUM_VARIANTS; ++i) {
+        const Variant &v = g_variants[i];
+        if (v.sweep_only || (staged_only && v.direct) || !variant_fits(v, d)) continue;
+        if (v.kind != KIND_TILED) {
+            // a streaming kernel wins whenever it applies
+            if (v.stream_rank == 2) return i;
+            if (v.stream_rank == 1 && second_stream < 0) second_stream = i;
+            continue;
+        }
+        const double c = tiled_cost(v, d, choose_split(v, d));
+        if (pick < 0 || c < best) { pick = i; best = c; }
+    }
+    return second_stream >= 0 ? second_stream : pick;
 }
 
 // Selector table from an offline sweep: exact shape -> variant and K split.
@@ -399,11 +259,28 @@ static int load_tuning_file(const char *path)
     return (int)g_tuning.size();
 }
 
+// The table that ships with the library: peak_gemm_tuning.txt beside the shared object.
+static std::string shipped_table_path()
+{
+    Dl_info info;
+    if (!dladdr((const void *)&peak_gemm_variant_count, &info) || !info.dli_fname) return std::string();
+    std::string path(info.dli_fname);
+    const size_t slash = path.rfind('/');
+    path = slash == std::string::npos ? std::string() : path.substr(0, slash + 1);
+    return path + "peak_gemm_tuning.txt";
+}
+
 static const TuneEntry *tuned(const peak_gemm_desc_t &d)
 {
     if (!g_tuning_env_done) {
         g_tuning_env_done = true;
-        if (const char *e = getenv("PEAK_GEMM_TUNING")) load_tuning_file(e);
+        // PEAK_GEMM_TUNING names another table; set to the empty string it turns the shipped one off
+        if (const char *e = getenv("PEAK_GEMM_TUNING")) {
+            if (*e) load_tuning_file(e);
+        } else {
+            const std::string path = shipped_table_path();
+            if (!path.empty()) load_tuning_file(path.c_str());
+        }
     }
     for (const TuneEntry &e : g_tuning)
         if (e.dt == (int)d.dtype && e.ta == d.transA && e.tb == d.transB && e.M == d.M && e.N == d.N && e.K == d.K &&
@@ -464,8 +341,8 @@ peak_status_t peak_gemm_create(const peak_gemm_desc_t *desc, peak_gemm_plan_t **
     if (!p) return PEAK_ERR_ALLOC;
     memset(p, 0, sizeof *p);
     p->d = d;
-    p->variant = -1;
-    p->split = 1;
+    p->g.variant = p->alt.variant = -1;
+    p->g.split = p->alt.split = 1;
 
     const int forced = (int)(d.flags & 0xFF) - 1;
     const int forced_split = (int)((d.flags >> 8) & 0xFF);
@@ -491,34 +368,23 @@ peak_status_t peak_gemm_create(const peak_gemm_desc_t *desc, peak_gemm_plan_t **
         pick = t->variant;
         table_split = t->split;
     } else {
-        double best = 0.0;
-        int skinny_pick = -1;
-        for (int i = 0; i < NUM_VARIANTS; ++i) {
-            const Variant &v = g_variants[i];
-            if (!variant_fits(v, d)) continue;
-            if (v.kind != KIND_TILED) {
-                // a streaming kernel wins whenever it applies: long row runs through LDS first,
-                // the register-streaming one for K that is not a multiple of 512
-                const bool preferred = strstr(v.name, "skinny64k512s2") != nullptr;
-                const bool second = v.kind == KIND_SKINNY_REG && strstr(v.name, "_d8_") != nullptr;
-                if (preferred) { pick = i; break; }
-                if (second && skinny_pick < 0) skinny_pick = i;
-                continue;
-            }
-            if (!variant_selectable(i)) continue;
-            const double c = tiled_cost(v, d, choose_split(v, d));
-            if (pick < 0 || c < best) { pick = i; best = c; }
-        }
-        if (skinny_pick >= 0 && (pick < 0 || g_variants[pick].kind == KIND_TILED)) pick = skinny_pick;
+        pick = select_variant(d, false);
         if (pick < 0) {
             delete p;
             return PEAK_ERR_UNSUPPORTED;
         }
     }
-    p->variant = pick;
-    plan_geometry(p, g_variants[pick], forced_split > 0 ? forced_split : table_split);
-    const int64_t grid = (int64_t)p->tiles_m * p->tiles_n * p->split;
-    if (grid > 0x7FFFFFFF) {
+    plan_geometry(&p->g, d, pick, forced_split > 0 ? forced_split : table_split);
+    // Leading dimensions are known here, base addresses only at run time: a variant that copies
+    // 16-byte chunks gets a register-staged stand-in for runs whose A or B base is off that alignment
+    if (g_variants[pick].direct) {
+        const int alt = select_variant(d, true);
+        if (alt >= 0) plan_geometry(&p->alt, d, alt, forced_split);
+    }
+    p->ws_bytes = p->g.ws_bytes > p->alt.ws_bytes ? p->g.ws_bytes : p->alt.ws_bytes;
+    const int64_t grid = (int64_t)p->g.tiles_m * p->g.tiles_n * p->g.split;
+    const int64_t grid_alt = p->alt.variant < 0 ? 0 : (int64_t)p->alt.tiles_m * p->alt.tiles_n * p->alt.split;
+    if (grid > 0x7FFFFFFF || grid_alt > 0x7FFFFFFF) {
         delete p;
         return PEAK_ERR_UNSUPPORTED;
     }
@@ -531,15 +397,17 @@ size_t peak_gemm_workspace_bytes(const peak_gemm_plan_t *plan) { return plan ? p
 int peak_gemm_plan_info(const peak_gemm_plan_t *p, char *buf, size_t n)
 {
     if (!p) return snprintf(buf, n, "null plan");
-    if (p->variant < 0)
+    if (p->g.variant < 0)
         return snprintf(buf, n, "variant=none (degenerate size) M=%lld N=%lld K=%lld", (long long)p->d.M,
                         (long long)p->d.N, (long long)p->d.K);
-    const Variant &v = g_variants[p->variant];
+    const Geometry &g = p->g;
+    const Variant &v = g_variants[g.variant];
     return snprintf(buf, n,
                     "variant=%d:%s tile=%dx%dx%d threads=%d stages=%d lds=%d split=%d ktiles/slice=%d "
-                    "grid=%lld (tiles %dx%d) group_m=%d workspace=%zu",
-                    p->variant, v.name, v.bm, v.bn, v.bk, v.nt, v.ns, v.lds, p->split, p->ktiles_per_slice,
-                    (long long)p->tiles_m * p->tiles_n * p->split, p->tiles_m, p->tiles_n, p->group_m, p->ws_bytes);
+                    "grid=%lld (tiles %dx%d) group_m=%d workspace=%zu unaligned=%s",
+                    g.variant, v.name, v.bm, v.bn, v.bk, v.nt, v.ns, v.lds, g.split, g.ktiles_per_slice,
+                    (long long)g.tiles_m * g.tiles_n * g.split, g.tiles_m, g.tiles_n, g.group_m, p->ws_bytes,
+                    p->alt.variant >= 0 ? g_variants[p->alt.variant].name : "same");
 }
 
 static peak_status_t run_plan(peak_gemm_plan_t *p, float alpha, const void *A, const void *B, float beta, void *C,
@@ -581,35 +449,40 @@ static peak_status_t run_plan(peak_gemm_plan_t *p, float alpha, const void *A, c
 
     if (!A || !B) return PEAK_ERR_INVALID_ARG;
     if ((uintptr_t)A % es || (uintptr_t)B % es) return PEAK_ERR_INVALID_ARG;
-    if (p->variant < 0) return PEAK_ERR_UNSUPPORTED;
-    const Variant &v = g_variants[p->variant];
+    if (p->g.variant < 0) return PEAK_ERR_UNSUPPORTED;
 
     const bool a_al = (uintptr_t)A % 16 == 0 && (d.lda * es) % 16 == 0;
     const bool b_al = (uintptr_t)B % 16 == 0 && (d.ldb * es) % 16 == 0;
     if (a_al) a.flags |= GF_A_VEC;
     if (b_al) a.flags |= GF_B_VEC;
-    if (v.direct && !(a_al && b_al)) return PEAK_ERR_INVALID_ARG;   // plan was made for aligned operands
+    // the selected variant, or its stand-in when it copies 16-byte chunks and a base is off that alignment
+    const Geometry *g = &p->g;
+    if (g_variants[g->variant].direct && !(a_al && b_al)) {
+        if (p->alt.variant < 0) return PEAK_ERR_UNSUPPORTED;
+        g = &p->alt;
+    }
+    const Variant &v = g_variants[g->variant];
 
-    if (p->split > 1) {
-        if (!workspace || workspace_bytes < p->ws_bytes) return PEAK_ERR_WORKSPACE;
+    if (g->split > 1) {
+        if (!workspace || workspace_bytes < g->ws_bytes) return PEAK_ERR_WORKSPACE;
         if ((uintptr_t)workspace % 256) return PEAK_ERR_INVALID_ARG;
         a.ws = (float *)workspace;
         if (d.N % 4 == 0) a.flags |= GF_WS_VEC;
     }
-    a.tiles_m = p->tiles_m; a.tiles_n = p->tiles_n;
-    a.split = p->split;
-    a.ktiles_per_slice = p->ktiles_per_slice;
-    a.ktiles_total = p->ktiles_total;
-    a.group_m = p->group_m;
-    a.rot_m = p->rot_m;
-    a.rot_n = p->rot_n;
+    a.tiles_m = g->tiles_m; a.tiles_n = g->tiles_n;
+    a.split = g->split;
+    a.ktiles_per_slice = g->ktiles_per_slice;
+    a.ktiles_total = g->ktiles_total;
+    a.group_m = g->group_m;
+    a.rot_m = g->rot_m;
+    a.rot_n = g->rot_n;
 
-    int64_t nblocks = (int64_t)p->tiles_m * p->tiles_n * p->split;
-    if (v.kind == KIND_SKINNY_REG) nblocks = cdiv((int64_t)p->tiles_n * p->split, v.nt / 64);   // one wave per row group and slice
+    int64_t nblocks = (int64_t)g->tiles_m * g->tiles_n * g->split;
+    if (v.kind == KIND_SKINNY_REG) nblocks = cdiv((int64_t)g->tiles_n * g->split, v.nt / 64);   // one wave per row group and slice
     dim3 grid((unsigned)nblocks);
     if (v.launch(a, grid, stream) != hipSuccess) return PEAK_ERR_HIP;
 
-    if (p->split > 1) {
+    if (g->split > 1) {
         const int64_t quads = d.M * cdiv(d.N, 4);
         dim3 rgrid((unsigned)cdiv(quads, 256));
         if (c_dt == PEAK_DT_F32) hipLaunchKernelGGL(splitk_reduce_kernel<DT_F32>, rgrid, dim3(256), 0, stream, a);

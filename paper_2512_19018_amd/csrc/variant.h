@@ -1,0 +1,111 @@
+// Kernel variant table: one row per instantiation of the kernel templates (the
+// tuning parameters of the paper's Section 3.1: tile shape, waves, stages,
+// staging kind).  The rows are defined in several translation units, one per
+// group of variants, so that the groups compile in parallel; peak_gemm.hip
+// joins them into one table.
+#pragma once
+
+#include <hip/hip_runtime.h>
+
+#include "gemm_device.h"
+
+namespace peak {
+
+typedef hipError_t (*launch_fn)(const GemmArgs &, dim3 grid, hipStream_t);
+
+enum Kind { KIND_TILED = 0, KIND_SKINNY = 1, KIND_SKINNY_REG = 2 };
+
+struct Variant {
+    const char *name;
+    int kind;
+    int dt;
+    int a_t, b_t;        // operand layouts the kernel was built for (1: stored K rows x M/N)
+    int direct;          // needs 16-byte aligned operand bases and rows (tiled: K a whole number of 16-byte chunks; skinny: K % BK == 0)
+    int bm, bn, bk, nt, ns, lds;
+    int max_m;           // skinny kernels: largest M
+    launch_fn launch;
+    int tr;              // B (K x N) goes to LDS untransposed ([k][n] rows)
+    int atr;             // A (K x M) goes to LDS untransposed ([k][m] rows)
+    int sweep_only;      // 1: reachable through the force bits only (kept for sweeps); the selector skips it
+    int stream_rank;     // streaming (skinny) kernels: 2 = the selector's first choice, 1 = its second, 0 = sweeps only
+};
+
+struct VariantGroup {
+    const Variant *rows;
+    int count;
+};
+
+// one per translation unit
+VariantGroup variants_general();
+VariantGroup variants_bf16_nt();
+VariantGroup variants_f16_nt();
+VariantGroup variants_bf16_nn();
+VariantGroup variants_f16_nn();
+VariantGroup variants_f32();
+VariantGroup variants_ta();
+VariantGroup variants_skinny();
+
+template <class C>
+static hipError_t launch_gemm(const GemmArgs &a, dim3 grid, hipStream_t s)
+{
+    hipLaunchKernelGGL((gemm_kernel<C>), grid, dim3(C::NT), 0, s, a);
+    return hipGetLastError();
+}
+
+#define PEAK_BK(DT, RB) ((RB) / ((DT) == DT_F32 ? 4 : 2))
+
+// both operands handled by the template's own flags
+#define TILED(NAME, DT, BM, BN, RB, WMW, WNW, NS, AT, BT, DIR)                                         \
+    {NAME, KIND_TILED, DT, AT, BT, DIR, BM, BN, PEAK_BK(DT, RB), WMW * WNW * 64, NS,                   \
+     Cfg<DT, BM, BN, RB, WMW, WNW, NS, AT, BT, DIR>::LDS_BYTES, 0,                                     \
+     &launch_gemm<Cfg<DT, BM, BN, RB, WMW, WNW, NS, AT, BT, DIR>>, 0, 0, 0, 0}
+
+// the same, reachable through the force bits only
+#define TILED_SWEEP(NAME, DT, BM, BN, RB, WMW, WNW, NS, AT, BT, DIR)                                   \
+    {NAME, KIND_TILED, DT, AT, BT, DIR, BM, BN, PEAK_BK(DT, RB), WMW * WNW * 64, NS,                   \
+     Cfg<DT, BM, BN, RB, WMW, WNW, NS, AT, BT, DIR>::LDS_BYTES, 0,                                     \
+     &launch_gemm<Cfg<DT, BM, BN, RB, WMW, WNW, NS, AT, BT, DIR>>, 0, 0, 1, 0}
+
+// AX extra A stages (both operands along K)
+#define TILED_AX(NAME, DT, BM, BN, RB, WMW, WNW, NS, AX)                                              \
+    {NAME, KIND_TILED, DT, 0, 0, 1, BM, BN, PEAK_BK(DT, RB), WMW * WNW * 64, NS,                       \
+     Cfg<DT, BM, BN, RB, WMW, WNW, NS, false, false, true, AX>::LDS_BYTES, 0,                          \
+     &launch_gemm<Cfg<DT, BM, BN, RB, WMW, WNW, NS, false, false, true, AX>>, 0, 0, 0, 0}
+
+// AX extra A stages, B kept as [k][n] rows
+#define TILED_AX_TR(NAME, DT, BM, BN, RB, WMW, WNW, NS, AX)                                           \
+    {NAME, KIND_TILED, DT, 0, 1, 1, BM, BN, PEAK_BK(DT, RB), WMW * WNW * 64, NS,                       \
+     Cfg<DT, BM, BN, RB, WMW, WNW, NS, false, true, true, AX, true>::LDS_BYTES, 0,                     \
+     &launch_gemm<Cfg<DT, BM, BN, RB, WMW, WNW, NS, false, true, true, AX, true>>, 1, 0, 0, 0}
+
+// B kept as [k][n] rows
+#define TILED_TR(NAME, DT, BM, BN, RB, WMW, WNW, NS)                                                   \
+    {NAME, KIND_TILED, DT, 0, 1, 1, BM, BN, PEAK_BK(DT, RB), WMW * WNW * 64, NS,                       \
+     Cfg<DT, BM, BN, RB, WMW, WNW, NS, false, true, true, 0, true>::LDS_BYTES, 0,                      \
+     &launch_gemm<Cfg<DT, BM, BN, RB, WMW, WNW, NS, false, true, true, 0, true>>, 1, 0, 0, 0}
+
+// A stored K x M staged directly as [k][m] rows; B either along K ("_tt") or [k][n] rows as well ("_tn")
+#define TILED_ATR(NAME, DT, BM, BN, RB, WMW, WNW, NS, BTR)                                             \
+    {NAME, KIND_TILED, DT, 1, BTR, 1, BM, BN, PEAK_BK(DT, RB), WMW * WNW * 64, NS,                     \
+     Cfg<DT, BM, BN, RB, WMW, WNW, NS, true, BTR != 0, true, 0, BTR != 0, false, true>::LDS_BYTES, 0,  \
+     &launch_gemm<Cfg<DT, BM, BN, RB, WMW, WNW, NS, true, BTR != 0, true, 0, BTR != 0, false, true>>, BTR, 1, 0, 0}
+
+// alternating main loop (sweeps only)
+#define TILED_PP(NAME, DT, BM, BN, RB, WMW, WNW, NS, TR)                                              \
+    {NAME, KIND_TILED, DT, 0, TR, 1, BM, BN, PEAK_BK(DT, RB), WMW * WNW * 64, NS,                      \
+     Cfg<DT, BM, BN, RB, WMW, WNW, NS, false, TR != 0, true, 0, TR != 0, true>::LDS_BYTES, 0,          \
+     &launch_gemm<Cfg<DT, BM, BN, RB, WMW, WNW, NS, false, TR != 0, true, 0, TR != 0, true>>, TR, 0, 1, 0}
+
+// Layout suffix of the names: first letter is A (n: runs along K, t: stored K x M),
+// second is B as stored (t: N x K, runs along K; n: K x N).  So "_nt" is transA=0,
+// transB=1: both operands K-contiguous.
+#define TILED_LAYOUTS(NAME, DT, BM, BN, RB, WMW, WNW, NS)                                              \
+    TILED(NAME "_nt", DT, BM, BN, RB, WMW, WNW, NS, false, false, false),                             \
+    TILED(NAME "_nn", DT, BM, BN, RB, WMW, WNW, NS, false, true, false),                              \
+    TILED(NAME "_tt", DT, BM, BN, RB, WMW, WNW, NS, true, false, false),                              \
+    TILED(NAME "_tn", DT, BM, BN, RB, WMW, WNW, NS, true, true, false)
+
+#define PEAK_VARIANT_GROUP(FN, ROWS)                                                                   \
+    VariantGroup FN() { return VariantGroup{ROWS, (int)(sizeof(ROWS) / sizeof(ROWS[0]))}; }
+
+}  // namespace peak

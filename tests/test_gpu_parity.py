@@ -108,12 +108,13 @@ def test_random_every_direct_variant_deep_k(gu, oracle, dtype):
                 shapes = [(304, 520, 1024), (264, 264, 1000)] + ([(264, 264, 1003)] if not transB else [])
             for M, N, K in shapes:
                 A, B, C = _stored(6000 + vid, dtype, M, N, K, transA, transB)
-                ref = oracle.gemm(dtype, transA, transB, M, N, K, 1.0, A, B, 0.25, C)
+                ref, bound = gu.elementwise_bound(oracle, dtype, transA, transB, M, N, K, 1.0, A, B, 0.25, C)
                 for split in (None, 3):
                     got, raw, info = gu.run_gemm(dtype, transA, transB, M, N, K, 1.0, 0.25, A, B, C,
                                                  flags=gu.pg.force_flags(variant=vid, split=split))
                     err = oracle.rel_frobenius(got, ref)
                     assert err <= gu.TOL[dtype], (info, M, N, K, err)
+                    gu.assert_elementwise(got, ref, bound, (info, M, N, K))
 
 
 @pytest.mark.parametrize("dtype", DTYPES)
@@ -124,10 +125,9 @@ def test_random_against_oracle_auto_selection(gu, oracle, dtype, transA, transB)
         A, B, C = _stored(2000 + case, dtype, M, N, K, transA, transB)
         for alpha, beta in [(1.0, 0.0), (0.75, -0.5)]:
             C0 = C if beta != 0 else gu.nan_fill(M, N, dtype)
-            ref = oracle.gemm(dtype, transA, transB, M, N, K, alpha, A, B, beta, C if beta != 0 else None)
             got, raw, info = gu.run_gemm(dtype, transA, transB, M, N, K, alpha, beta, A, B, C0)
-            err = oracle.rel_frobenius(got, ref)
-            assert err <= gu.TOL[dtype], (info, M, N, K, err)
+            gu.check_against_oracle(oracle, got, dtype, transA, transB, M, N, K, alpha, A, B, beta, C,
+                                    what=(info, M, N, K, alpha, beta))
 
 
 @pytest.mark.parametrize("dtype", DTYPES)
@@ -153,6 +153,7 @@ def test_unaligned_operands_and_odd_leading_dimensions(gu, oracle, dtype):
         raw = gu.from_dev(dC, dtype)
         got = pi.to_f64(np.ascontiguousarray(raw[:M, :N]), dtype)
         assert oracle.rel_frobenius(got, ref) <= gu.TOL[dtype], (info, transA, transB)
+        gu.check_against_oracle(oracle, got, dtype, transA, transB, M, N, K, 1.0, A, B, 0.5, C, what=(info, transA, transB))
         _check_padding(raw, C, M, N)
 
 
@@ -168,6 +169,7 @@ def test_split_k_forced_and_deterministic(gu, oracle, dtype):
                                      flags=gu.pg.force_flags(split=split))
         assert ("split=%d" % split) in info or split > 1, info
         assert oracle.rel_frobenius(got, ref) <= gu.TOL[dtype], info
+        gu.check_against_oracle(oracle, got, dtype, transA, transB, M, N, K, 1.25, A, B, 0.5, C, what=info)
         again, raw2, _ = gu.run_gemm(dtype, transA, transB, M, N, K, 1.25, 0.5, A, B, C,
                                      flags=gu.pg.force_flags(split=split))
         assert np.array_equal(raw.view(np.uint8), raw2.view(np.uint8)), "run-to-run bits differ: " + info
@@ -251,13 +253,16 @@ def test_two_workgroups_per_cu_with_assembly_issued_reads(gu, oracle, dtype):
             err = oracle.rel_frobenius(got[rows], ref)
             assert err <= gu.TOL[dtype], (info, rep, err)
             assert np.isfinite(got).all(), info
+            if rep == 0:
+                gu.check_against_oracle(oracle, got, dtype, tA, tB, M, N, K, 1.0, A, B, 0.0, None, rows=rows, what=info)
 
 
 @pytest.mark.parametrize("dtype", DTYPES)
 def test_more_tiles_than_workgroups(gu, oracle, dtype):
-    """Kernels that hold a CU alone run one workgroup per CU and loop over their tiles.
-    Shapes with more tiles than the chip has CUs (and not a multiple of it), exact
-    integers, checked on sampled rows including the first and last tile rows."""
+    """More tiles than the chip has CUs (and not a multiple of it), for the kernels that
+    hold a CU alone: every CU gets several workgroups one after another and the last
+    round is partial.  Exact integers, checked on sampled rows including the first and
+    last tile rows."""
     import torch
     cus = torch.cuda.get_device_properties(0).multi_processor_count
     M, N, K = 4352 + 40, 4352 + 8, 128                       # 18 x 18 tiles of 256 x 256
@@ -283,3 +288,71 @@ def test_more_tiles_than_workgroups(gu, oracle, dtype):
             assert np.array_equal(got[rows], ref), (name, info)
             ran += 1
         assert ran >= 1, (dtype, transA, transB)
+
+
+@pytest.mark.parametrize("dtype", DTYPES)
+def test_exact_integers_deep_k_every_direct_variant(gu, oracle, dtype):
+    """Entries in {-1, 0, 1} over 16 and more K tiles, so every staging ring wraps
+    several times in its steady state: all sums are exact in fp32, so a stale stage,
+    a fragment read before its load has landed or a slice boundary off by one shows
+    as a wrong integer.  Every direct-to-LDS and streaming variant, split and unsplit,
+    K ending inside a K tile as well.  16-bit kernels are checked twice: with C in
+    their own storage type (the sums stay within the integers it holds exactly,
+    asserted) and with fp32 C (PEAK_GEMM_C_F32), which takes the other readout."""
+    limit = {pi.F32: 2 ** 24, pi.F16: 2048, pi.BF16: 256}[dtype]
+    for transA, transB in LAYOUTS:
+        for vid, name in gu.variants_for(dtype, transA, transB):
+            if not (re.search(r"_(?:d|t|p|pt)\d", name) or "skinny" in name):
+                continue
+            if "skinny" in name:
+                shapes = [(13, 1000, 4096), (16, 264, 4096)]
+            elif transA:
+                shapes = [(304, 520, 1024), (264, 264, 2056 if transB else 2051)]
+            else:
+                shapes = [(300, 520, 1024), (260, 264, 2056)]
+            for case, (M, N, K) in enumerate(shapes):
+                A, B, C = _stored(7000 + vid * 4 + case, dtype, M, N, K, transA, transB, ints=True, amp=1)
+                ref = oracle.gemm(dtype, transA, transB, M, N, K, 1.0, A, B, 1.0, C)
+                assert np.abs(ref).max() <= limit, (name, np.abs(ref).max())
+                for split in (None, 3):
+                    got, raw, info = gu.run_gemm(dtype, transA, transB, M, N, K, 1.0, 1.0, A, B, C,
+                                                 flags=gu.pg.force_flags(variant=vid, split=split))
+                    assert np.array_equal(got, ref), (info, M, N, K, int((got != ref).sum()))
+                    if dtype != pi.F32 and split is None:
+                        C32 = pi.to_f64(C, dtype).astype(np.float32)
+                        got, raw, info = gu.run_gemm(dtype, transA, transB, M, N, K, 1.0, 1.0, A, B, C32,
+                                                     flags=gu.pg.force_flags(variant=vid), cdtype=pi.F32)
+                        assert np.array_equal(got, ref), (info, "fp32 C", M, N, K, int((got != ref).sum()))
+
+
+@pytest.mark.parametrize("dtype", DTYPES)
+def test_operand_base_off_16_bytes_with_aligned_rows(gu, oracle, dtype):
+    """Leading dimensions that suit the 16-byte copies, but A or B starting one
+    element into an allocation (a view into a larger matrix): legal by the interface,
+    which asks for element alignment only.  The plan is made without the addresses, so
+    it holds a direct-to-LDS variant; the run must fall back to the plan's
+    register-staged stand-in and still match the oracle, with and without a K split."""
+    import torch
+    es = pi.DTYPE_SIZE[dtype]
+    for transA, transB in LAYOUTS:
+        for M, N, K, split in [(264, 520, 1024, None), (136, 264, 2048, 4), (16, 512, 1024, None)]:
+            if (M == 16) and (transA or not transB):
+                continue
+            A, B, C = _stored(3100 + M, dtype, M, N, K, transA, transB)
+            with gu.pg.Plan(M, N, K, dtype, transA, transB, flags=gu.pg.force_flags(split=split)) as plan:
+                info = plan.info()
+                assert re.search(r"variant=\d+:\w+_(?:d|t)\d|skinny", info), info      # a variant with alignment needs
+                assert "unaligned=same" not in info, info
+                ws = torch.empty(max(plan.workspace_bytes, 256), dtype=torch.uint8, device="cuda")
+                for off_a, off_b in [(1, 0), (0, 1), (1, 1)]:
+                    # the same values, one element into a larger allocation
+                    A1 = np.concatenate([A.ravel()[:1], A.ravel()]).reshape(1, -1)
+                    B1 = np.concatenate([B.ravel()[:1], B.ravel()]).reshape(1, -1)
+                    dA, dB, dC = gu.to_dev(A1 if off_a else A), gu.to_dev(B1 if off_b else B), gu.to_dev(C)
+                    plan.run(0.5, dA.data_ptr() + off_a * es, dB.data_ptr() + off_b * es, 2.0, dC.data_ptr(),
+                             ws.data_ptr(), plan.workspace_bytes, torch.cuda.current_stream().cuda_stream)
+                    torch.cuda.synchronize()
+                    raw = gu.from_dev(dC, dtype)
+                    got = pi.to_f64(np.ascontiguousarray(raw[:M, :N]), dtype)
+                    gu.check_against_oracle(oracle, got, dtype, transA, transB, M, N, K, 0.5, A, B, 2.0, C,
+                                            what=(info, transA, transB, off_a, off_b))

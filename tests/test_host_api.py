@@ -21,9 +21,13 @@ def _desc(M=64, N=64, K=64, dtype=pg.PEAK_DT_BF16, tA=0, tB=0, lda=None, ldb=Non
 
 
 def test_every_declared_symbol_is_exported():
-    header = open(os.path.join(ROOT, "include", "peak_gemm.h")).read()
+    import glob
+    headers = sorted(glob.glob(os.path.join(ROOT, "include", "*.h")))
+    assert len(headers) >= 2
+    header = "\n".join(open(h).read() for h in headers)
     header = re.sub(r"/\*.*?\*/", "", header, flags=re.S)
     names = set(re.findall(r"\b(peak_[a-z_]+)\s*\(", header))
+    assert {"peak_calib_mfma", "peak_calib_read"} <= names
     assert {"peak_gemm_create", "peak_gemm_run", "peak_gemm_destroy", "peak_gemm_workspace_bytes",
             "peak_status_string", "peak_gemm_plan_info"} <= names
     lib = pg.load_library()
@@ -274,3 +278,68 @@ def test_bench_refuses_more_than_one_gpu():
     r = subprocess.run([sys.executable, os.path.join(ROOT, "bench.py"), "--gpus", "2"], capture_output=True, text=True, timeout=120)
     assert r.returncode != 0
     assert "one GPU" in r.stderr and r.stdout.strip() == ""
+
+
+def _plan_info_in_fresh_process(env_extra, shape):
+    import subprocess
+    import sys
+    code = ("import sys; sys.path.insert(0, %r); import paper_2512_19018_amd as pg\n"
+            "with pg.Plan(%d, %d, %d, pg.PEAK_DT_BF16, 0, 1) as p: print(p.info())" % ((ROOT,) + shape))
+    env = dict(os.environ)
+    env.pop("PEAK_GEMM_TUNING", None)
+    env.update(env_extra)
+    r = subprocess.run([sys.executable, "-c", code], capture_output=True, text=True, timeout=120, env=env)
+    assert r.returncode == 0, r.stderr
+    return r.stdout.strip()
+
+
+def test_shipped_selector_table_is_loaded_by_default():
+    """The table beside the shared object decides for the shapes it lists from the
+    first create on; PEAK_GEMM_TUNING names another table or, empty, turns tables off."""
+    table = os.path.join(ROOT, "paper_2512_19018_amd", "peak_gemm_tuning.txt")
+    rows = [l.split("#")[0].split() for l in open(table) if l.split("#")[0].strip()]
+    assert len(rows) >= 40 and all(len(r) == 8 for r in rows)
+    names = {pg.peak_gemm_variant_name(i) for i in range(pg.peak_gemm_variant_count())}
+    assert all(r[6] in names for r in rows)
+    # a small problem the cost model is known to rank badly
+    row = [r for r in rows if r[:6] == ["bf16", "0", "1", "256", "256", "1024"]][0]
+    with_table = _plan_info_in_fresh_process({}, (256, 256, 1024))
+    assert row[6] in with_table and "split=%s " % row[7] in with_table
+    without = _plan_info_in_fresh_process({"PEAK_GEMM_TUNING": ""}, (256, 256, 1024))
+    assert "variant=" in without
+    # a shape that is not listed is the cost model's either way
+    assert _plan_info_in_fresh_process({}, (777, 512, 1024)) == _plan_info_in_fresh_process({"PEAK_GEMM_TUNING": ""}, (777, 512, 1024))
+
+
+def test_plans_keep_a_stand_in_for_unaligned_operand_bases():
+    # rows suit the 16-byte copies: a direct variant, with a register-staged stand-in for odd base addresses
+    with pg.Plan(512, 512, 1024, pg.PEAK_DT_BF16, 0, 1) as p:
+        info = p.info()
+        assert re.search(r"unaligned=bf16_r\d+x\d+_nt", info), info
+    # rows that do not: the selected variant takes any alignment itself
+    with pg.Plan(512, 512, 1024, pg.PEAK_DT_BF16, 0, 1, lda=1027) as p:
+        assert "unaligned=same" in p.info()
+    # the workspace covers whichever of the two runs
+    with pg.Plan(64, 64, 8192, pg.PEAK_DT_F16, 0, 1) as p:
+        m = re.search(r"split=(\d+) ", p.info())
+        assert p.workspace_bytes >= int(m.group(1)) * 64 * 64 * 4 if int(m.group(1)) > 1 else True
+
+
+def test_compute_unit_count_comes_from_the_environment_when_given():
+    # 1024 tiles: with 1024 CUs they fit one round and nothing needs splitting; the plan still is made
+    a = _plan_info_in_fresh_process({"PEAK_GEMM_NUM_CU": "8", "PEAK_GEMM_TUNING": ""}, (1024, 1024, 8192))
+    b = _plan_info_in_fresh_process({"PEAK_GEMM_NUM_CU": "1024", "PEAK_GEMM_TUNING": ""}, (1024, 1024, 8192))
+    assert "variant=" in a and "variant=" in b
+    assert "split=1 " in a                      # 16 tiles of 256x256 already fill 8 CUs twice over
+    assert "split=1 " not in b                  # 1024 CUs: the K loop is cut to fill them
+
+
+def test_calibration_calls_check_their_arguments():
+    # argument checks come before any device call
+    assert pg.peak_calib_mfma(7, True, 10, 0x1000)[0] == pg.PEAK_ERR_INVALID_ARG
+    assert pg.peak_calib_mfma(pg.PEAK_DT_BF16, True, 0, 0x1000)[0] == pg.PEAK_ERR_INVALID_ARG
+    assert pg.peak_calib_mfma(pg.PEAK_DT_BF16, True, 10, 0)[0] == pg.PEAK_ERR_INVALID_ARG
+    assert pg.peak_calib_mfma(pg.PEAK_DT_BF16, True, 10, 0x1004)[0] == pg.PEAK_ERR_INVALID_ARG
+    assert pg.peak_calib_read(0, 1 << 20, 0x1000) == pg.PEAK_ERR_INVALID_ARG
+    assert pg.peak_calib_read(0x1008, 1 << 20, 0x1000) == pg.PEAK_ERR_INVALID_ARG
+    assert pg.peak_calib_read(0x1000, 8, 0x1000) == pg.PEAK_ERR_INVALID_ARG
