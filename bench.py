@@ -9,6 +9,13 @@ under "workloads" in the same JSON line.
 
     python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload C3] [--only] [--no-cpu] [--no-torch]
 
+Order of a run: the headline workload's inputs are made and uploaded; the
+matrix cores' sustained rate is measured with an MFMA-only loop on random
+operands (include/peak_calib.h); then W warmup steps, K timed steps between one
+pair of HIP events, K more steps with an event pair each (median, min, mean);
+torch.matmul on the same buffers as context; the CPU oracle on a bounded sample
+of rows; then the other workloads the same way with shorter CPU samples.
+
 Prints ONE JSON line.
 """
 from __future__ import annotations
@@ -31,8 +38,39 @@ PEAK_HBM_GBS = 8000.0
 # FETCH_SIZE and WRITE_SIZE (profiles/*_summary.md), each scaled by what the same
 # counter reads for a plain 1 GiB device copy (FETCH_SIZE reads half the bytes:
 # factor 2.0; WRITE_SIZE factor 1.0).  Summed over the kernels of one launch.
-# None where not measured.
-MEASURED_TRAFFIC = {"C3": 1.752e9, "C5": 5.424e8, "C2": 9.20e8, "C4": 7.63e8}
+# A figure belongs to the kernel variant it was measured on: it is reported only
+# when the plan of this run selects that very variant and split, else null.
+MEASURED_TRAFFIC = {
+    "C3": ("bf16_d256x256w4a3_nt", 1, 1.752e9),
+    "C5": ("bf16_skinny64k512s2_nt", 1, 5.424e8),
+    "C2": ("f32_t256x128w8_nn", 1, 9.20e8),
+    "C4": ("f16_t256x256w4a3_nn", 1, 7.63e8),
+}
+
+
+def measured_traffic(name, plan_info):
+    t = MEASURED_TRAFFIC.get(name)
+    if not t:
+        return None
+    variant, split, nbytes = t
+    return nbytes if (":%s " % variant) in plan_info and ("split=%d " % split) in plan_info else None
+
+
+def smi_snapshot():
+    """Clocks and power as rocm-smi reports them (a child process; context only)."""
+    import subprocess
+    try:
+        r = subprocess.run(["rocm-smi", "--showclocks", "--showpower", "--json"], capture_output=True, text=True, timeout=30)
+        d = json.loads(r.stdout)
+        card = d[sorted(d)[0]]
+        keep = {}
+        for k, v in card.items():
+            kl = k.lower()
+            if "sclk" in kl or "mclk" in kl or "power" in kl:
+                keep[k] = v
+        return keep or None
+    except Exception as ex:
+        return {"error": repr(ex)[:120]}
 
 
 def log(*a):
@@ -60,6 +98,8 @@ def main():
     ap.add_argument("--constant-inputs", action="store_true",
                     help="diagnostic only: every element 1.0 (the matrix pipe then draws far less power; shows how "
                          "much of the time is the chip's power limit)")
+    ap.add_argument("--no-calibration", action="store_true",
+                    help="skip the MFMA-only / read-only calibration legs (profiling runs that want the GEMM kernels only)")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="run a plain 1 GiB device copy instead (to scale FETCH_SIZE / WRITE_SIZE under rocprofv3)")
     args = ap.parse_args()
@@ -95,7 +135,74 @@ def main():
     def dev(x):
         return torch.from_numpy(x.view(np.int16).copy() if x.dtype == np.uint16 else np.ascontiguousarray(x)).cuda()
 
-    def time_workload(name, steps, warmup, variant=None, split=None, with_torch=True):
+    calib_out = torch.zeros(8, dtype=torch.int64, device="cuda")
+    sustained = {}          # dtype name -> {"tflops", "clock_ghz"}: MFMA-only loop, random operands
+
+    def mfma_sustained(dtype):
+        """What the matrix cores sustain on this machine right now: the MFMA-only loop of
+        include/peak_calib.h on random operands, about a quarter of a second of it."""
+        name = pi.DTYPE_NAMES[dtype]
+        iters = 4096 if dtype != pi.F32 else 2048
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        best = None
+        for rep in range(4):
+            launches = 40
+            e0.record(stream)
+            for _ in range(launches):
+                st, flops = pg.peak_calib_mfma(dtype, True, iters, calib_out.data_ptr(), stream.cuda_stream)
+                if st != pg.PEAK_OK:
+                    raise SystemExit("bench.py: peak_calib_mfma: " + pg.peak_status_string(st))
+            e1.record(stream)
+            e1.synchronize()
+            ms = e0.elapsed_time(e1) / launches
+            c = calib_out.cpu().numpy()
+            best = {"tflops": flops / (ms * 1e-3) * 1e-12, "clock_ghz": 0.1 * float(c[0]) / max(float(c[1]), 1.0)}
+        sustained[name] = best          # the last repetition: the settled state
+        return best
+
+    read_stream = {}
+
+    def hbm_read_sustained():
+        """Read bandwidth a kernel gets that only reads: 2 GiB, far beyond the last-level cache."""
+        n = 1 << 31
+        src = torch.empty(n, dtype=torch.uint8, device="cuda")
+        src.random_(0, 255)
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        for rep in range(2):
+            launches = 10
+            e0.record(stream)
+            for _ in range(launches):
+                st = pg.peak_calib_read(src.data_ptr(), n, calib_out.data_ptr(), stream.cuda_stream)
+                if st != pg.PEAK_OK:
+                    raise SystemExit("bench.py: peak_calib_read: " + pg.peak_status_string(st))
+            e1.record(stream)
+            e1.synchronize()
+            read_stream["gbs"] = n / (e0.elapsed_time(e1) / launches * 1e-3) * 1e-9
+        del src
+        torch.cuda.empty_cache()
+        return read_stream["gbs"]
+
+    def cpu_leg(w, host, seconds, threads=None, label=None):
+        """The oracle as it stands on a bounded sample of rows of C (all columns, full K)."""
+        from oracle import gemm_oracle
+        A, B, C = host
+        threads = threads or gemm_oracle.default_threads()
+        cin = C if w.beta != 0 else None
+        t0 = time.perf_counter()
+        gemm_oracle.gemm(w.dtype, w.transA, w.transB, w.M, w.N, w.K, w.alpha, A, B, w.beta, cin,
+                         rows=list(range(min(threads, w.M))), threads=threads)
+        t_probe = time.perf_counter() - t0
+        nrows = int(max(threads, min(w.M, threads * max(1.0, seconds / max(t_probe, 1e-4)))))
+        nrows = min(w.M, (nrows // threads) * threads if nrows >= threads else nrows)
+        rows = [int(r) for r in np.linspace(0, w.M - 1, nrows).astype(np.int64)]
+        t0 = time.perf_counter()
+        gemm_oracle.gemm(w.dtype, w.transA, w.transB, w.M, w.N, w.K, w.alpha, A, B, w.beta, cin, rows=rows, threads=threads)
+        t_cpu = time.perf_counter() - t0
+        return {"value": 2.0 * len(rows) * w.N * w.K / t_cpu * 1e-12, "unit": "TFLOP/s", "cores": threads, "kind": "oracle",
+                "sample": "%d of %d rows of C (all N columns, full K) of %s in %.2f s on %d thread%s; rate scaled to the "
+                          "whole product" % (len(rows), w.M, label or w.name, t_cpu, threads, "" if threads == 1 else "s")}
+
+    def time_workload(name, steps, warmup, variant=None, split=None, with_torch=True, cpu_seconds=0.0):
         w = pi.WORKLOADS[name]
         t0 = time.time()
         if args.fast_inputs or args.constant_inputs:
@@ -128,8 +235,17 @@ def main():
                 raise SystemExit("bench.py: no kernel variant named %r" % (variant,))
             variant = names.index(variant)
         flags = pg.force_flags(None if variant is None else int(variant), split)
-        res = {"workload": name, "note": w.note, "dtype": pi.DTYPE_NAMES[w.dtype], "M": w.M, "N": w.N, "K": w.K,
+        dname = pi.DTYPE_NAMES[w.dtype]
+        res = {"workload": name, "note": w.note, "dtype": dname, "M": w.M, "N": w.N, "K": w.K,
                "transA": w.transA, "transB": w.transB, "alpha": w.alpha, "beta": w.beta, "buffer_sets": nset}
+        hbm_bound = (w.flops / w.min_bytes) < (PEAK_TFLOPS[dname] * 1e12 / (PEAK_HBM_GBS * 1e9))
+        if not args.no_calibration:
+            # the ceiling first, in the state the timed steps will find
+            if hbm_bound:
+                if "gbs" not in read_stream:
+                    hbm_read_sustained()
+            else:
+                mfma_sustained(w.dtype)
         with pg.Plan(w.M, w.N, w.K, w.dtype, w.transA, w.transB, lda, ldb, ldc, flags) as plan:
             res["plan"] = plan.info()
             ws = torch.empty(max(plan.workspace_bytes, 256), dtype=torch.uint8, device="cuda")
@@ -162,19 +278,40 @@ def main():
             torch.cuda.synchronize()
             wall_ms = (time.perf_counter() - t0) * 1e3 / steps
             ev_ms = e0.elapsed_time(e1) / steps
+            # the same number of launches again, an event pair around each
+            pairs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(steps)]
+            for i, (a0, a1) in enumerate(pairs):
+                a0.record(stream)
+                step(i)
+                a1.record(stream)
+            torch.cuda.synchronize()
+            each = np.array([a0.elapsed_time(a1) for a0, a1 in pairs])
         res["ms_per_step"] = wall_ms
         res["event_ms_per_step"] = ev_ms
+        res["per_launch_ms"] = {"median": float(np.median(each)), "min": float(each.min()), "mean": float(each.mean()),
+                                "launches": int(each.size)}
         res["tflops"] = w.flops / (wall_ms * 1e-3) * 1e-12
         res["tflops_events"] = w.flops / (ev_ms * 1e-3) * 1e-12
         res["gbs_events"] = w.min_bytes / (ev_ms * 1e-3) * 1e-9
-        hbm_bound = (w.flops / w.min_bytes) < (PEAK_TFLOPS[res["dtype"]] * 1e12 / (PEAK_HBM_GBS * 1e9))
+        traffic = measured_traffic(name, res["plan"])
         if hbm_bound:
             res["roofline"] = {"bound": "hbm", "achieved": res["gbs_events"], "peak": PEAK_HBM_GBS, "unit": "GB/s",
-                               "frac": res["gbs_events"] / PEAK_HBM_GBS, "traffic": MEASURED_TRAFFIC.get(name)}
+                               "frac": res["gbs_events"] / PEAK_HBM_GBS, "traffic": traffic}
+            if "gbs" in read_stream:
+                res["roofline"]["read_only_stream_gbs"] = read_stream["gbs"]
+                res["roofline"]["frac_of_read_only_stream"] = res["gbs_events"] / read_stream["gbs"]
         else:
-            pk = PEAK_TFLOPS[res["dtype"]]
+            pk = PEAK_TFLOPS[dname]
             res["roofline"] = {"bound": "mfma", "achieved": res["tflops_events"], "peak": pk, "unit": "TFLOP/s",
-                               "frac": res["tflops_events"] / pk, "traffic": MEASURED_TRAFFIC.get(name)}
+                               "frac": res["tflops_events"] / pk, "traffic": traffic}
+            if dname in sustained:
+                # the data-sheet peak assumes 2.4 GHz; under an MFMA-only load with random operands the
+                # chip holds clock_ghz, and peak * clock_ghz / 2.4 is what it can issue in that state
+                sus = sustained[dname]
+                res["roofline"]["mfma_only_sustained"] = sus["tflops"]
+                res["roofline"]["mfma_only_clock_ghz"] = sus["clock_ghz"]
+                res["roofline"]["peak_at_measured_clock"] = pk * sus["clock_ghz"] / 2.4
+                res["roofline"]["frac_measured_clock"] = res["tflops_events"] / (pk * sus["clock_ghz"] / 2.4)
         if with_torch:
             try:
                 tdt = {pi.F32: torch.float32, pi.F16: torch.float16, pi.BF16: torch.bfloat16}[w.dtype]
@@ -200,12 +337,18 @@ def main():
                 tms = (time.perf_counter() - t0) * 1e3 / steps
                 res["torch_ms"] = tms
                 res["torch_tflops"] = w.flops / (tms * 1e-3) * 1e-12
+                res["pct_of_library"] = 100.0 * res["tflops"] / res["torch_tflops"]
             except Exception as ex:      # context only
                 res["torch_error"] = repr(ex)[:200]
         del dA, dB, dC
         torch.cuda.empty_cache()
+        if cpu_seconds > 0:
+            res["cpu_baseline"] = cpu_leg(w, (A, B, C), cpu_seconds)
+            if name in ("C1", "C5"):
+                res["cpu_baseline_1_thread"] = cpu_leg(w, (A, B, C), min(cpu_seconds, 3.0), threads=1)
         return res, (A, B, C)
 
+    smi_before = smi_snapshot()
     head, host = time_workload(args.workload, args.steps, args.warmup, args.variant, args.split,
                                with_torch=not args.no_torch)
     w = pi.WORKLOADS[args.workload]
@@ -228,30 +371,14 @@ def main():
                    "plan": head["plan"]},
         "roofline": head["roofline"],
         "pct_of_peak": 100.0 * head["roofline"]["frac"],
+        "per_launch_ms": head["per_launch_ms"],
         "torch_matmul_tflops": head.get("torch_tflops"),
+        "pct_of_library": head.get("pct_of_library"),
     }
 
     # CPU baseline: the oracle as it stands, on a bounded sample of rows of the same workload
     if not args.no_cpu:
-        from oracle import gemm_oracle
-        A, B, C = host
-        threads = gemm_oracle.default_threads()
-        # one probe row to size the sample for roughly 15 s
-        t0 = time.perf_counter()
-        gemm_oracle.gemm(w.dtype, w.transA, w.transB, w.M, w.N, w.K, w.alpha, A, B, w.beta,
-                         C if w.beta != 0 else None, rows=list(range(min(threads, w.M))), threads=threads)
-        t_probe = time.perf_counter() - t0
-        nrows = int(max(threads, min(w.M, threads * max(1.0, 15.0 / max(t_probe, 1e-3)))))
-        nrows = min(w.M, (nrows // threads) * threads if nrows >= threads else nrows)
-        rows = [int(r) for r in np.linspace(0, w.M - 1, nrows).astype(np.int64)]
-        t0 = time.perf_counter()
-        gemm_oracle.gemm(w.dtype, w.transA, w.transB, w.M, w.N, w.K, w.alpha, A, B, w.beta,
-                         C if w.beta != 0 else None, rows=rows, threads=threads)
-        t_cpu = time.perf_counter() - t0
-        cpu_tflops = 2.0 * len(rows) * w.N * w.K / t_cpu * 1e-12
-        out["cpu_baseline"] = {"value": cpu_tflops, "unit": "TFLOP/s", "cores": threads, "kind": "oracle",
-                               "sample": "%d of %d rows of C (all N columns, full K) of %s in %.1f s; "
-                                         "rate scaled to the whole product" % (len(rows), w.M, w.name, t_cpu)}
+        out["cpu_baseline"] = cpu_leg(w, host, 15.0)
     del host
 
     if not args.only:
@@ -261,11 +388,12 @@ def main():
                 continue
             small = pi.WORKLOADS[name].flops < 1e10
             r, _ = time_workload(name, max(args.steps, 200) if small else args.steps, args.warmup,
-                                 with_torch=not args.no_torch)
+                                 with_torch=not args.no_torch, cpu_seconds=0.0 if args.no_cpu else 1.5)
             log("[bench] %s: %.3f ms  %.1f TFLOP/s  %.0f GB/s  (%s)" % (name, r["event_ms_per_step"], r["tflops_events"],
                                                                         r["gbs_events"], r["plan"]))
             others.append(r)
         out["workloads"] = others
+    out["rocm_smi"] = {"before": smi_before, "after": smi_snapshot()}
 
     print(json.dumps(out))
 
