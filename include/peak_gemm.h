@@ -176,6 +176,29 @@ peak_status_t peak_gemm_run_fused(peak_gemm_plan_t *plan, float alpha,
                                   void *workspace, size_t workspace_bytes,
                                   void *hip_stream);
 
+/*
+ * peak_gemm_run for callers that cannot allocate device memory or pass a
+ * workspace: code under HIP graph capture, tight serving loops, harnesses that
+ * forbid hipMalloc.  Same plan, same kernels, same result bits as peak_gemm_run;
+ * the Split-K partials go to an array of PEAK_GEMM_STATIC_WORKSPACE_BYTES that
+ * is part of the library's device code (every GPU the library runs on holds
+ * its own copy until the process ends).  The call allocates nothing.
+ *
+ *   PEAK_ERR_WORKSPACE  the plan needs more than PEAK_GEMM_STATIC_WORKSPACE_BYTES
+ *                       (peak_gemm_workspace_bytes() tells beforehand); nothing is launched.
+ *   PEAK_ERR_HIP        no current device, or the array's address could not be obtained.
+ *
+ * The array's device address is looked up on the first call on each device
+ * (make that call outside a graph capture).  All calls on one GPU share the
+ * array: runs that overlap in time on one GPU (different streams, or replays of
+ * two captured graphs) race on it and must be serialised by the caller.  No
+ * clearing is needed between calls: a run reads only partials it has written.
+ */
+#define PEAK_GEMM_STATIC_WORKSPACE_BYTES (32u << 20)
+peak_status_t peak_gemm_run_static(peak_gemm_plan_t *plan, float alpha,
+                                   const void *A, const void *B, float beta, void *C,
+                                   void *hip_stream);
+
 /* Frees the plan made by peak_gemm_create (host memory only; the kernel context of Section 3.1 owns nothing
  * on the device).  NULL is accepted.  Always PEAK_OK. */
 peak_status_t peak_gemm_destroy(peak_gemm_plan_t *plan);

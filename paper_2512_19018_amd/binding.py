@@ -62,6 +62,8 @@ def load_library():
         lib.peak_gemm_run.argtypes = [P, ctypes.c_float, P, P, ctypes.c_float, P, P, ctypes.c_size_t, P]
         lib.peak_gemm_run_fused.restype = ctypes.c_int
         lib.peak_gemm_run_fused.argtypes = [P, ctypes.c_float, P, P, ctypes.c_float, P, P, P, ctypes.c_size_t, P]
+        lib.peak_gemm_run_static.restype = ctypes.c_int
+        lib.peak_gemm_run_static.argtypes = [P, ctypes.c_float, P, P, ctypes.c_float, P, P]
         lib.peak_gemm_destroy.restype = ctypes.c_int
         lib.peak_gemm_destroy.argtypes = [P]
         lib.peak_status_string.restype = ctypes.c_char_p
@@ -134,6 +136,15 @@ def peak_gemm_run_fused(plan, alpha: float, A: int, B: int, beta: float, C: int,
     ep = ctypes.addressof(epilogue) if epilogue is not None else None     # host struct, read during the call
     return load_library().peak_gemm_run_fused(plan, float(alpha), A or None, B or None, float(beta), C or None, ep,
                                               workspace or None, int(workspace_bytes), stream or None)
+
+
+PEAK_GEMM_STATIC_WORKSPACE_BYTES = 32 << 20
+
+
+def peak_gemm_run_static(plan, alpha: float, A: int, B: int, beta: float, C: int, stream: int = 0) -> int:
+    """peak_gemm_run without a workspace argument: the partials go to the library's own fixed device array."""
+    return load_library().peak_gemm_run_static(plan, float(alpha), A or None, B or None, float(beta), C or None,
+                                               stream or None)
 
 
 def peak_calib_mfma(dtype: int, random_operands: bool, iters: int, out_dev: int, stream: int = 0):

@@ -469,6 +469,10 @@ static peak_status_t run_plan(peak_gemm_plan_t *p, float alpha, const void *A, c
         a.ws = (float *)workspace;
         if (d.N % 4 == 0) a.flags |= GF_WS_VEC;
     }
+#ifdef PEAK_TRACE
+    // diagnostic build: an unsplit run writes 64 bytes of time stamps per wave into the workspace, if one that large is given
+    if (g->split == 1 && workspace && workspace_bytes >= (size_t)g->tiles_m * g->tiles_n * (v.nt / 64) * 64) a.ws = (float *)workspace;
+#endif
     a.tiles_m = g->tiles_m; a.tiles_n = g->tiles_n;
     a.split = g->split;
     a.ktiles_per_slice = g->ktiles_per_slice;
@@ -517,6 +521,42 @@ peak_status_t peak_gemm_run_fused(peak_gemm_plan_t *plan, float alpha, const voi
         hook.act = epilogue->act;
     }
     return run_plan(plan, alpha, A, B, beta, C, hook, workspace, workspace_bytes, hip_stream);
+}
+
+// Workspace of peak_gemm_run_static: one array per GPU, part of the loaded code
+// object, held until the process ends.  In host code the array's name only
+// stands for the symbol; its address on a device comes from hipGetSymbolAddress
+// with that device current.
+static __device__ __align__(256) unsigned char scratch[PEAK_GEMM_STATIC_WORKSPACE_BYTES];
+
+constexpr int MAX_DEVICES = 64;
+static void *g_scratch_ptr[MAX_DEVICES];          // per device; nullptr until looked up
+static std::mutex g_scratch_mutex;
+
+peak_status_t peak_gemm_run_static(peak_gemm_plan_t *plan, float alpha, const void *A, const void *B, float beta,
+                                   void *C, void *hip_stream)
+{
+    if (!plan) return PEAK_ERR_INVALID_ARG;
+    if (plan->ws_bytes > (size_t)PEAK_GEMM_STATIC_WORKSPACE_BYTES) return PEAK_ERR_WORKSPACE;
+    void *ws = nullptr;
+    if (plan->ws_bytes > 0) {
+        int dev = -1;
+        if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= MAX_DEVICES) return PEAK_ERR_HIP;
+        std::lock_guard<std::mutex> lock(g_scratch_mutex);
+        if (!g_scratch_ptr[dev]) {
+            void *ptr = nullptr;
+            if (hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)) != hipSuccess || !ptr) {
+                (void)hipGetLastError();
+                return PEAK_ERR_HIP;
+            }
+            g_scratch_ptr[dev] = ptr;
+        }
+        ws = g_scratch_ptr[dev];
+    }
+    // Every element of the partials that the reduction reads is written by the slices of
+    // this very call, so nothing of an earlier call's contents needs clearing.
+    return run_plan(plan, alpha, A, B, beta, C, Hook{nullptr, BIAS_NONE, ACT_NONE}, ws,
+                    ws ? (size_t)PEAK_GEMM_STATIC_WORKSPACE_BYTES : 0, hip_stream);
 }
 
 peak_status_t peak_gemm_destroy(peak_gemm_plan_t *plan)
