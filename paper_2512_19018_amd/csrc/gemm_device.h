@@ -598,6 +598,23 @@ __global__ __launch_bounds__(C::NT) void gemm_kernel(const GemmArgs p)
     const int tid = threadIdx.x;
     const int lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int wm = wave / C::WAVES_N, wn = wave % C::WAVES_N;
+#ifdef PEAK_TRACE
+    // Diagnostic build only: per wave, shader-clock time stamps of the kernel's phases and the
+    // cycles spent at the K loop's waits, written to the workspace (see trace_store below).
+    const uint64_t tr_start = __builtin_amdgcn_s_memtime();
+    uint64_t tr_loop0 = 0, tr_loop1 = 0, tr_w0 = 0, tr_w1 = 0, tr_wait_sum = 0, tr_wait_max = 0;
+    auto trace_store = [&]() {
+        if (p.split == 1 && p.ws && lane == 0) {
+            const uint64_t tr_end = __builtin_amdgcn_s_memtime();
+            uint32_t hwid, xcc;
+            asm volatile("s_getreg_b32 %0, hwreg(HW_REG_HW_ID)" : "=s"(hwid));
+            asm volatile("s_getreg_b32 %0, hwreg(HW_REG_XCC_ID)" : "=s"(xcc));
+            uint64_t *dst = (uint64_t *)p.ws + ((size_t)blockIdx.x * C::NW + wave) * 8;
+            dst[0] = tr_start; dst[1] = tr_loop0; dst[2] = tr_loop1; dst[3] = tr_end;
+            dst[4] = tr_wait_sum; dst[5] = tr_wait_max; dst[6] = (uint64_t)hwid | ((uint64_t)xcc << 32); dst[7] = (uint64_t)p.ktiles_total;
+        }
+    };
+#endif
     const int r32 = lane & 31, half = lane >> 5;
 
     const int tiles = p.tiles_m * p.tiles_n;
@@ -956,6 +973,9 @@ __global__ __launch_bounds__(C::NT) void gemm_kernel(const GemmArgs p)
         issue_direct_all(0, 0);
         wait_vmcnt<0>();
         lds_barrier();
+#ifdef PEAK_TRACE
+        tr_loop0 = __builtin_amdgcn_s_memtime();
+#endif
         issue_b(1, 1, IC<0>{}, IC<1>{});
         issue_a(1, 1, IC<0>{}, IC<1>{});
         static_for<NFR>([&](auto fc) { fetch_one(0, 0, 0, IC<0>{}, fc); });
@@ -971,10 +991,25 @@ __global__ __launch_bounds__(C::NT) void gemm_kernel(const GemmArgs p)
                         constexpr bool LAST = kg + 1 == C::KG;
                         constexpr int cur = kg & 1, nxt = cur ^ 1;
                         if constexpr (LAST) {
+#ifdef PEAK_TRACE
+                            tr_w0 = __builtin_amdgcn_s_memtime();
+#endif
                             wait_vmcnt<PENDING>();                      // own loads of tile kt+1
                             lds_barrier();                              // tile kt+1 complete, tile kt read
+#ifdef PEAK_TRACE
+                            tr_w1 = __builtin_amdgcn_s_memtime();
+#endif
                         }
                         settle(IC<cur>{});
+#ifdef PEAK_TRACE
+                        if constexpr (kg == 1) {
+                            // the stamps of the step before: long since returned (the fragments this
+                            // k-group needs were asked for after them and are waited for here anyway)
+                            const uint64_t dw = tr_w1 - tr_w0;
+                            tr_wait_sum += dw;
+                            tr_wait_max = dw > tr_wait_max ? dw : tr_wait_max;
+                        }
+#endif
                         __builtin_amdgcn_sched_barrier(0);
                         static_for<NM>([&](auto ic) {
                             constexpr int i = decltype(ic)::value;
@@ -1004,6 +1039,9 @@ __global__ __launch_bounds__(C::NT) void gemm_kernel(const GemmArgs p)
         settle(IC<0>{});      // the last k-group's reads feed nothing, but must have returned before their registers are reused
         // 32x32x16 MFMA: 8 passes of 4 cycles; an accumulator may be read 18 wait states after the issue
         asm volatile("s_nop 15\n\ts_nop 15" ::: "memory");
+#ifdef PEAK_TRACE
+        tr_loop1 = __builtin_amdgcn_s_memtime();
+#endif
         static_for<C::MI * C::NI>([&](auto ic) {
             constexpr int i = decltype(ic)::value;
             f32x16 &c = acc[i / C::NI][i % C::NI];
@@ -1340,6 +1378,9 @@ __global__ __launch_bounds__(C::NT) void gemm_kernel(const GemmArgs p)
                         *(u32x4 *)((uint16_t *)p.C + m * p.ldc + n) = o;
                     }
                 }
+#ifdef PEAK_TRACE
+                trace_store();
+#endif
                 return;
             }
         }
@@ -1478,6 +1519,9 @@ __global__ __launch_bounds__(C::NT) void gemm_kernel(const GemmArgs p)
             __builtin_amdgcn_sched_barrier(0);
         }
     }
+#ifdef PEAK_TRACE
+    trace_store();
+#endif
 #endif
 }
 

@@ -34,6 +34,11 @@ static const Variant rows_skinny[] = {
     SKINNY("f16_skinny32k512s3_nt", DT_F16, 32, 512, 3, 0),
     SKINNY("bf16_skinny64k256s3_nt", DT_BF16, 64, 256, 3, 0),
     SKINNY("f16_skinny64k256s3_nt", DT_F16, 64, 256, 3, 0),
+    // deeper rings of shorter stages: more of the stream in flight per CU for the same 160 KB
+    SKINNY("bf16_skinny64k256s4_nt", DT_BF16, 64, 256, 4, 0),
+    SKINNY("f16_skinny64k256s4_nt", DT_F16, 64, 256, 4, 0),
+    SKINNY("bf16_skinny64k128s8_nt", DT_BF16, 64, 128, 8, 0),
+    SKINNY("f16_skinny64k128s8_nt", DT_F16, 64, 128, 8, 0),
     // long row runs through LDS: the selector's first choice wherever K is a multiple of 512
     SKINNY("bf16_skinny64k512s2_nt", DT_BF16, 64, 512, 2, 2),
     SKINNY("f16_skinny64k512s2_nt", DT_F16, 64, 512, 2, 2),
