@@ -152,6 +152,8 @@ struct Cfg {
     static_assert(DT_ == DT_F32 || ((!TR_ || BN_ >= 128) && (!ATR_ || BM_ >= 128)), "16-bit rows kept as [k][n] need at least 16 chunks");
     static constexpr int A_BYTES = BM_ * RB_;
     static constexpr int B_BYTES = BN_ * RB_;
+    // chunk c of tile row r sits at chunk position c ^ swizzle(r)
+    static __device__ __forceinline__ int swizzle(int r) { return swz<RB_ / 16>(r); }
     // LDS: NSA stages of the A tile, then NSB stages of the B tile.  AX extra A
     // stages let A's loads run one more step ahead than B's when LDS cannot hold
     // another full stage of both (asymmetric ring, prefetch loops only).
@@ -338,7 +340,7 @@ struct LoaderDirect {
             const int j = wave + C::NW * i;
             int row = j * (64 / C::CPR) + lane / C::CPR;
             const int pos = lane % C::CPR;
-            const int c = pos ^ swz<C::CPR>(row);
+            const int c = pos ^ C::swizzle(row);
             if (row > rows_here - 1) row = (int)rows_here - 1;    // duplicate of a valid row; its results are never stored
             voff[i] = (int)((row * ld + (int64_t)c * C::EPC) * C::ESZ);
             voff_tail[i] = c * C::EPC >= tail_k ? OOB_VOFFSET : voff[i];
@@ -584,6 +586,206 @@ PEAK_DEV void tile_of_block(int t, int tiles_m, int tiles_n, int group_m, int &t
     const int w = L - g * band;
     tm = first + w % gsz;
     tn = w / gsz;
+}
+
+// ---------------------------------------------------------------------------
+// Epilogue shared by the tiled kernels.  Each wave turns its wave tile around in
+// LDS, one slab of 32 rows at a time, so that a store instruction writes whole
+// row segments of C.  How the accumulators of a slab get into LDS depends on the
+// MFMA block shape and is the caller's part:
+//   write_slab(s, scr)    raw fp32 accumulators of slab s to scr[row * SROW + 4 * col], SROW = WTN * 4 + 16
+//   write16(s, scr16)     (16-bit kernels) alpha * acc rounded to the storage type, 8 bytes per 4-column
+//                         group g = col / 4 at scr16[row * SROW16 + 8 * (g ^ (row >> 4))], SROW16 = WTN * 2 + 16
+// ---------------------------------------------------------------------------
+template <class C, int SLABS, class WriteSlab, class Write16>
+PEAK_DEV void epilogue_slabs(const GemmArgs &p, char *lds, int wave, int lane, int wm, int wn, int64_t m0, int64_t n0,
+                             int slice, WriteSlab &&write_slab, Write16 &&write16)
+{
+    const bool c_vec = p.flags & GF_C_VEC, ws_vec = p.flags & GF_WS_VEC;
+    float *wsl = p.split > 1 ? p.ws + (int64_t)slice * p.M * p.N : nullptr;
+    const bool interior = m0 + C::BM <= p.M && n0 + C::BN <= p.N;      // whole tile inside C: no masks
+    // Each wave turns its 32-row slabs around in LDS (fp32, padded rows) so that a
+    // store instruction writes whole row segments of the wave tile (16 bytes per
+    // lane, WTN elements per row) instead of 32 scattered 8-byte pieces.  Interior
+    // tiles with 16-byte aligned C rows store vectors; edge tiles, unaligned rows and
+    // split-K partials leave through the same turnaround with masked stores, so the
+    // accumulators have one way out and never wait in ordinary registers.
+    constexpr int SROW = C::WTN * 4 + 16;                              // scratch row stride, bytes
+    static_assert(32 * SROW * C::NW <= C::LDS_BYTES, "the staging buffers are large enough for the turnaround");
+    {
+        lds_barrier();                                                 // nobody still reads the last stage
+        char *scr = lds + wave * (32 * SROW);
+        constexpr int OUT_ROW = C::WTN * C::ESZ;                       // bytes of one output row of the wave tile
+        constexpr int LPR = OUT_ROW / 16;                              // lanes per row on the way out
+        constexpr int RPI = 64 / LPR;                                  // rows per store instruction
+        static_assert(OUT_ROW % 16 == 0 && 64 % LPR == 0 && 32 % RPI == 0, "wave tile rows split into 16-byte pieces");
+        const int orow = lane / LPR, ocol = (lane % LPR) * (16 / C::ESZ);   // row within the group, first column (elements)
+        // fused step: a lane stores the same columns of every row, so their bias is fetched once
+        const bool hooked = !wsl && hook_active(p.hook), has_bias = p.hook.bias_kind != BIAS_NONE;
+        const bool c_f32 = C::DT != DT_F32 && (p.flags & GF_C_F32);    // fp32 C of a 16-bit kernel: masked readout
+        constexpr int EPL = 16 / C::ESZ;                               // elements per lane and row
+        float bcol[EPL];
+#pragma unroll
+        for (int e = 0; e < EPL; ++e) bcol[e] = 0.0f;
+        if (hooked && p.hook.bias_kind == BIAS_PER_COLUMN) {
+            const int64_t n = n0 + wn * C::WTN + ocol;
+#pragma unroll
+            for (int e = 0; e < EPL; ++e)
+                if (n + e < p.N) bcol[e] = p.hook.bias[n + e];
+        }
+        // Plain runs of the 16-bit kernels on interior tiles (beta == 0, no fused step): the slab
+        // goes through LDS already scaled and rounded, 8 bytes per lane and 4-column group, which
+        // halves the LDS traffic of the turnaround; the way back is a 16-byte read and the store.
+        // Rows r and r + 16 would meet in the same banks (row stride = 4 banks mod 64), so the
+        // 8-byte groups of rows 16..31 swap places pairwise; the reader swaps them back.
+        if constexpr (C::DT != DT_F32) {
+            if (interior && !wsl && (p.flags & GF_C_VEC16) && !c_f32 && p.beta == 0.0f && !hooked) {
+                constexpr int SROW16 = C::WTN * 2 + 16;
+                constexpr int G = 32 / RPI;
+                char *scr16 = lds + wave * (32 * SROW16);
+                write16(0, scr16);
+#pragma unroll
+                for (int mi = 0; mi < SLABS; ++mi) {
+                    u32x4 v[G];
+#pragma unroll
+                    for (int g = 0; g < G; ++g)
+                        v[g] = *(const u32x4 *)(scr16 + (g * RPI + orow) * SROW16 + ocol * 2);
+                    if (mi + 1 < SLABS) write16(mi + 1, scr16);      // in-order LDS: lands after the reads above
+#pragma unroll
+                    for (int g = 0; g < G; ++g) {
+                        const int64_t m = m0 + wm * C::WTM + mi * 32 + g * RPI + orow;
+                        const int64_t n = n0 + wn * C::WTN + ocol;
+                        const u32x4 o = (((g * RPI) >> 4) & 1) ? u32x4{v[g][2], v[g][3], v[g][0], v[g][1]} : v[g];
+                        *(u32x4 *)((uint16_t *)p.C + m * p.ldc + n) = o;
+                    }
+                }
+                return;
+            }
+        }
+        // A wave's LDS instructions execute in the order issued, so the next slab may be
+        // written into the same scratch as soon as this slab's reads are issued: the writes
+        // then run while this slab is converted and stored.
+        write_slab(0, scr);
+#pragma unroll
+        for (int mi = 0; mi < SLABS; ++mi) {
+            float brow = 0.0f;                                         // per-row bias of slab row (lane % 32)
+            if (hooked && p.hook.bias_kind == BIAS_PER_ROW) {
+                const int64_t m = m0 + wm * C::WTM + mi * 32 + (lane & 31);
+                if (m < p.M) brow = p.hook.bias[m];
+            }
+            asm volatile("" ::: "memory");
+            __builtin_amdgcn_sched_barrier(0);         // one slab's accumulators out of the accumulation registers at a time
+            // 16-byte stores need aligned rows; on edge tiles also that no lane's column group
+            // straddles N (then a group is either stored whole or not at all)
+            const bool vec_ok = !wsl && (p.flags & GF_C_VEC16) && !c_f32 && (interior || p.N % EPL == 0);
+            if (!vec_ok) {
+                // masked 4-element stores
+#pragma unroll 1
+                for (int g = 0; g < 32 / RPI; ++g) {
+                    const int row = g * RPI + orow;
+                    const int64_t m = m0 + wm * C::WTM + mi * 32 + row;
+                    const int64_t n = n0 + wn * C::WTN + ocol;
+                    const char *src = scr + row * SROW + ocol * 4;
+                    const float br = __shfl(brow, row);                // (every lane takes part)
+                    if (m < p.M) {
+#pragma unroll
+                        for (int q = 0; q < 4 / C::ESZ; ++q) {         // 4 elements at a time
+                            const int64_t nn = n + q * 4, left = p.N - nn;
+                            if (left > 0) {
+                                const int nvalid = left >= 4 ? 4 : (int)left;
+                                const f32x4 t = *(const f32x4 *)(src + q * 16);
+                                const float x[4] = {t[0], t[1], t[2], t[3]};
+                                if (wsl) store4<DT_F32>(wsl, m * p.N + nn, x, 1.0f, 0.0f, ws_vec, nvalid);
+                                else {
+                                    const bool per_row = p.hook.bias_kind == BIAS_PER_ROW;
+                                    const float b[4] = {per_row ? br : bcol[q * 4 + 0], per_row ? br : bcol[q * 4 + 1],
+                                                        per_row ? br : bcol[q * 4 + 2], per_row ? br : bcol[q * 4 + 3]};
+                                    if (c_f32)
+                                        store4<DT_F32>(p.C, m * p.ldc + nn, x, p.alpha, p.beta, c_vec, nvalid,
+                                                       hooked, p.hook.act, has_bias, b);
+                                    else
+                                        store4<C::DT>(p.C, m * p.ldc + nn, x, p.alpha, p.beta, c_vec, nvalid,
+                                                      hooked, p.hook.act, has_bias, b);
+                                }
+                            }
+                        }
+                    }
+                }
+                if (mi + 1 < SLABS) write_slab(mi + 1, scr);
+            } else {
+                // All rows of the slab are fetched from LDS first, so that one LDS latency is
+                // paid per slab and not per row; PLAIN (interior, beta == 0, no fused step) is straight-line.
+                auto vector_readout = [&](auto plain_c) {
+                    constexpr bool PLAIN = decltype(plain_c)::value != 0;
+                    constexpr int G = 32 / RPI;
+                    f32x4 lo[G], hi[G];
+#pragma unroll
+                    for (int g = 0; g < G; ++g) {
+                        const char *src = scr + (g * RPI + orow) * SROW + ocol * 4;
+                        lo[g] = *(const f32x4 *)src;
+                        if constexpr (C::DT != DT_F32) hi[g] = *(const f32x4 *)(src + 16);
+                    }
+                    // per-row bias of the rows this lane stores, handed round (every lane takes part)
+                    // before the next slab's writes queue up behind the shuffles
+                    float brs[G];
+                    const bool per_row = !PLAIN && hooked && p.hook.bias_kind == BIAS_PER_ROW;
+                    if (per_row) {
+#pragma unroll
+                        for (int g = 0; g < G; ++g) brs[g] = __shfl(brow, g * RPI + orow);
+                    }
+                    if (mi + 1 < SLABS) write_slab(mi + 1, scr);
+#pragma unroll
+                    for (int g = 0; g < G; ++g) {
+                        const int row = g * RPI + orow;
+                        const int64_t m = m0 + wm * C::WTM + mi * 32 + row;
+                        const int64_t n = n0 + wn * C::WTN + ocol;
+                        float b[EPL];                                  // this row's bias, if any
+                        if (!PLAIN && !interior && !(m < p.M && n + EPL <= p.N)) continue;
+                        if (!PLAIN && hooked) {
+#pragma unroll
+                            for (int e = 0; e < EPL; ++e) b[e] = per_row ? brs[g] : bcol[e];
+                        }
+                        if constexpr (C::DT == DT_F32) {
+                            f32x4 o = lo[g];
+                            o[0] *= p.alpha; o[1] *= p.alpha; o[2] *= p.alpha; o[3] *= p.alpha;
+                            float *dst = (float *)p.C + m * p.ldc + n;
+                            if (!PLAIN && p.beta != 0.0f) {
+                                const f32x4 c = *(const f32x4 *)dst;
+                                o[0] += p.beta * c[0]; o[1] += p.beta * c[1]; o[2] += p.beta * c[2]; o[3] += p.beta * c[3];
+                            }
+                            if (!PLAIN && hooked) {
+                                float oh[4] = {o[0], o[1], o[2], o[3]};
+                                hook_apply(p.hook.act, has_bias, oh, b);
+                                o[0] = oh[0]; o[1] = oh[1]; o[2] = oh[2]; o[3] = oh[3];
+                            }
+                            *(f32x4 *)dst = o;
+                        } else {
+                            float o[8] = {p.alpha * lo[g][0], p.alpha * lo[g][1], p.alpha * lo[g][2], p.alpha * lo[g][3],
+                                          p.alpha * hi[g][0], p.alpha * hi[g][1], p.alpha * hi[g][2], p.alpha * hi[g][3]};
+                            uint16_t *dst = (uint16_t *)p.C + m * p.ldc + n;
+                            union { u32x4 u; _Float16 h[8]; __bf16 b[8]; } pk;
+                            if (!PLAIN && p.beta != 0.0f) {
+                                pk.u = *(const u32x4 *)dst;
+#pragma unroll
+                                for (int e = 0; e < 8; ++e) o[e] += p.beta * (C::DT == DT_F16 ? (float)pk.h[e] : (float)pk.b[e]);
+                            }
+                            if (!PLAIN && hooked) hook_apply(p.hook.act, has_bias, o, b);
+#pragma unroll
+                            for (int e = 0; e < 8; ++e) {
+                                if (C::DT == DT_F16) pk.h[e] = (_Float16)o[e];
+                                else pk.b[e] = (__bf16)o[e];
+                            }
+                            *(u32x4 *)dst = pk.u;
+                        }
+                    }
+                };
+                if (p.beta == 0.0f && !hooked && interior) vector_readout(IC<1>{});
+                else vector_readout(IC<0>{});
+            }
+            asm volatile("" ::: "memory");
+            __builtin_amdgcn_sched_barrier(0);
+        }
+    }
 }
 
 // ---------------------------------------------------------------------------
@@ -1292,233 +1494,49 @@ __global__ __launch_bounds__(C::NT) void gemm_kernel(const GemmArgs p)
 
     if (DLOADS > 0) wait_vmcnt<0>();    // refetches past the end must land before this workgroup's LDS is given away
 
-    // epilogue
-    const bool c_vec = p.flags & GF_C_VEC, ws_vec = p.flags & GF_WS_VEC;
-    float *wsl = p.split > 1 ? p.ws + (int64_t)slice * p.M * p.N : nullptr;
-    const bool interior = m0 + C::BM <= p.M && n0 + C::BN <= p.N;      // whole tile inside C: no masks
-    // Each wave turns its 32-row slabs around in LDS (fp32, padded rows) so that a
-    // store instruction writes whole row segments of the wave tile (16 bytes per
-    // lane, WTN elements per row) instead of 32 scattered 8-byte pieces.  Interior
-    // tiles with 16-byte aligned C rows store vectors; edge tiles, unaligned rows and
-    // split-K partials leave through the same turnaround with masked stores, so the
-    // accumulators have one way out and never wait in ordinary registers.
-    constexpr int SROW = C::WTN * 4 + 16;                              // scratch row stride, bytes
-    static_assert(32 * SROW * C::NW <= C::LDS_BYTES, "the staging buffers are large enough for the turnaround");
-    {
-        lds_barrier();                                                 // nobody still reads the last stage
-        char *scr = lds + wave * (32 * SROW);
-        constexpr int OUT_ROW = C::WTN * C::ESZ;                       // bytes of one output row of the wave tile
-        constexpr int LPR = OUT_ROW / 16;                              // lanes per row on the way out
-        constexpr int RPI = 64 / LPR;                                  // rows per store instruction
-        static_assert(OUT_ROW % 16 == 0 && 64 % LPR == 0 && 32 % RPI == 0, "wave tile rows split into 16-byte pieces");
-        const int orow = lane / LPR, ocol = (lane % LPR) * (16 / C::ESZ);   // row within the group, first column (elements)
-        // fused step: a lane stores the same columns of every row, so their bias is fetched once
-        const bool hooked = !wsl && hook_active(p.hook), has_bias = p.hook.bias_kind != BIAS_NONE;
-        const bool c_f32 = C::DT != DT_F32 && (p.flags & GF_C_F32);    // fp32 C of a 16-bit kernel: masked readout
-        constexpr int EPL = 16 / C::ESZ;                               // elements per lane and row
-        float bcol[EPL];
+    // epilogue: the accumulators of slab mi (32 rows of the wave tile) go to LDS ...
+    // (raw accumulators: alpha is applied on the way back, so that accumulators held in
+    // AGPRs can go to LDS without passing through the ordinary registers)
+    auto write_slab = [&](int mi, char *scr) {
+        constexpr int SROW = C::WTN * 4 + 16;
 #pragma unroll
-        for (int e = 0; e < EPL; ++e) bcol[e] = 0.0f;
-        if (hooked && p.hook.bias_kind == BIAS_PER_COLUMN) {
-            const int64_t n = n0 + wn * C::WTN + ocol;
+        for (int ni = 0; ni < C::NI; ++ni)
 #pragma unroll
-            for (int e = 0; e < EPL; ++e)
-                if (n + e < p.N) bcol[e] = p.hook.bias[n + e];
-        }
-        // Plain runs of the 16-bit kernels on interior tiles (beta == 0, no fused step): the slab
-        // goes through LDS already scaled and rounded, 8 bytes per lane and 4-column group, which
-        // halves the LDS traffic of the turnaround; the way back is a 16-byte read and the store.
-        // Rows r and r + 16 would meet in the same banks (row stride = 4 banks mod 64), so the
-        // 8-byte groups of rows 16..31 swap places pairwise; the reader swaps them back.
-        if constexpr (C::DT != DT_F32) {
-            if (interior && !wsl && (p.flags & GF_C_VEC16) && !c_f32 && p.beta == 0.0f && !hooked) {
-                constexpr int SROW16 = C::WTN * 2 + 16;
-                constexpr int G = 32 / RPI;
-                char *scr16 = lds + wave * (32 * SROW16);
-                auto write16 = [&](int mi) {
-#pragma unroll
-                    for (int ni = 0; ni < C::NI; ++ni)
-#pragma unroll
-                        for (int vq = 0; vq < 4; ++vq) {
-                            float x[4];
-#pragma unroll
-                            for (int j = 0; j < 4; ++j) {
-                                if constexpr (C::ACC_AGPR) {
-                                    // copied out of the accumulation registers here, group by group (left to
-                                    // itself the compiler copies all of them ahead of the branch and spills)
-                                    asm volatile("v_accvgpr_read_b32 %0, %1" : "=v"(x[j]) : "a"(acc[mi][ni][vq * 4 + j]));
-                                } else {
-                                    x[j] = acc[mi][ni][vq * 4 + j];
-                                }
-                                x[j] *= p.alpha;
-                            }
-                            union { u32x2 u; _Float16 h[4]; __bf16 b[4]; } pk;
-#pragma unroll
-                            for (int j = 0; j < 4; ++j) {
-                                if (C::DT == DT_F16) pk.h[j] = (_Float16)x[j];
-                                else pk.b[j] = (__bf16)x[j];
-                            }
-                            const int grp = (ni * 8 + vq * 2 + half) ^ (r32 >> 4);
-                            *(u32x2 *)(scr16 + r32 * SROW16 + grp * 8) = pk.u;
-                        }
-                };
-                write16(0);
-#pragma unroll
-                for (int mi = 0; mi < C::MI; ++mi) {
-                    u32x4 v[G];
-#pragma unroll
-                    for (int g = 0; g < G; ++g)
-                        v[g] = *(const u32x4 *)(scr16 + (g * RPI + orow) * SROW16 + ocol * 2);
-                    if (mi + 1 < C::MI) write16(mi + 1);      // in-order LDS: lands after the reads above
-#pragma unroll
-                    for (int g = 0; g < G; ++g) {
-                        const int64_t m = m0 + wm * C::WTM + mi * 32 + g * RPI + orow;
-                        const int64_t n = n0 + wn * C::WTN + ocol;
-                        const u32x4 o = (((g * RPI) >> 4) & 1) ? u32x4{v[g][2], v[g][3], v[g][0], v[g][1]} : v[g];
-                        *(u32x4 *)((uint16_t *)p.C + m * p.ldc + n) = o;
-                    }
-                }
-#ifdef PEAK_TRACE
-                trace_store();
-#endif
-                return;
+            for (int vq = 0; vq < 4; ++vq) {
+                f32x4 v = {acc[mi][ni][vq * 4 + 0], acc[mi][ni][vq * 4 + 1], acc[mi][ni][vq * 4 + 2], acc[mi][ni][vq * 4 + 3]};
+                *(f32x4 *)(scr + r32 * SROW + (ni * 32 + vq * 8 + half * 4) * 4) = v;
             }
-        }
-        // (raw accumulators: alpha is applied on the way back, so that accumulators held in
-        // AGPRs can go to LDS without passing through the ordinary registers)
-        auto write_slab = [&](int mi) {
+    };
+    // ... or, for plain runs of the 16-bit kernels, already scaled and rounded
+    auto write16 = [&](int mi, char *scr16) {
+        constexpr int SROW16 = C::WTN * 2 + 16;
 #pragma unroll
-            for (int ni = 0; ni < C::NI; ++ni)
+        for (int ni = 0; ni < C::NI; ++ni)
 #pragma unroll
-                for (int vq = 0; vq < 4; ++vq) {
-                    f32x4 v = {acc[mi][ni][vq * 4 + 0], acc[mi][ni][vq * 4 + 1], acc[mi][ni][vq * 4 + 2], acc[mi][ni][vq * 4 + 3]};
-                    *(f32x4 *)(scr + r32 * SROW + (ni * 32 + vq * 8 + half * 4) * 4) = v;
+            for (int vq = 0; vq < 4; ++vq) {
+                float x[4];
+#pragma unroll
+                for (int j = 0; j < 4; ++j) {
+                    if constexpr (C::ACC_AGPR) {
+                        // copied out of the accumulation registers here, group by group (left to
+                        // itself the compiler copies all of them ahead of the branch and spills)
+                        asm volatile("v_accvgpr_read_b32 %0, %1" : "=v"(x[j]) : "a"(acc[mi][ni][vq * 4 + j]));
+                    } else {
+                        x[j] = acc[mi][ni][vq * 4 + j];
+                    }
+                    x[j] *= p.alpha;
                 }
-        };
-        // A wave's LDS instructions execute in the order issued, so the next slab may be
-        // written into the same scratch as soon as this slab's reads are issued: the writes
-        // then run while this slab is converted and stored.
-        write_slab(0);
+                union { u32x2 u; _Float16 h[4]; __bf16 b[4]; } pk;
 #pragma unroll
-        for (int mi = 0; mi < C::MI; ++mi) {
-            float brow = 0.0f;                                         // per-row bias of slab row (lane % 32)
-            if (hooked && p.hook.bias_kind == BIAS_PER_ROW) {
-                const int64_t m = m0 + wm * C::WTM + mi * 32 + (lane & 31);
-                if (m < p.M) brow = p.hook.bias[m];
-            }
-            asm volatile("" ::: "memory");
-            __builtin_amdgcn_sched_barrier(0);         // one slab's accumulators out of the accumulation registers at a time
-            // 16-byte stores need aligned rows; on edge tiles also that no lane's column group
-            // straddles N (then a group is either stored whole or not at all)
-            const bool vec_ok = !wsl && (p.flags & GF_C_VEC16) && !c_f32 && (interior || p.N % EPL == 0);
-            if (!vec_ok) {
-                // masked 4-element stores
-#pragma unroll 1
-                for (int g = 0; g < 32 / RPI; ++g) {
-                    const int row = g * RPI + orow;
-                    const int64_t m = m0 + wm * C::WTM + mi * 32 + row;
-                    const int64_t n = n0 + wn * C::WTN + ocol;
-                    const char *src = scr + row * SROW + ocol * 4;
-                    const float br = __shfl(brow, row);                // (every lane takes part)
-                    if (m < p.M) {
-#pragma unroll
-                        for (int q = 0; q < 4 / C::ESZ; ++q) {         // 4 elements at a time
-                            const int64_t nn = n + q * 4, left = p.N - nn;
-                            if (left > 0) {
-                                const int nvalid = left >= 4 ? 4 : (int)left;
-                                const f32x4 t = *(const f32x4 *)(src + q * 16);
-                                const float x[4] = {t[0], t[1], t[2], t[3]};
-                                if (wsl) store4<DT_F32>(wsl, m * p.N + nn, x, 1.0f, 0.0f, ws_vec, nvalid);
-                                else {
-                                    const bool per_row = p.hook.bias_kind == BIAS_PER_ROW;
-                                    const float b[4] = {per_row ? br : bcol[q * 4 + 0], per_row ? br : bcol[q * 4 + 1],
-                                                        per_row ? br : bcol[q * 4 + 2], per_row ? br : bcol[q * 4 + 3]};
-                                    if (c_f32)
-                                        store4<DT_F32>(p.C, m * p.ldc + nn, x, p.alpha, p.beta, c_vec, nvalid,
-                                                       hooked, p.hook.act, has_bias, b);
-                                    else
-                                        store4<C::DT>(p.C, m * p.ldc + nn, x, p.alpha, p.beta, c_vec, nvalid,
-                                                      hooked, p.hook.act, has_bias, b);
-                                }
-                            }
-                        }
-                    }
+                for (int j = 0; j < 4; ++j) {
+                    if (C::DT == DT_F16) pk.h[j] = (_Float16)x[j];
+                    else pk.b[j] = (__bf16)x[j];
                 }
-                if (mi + 1 < C::MI) write_slab(mi + 1);
-            } else {
-                // All rows of the slab are fetched from LDS first, so that one LDS latency is
-                // paid per slab and not per row; PLAIN (interior, beta == 0, no fused step) is straight-line.
-                auto vector_readout = [&](auto plain_c) {
-                    constexpr bool PLAIN = decltype(plain_c)::value != 0;
-                    constexpr int G = 32 / RPI;
-                    f32x4 lo[G], hi[G];
-#pragma unroll
-                    for (int g = 0; g < G; ++g) {
-                        const char *src = scr + (g * RPI + orow) * SROW + ocol * 4;
-                        lo[g] = *(const f32x4 *)src;
-                        if constexpr (C::DT != DT_F32) hi[g] = *(const f32x4 *)(src + 16);
-                    }
-                    // per-row bias of the rows this lane stores, handed round (every lane takes part)
-                    // before the next slab's writes queue up behind the shuffles
-                    float brs[G];
-                    const bool per_row = !PLAIN && hooked && p.hook.bias_kind == BIAS_PER_ROW;
-                    if (per_row) {
-#pragma unroll
-                        for (int g = 0; g < G; ++g) brs[g] = __shfl(brow, g * RPI + orow);
-                    }
-                    if (mi + 1 < C::MI) write_slab(mi + 1);
-#pragma unroll
-                    for (int g = 0; g < G; ++g) {
-                        const int row = g * RPI + orow;
-                        const int64_t m = m0 + wm * C::WTM + mi * 32 + row;
-                        const int64_t n = n0 + wn * C::WTN + ocol;
-                        float b[EPL];                                  // this row's bias, if any
-                        if (!PLAIN && !interior && !(m < p.M && n + EPL <= p.N)) continue;
-                        if (!PLAIN && hooked) {
-#pragma unroll
-                            for (int e = 0; e < EPL; ++e) b[e] = per_row ? brs[g] : bcol[e];
-                        }
-                        if constexpr (C::DT == DT_F32) {
-                            f32x4 o = lo[g];
-                            o[0] *= p.alpha; o[1] *= p.alpha; o[2] *= p.alpha; o[3] *= p.alpha;
-                            float *dst = (float *)p.C + m * p.ldc + n;
-                            if (!PLAIN && p.beta != 0.0f) {
-                                const f32x4 c = *(const f32x4 *)dst;
-                                o[0] += p.beta * c[0]; o[1] += p.beta * c[1]; o[2] += p.beta * c[2]; o[3] += p.beta * c[3];
-                            }
-                            if (!PLAIN && hooked) {
-                                float oh[4] = {o[0], o[1], o[2], o[3]};
-                                hook_apply(p.hook.act, has_bias, oh, b);
-                                o[0] = oh[0]; o[1] = oh[1]; o[2] = oh[2]; o[3] = oh[3];
-                            }
-                            *(f32x4 *)dst = o;
-                        } else {
-                            float o[8] = {p.alpha * lo[g][0], p.alpha * lo[g][1], p.alpha * lo[g][2], p.alpha * lo[g][3],
-                                          p.alpha * hi[g][0], p.alpha * hi[g][1], p.alpha * hi[g][2], p.alpha * hi[g][3]};
-                            uint16_t *dst = (uint16_t *)p.C + m * p.ldc + n;
-                            union { u32x4 u; _Float16 h[8]; __bf16 b[8]; } pk;
-                            if (!PLAIN && p.beta != 0.0f) {
-                                pk.u = *(const u32x4 *)dst;
-#pragma unroll
-                                for (int e = 0; e < 8; ++e) o[e] += p.beta * (C::DT == DT_F16 ? (float)pk.h[e] : (float)pk.b[e]);
-                            }
-                            if (!PLAIN && hooked) hook_apply(p.hook.act, has_bias, o, b);
-#pragma unroll
-                            for (int e = 0; e < 8; ++e) {
-                                if (C::DT == DT_F16) pk.h[e] = (_Float16)o[e];
-                                else pk.b[e] = (__bf16)o[e];
-                            }
-                            *(u32x4 *)dst = pk.u;
-                        }
-                    }
-                };
-                if (p.beta == 0.0f && !hooked && interior) vector_readout(IC<1>{});
-                else vector_readout(IC<0>{});
+                const int grp = (ni * 8 + vq * 2 + half) ^ (r32 >> 4);
+                *(u32x2 *)(scr16 + r32 * SROW16 + grp * 8) = pk.u;
             }
-            asm volatile("" ::: "memory");
-            __builtin_amdgcn_sched_barrier(0);
-        }
-    }
+    };
+    epilogue_slabs<C, C::MI>(p, lds, wave, lane, wm, wn, m0, n0, slice, write_slab, write16);
 #ifdef PEAK_TRACE
     trace_store();
 #endif

@@ -29,7 +29,8 @@ static const std::vector<Variant> &variants()
     static const std::vector<Variant> table = [] {
         std::vector<Variant> t;
         const VariantGroup groups[] = {variants_general(), variants_bf16_nt(), variants_f16_nt(), variants_bf16_nn(),
-                                       variants_f16_nn(),  variants_f32(),     variants_ta(),     variants_skinny()};
+                                       variants_f16_nn(),  variants_f32(),     variants_ta(),     variants_skinny(),
+                                       variants_mf16()};
         for (const VariantGroup &g : groups) t.insert(t.end(), g.rows, g.rows + g.count);
         return t;
     }();
@@ -139,6 +140,7 @@ static double tiled_cost(const Variant &v, const peak_gemm_desc_t &d, int split)
     if (v.tr) eff *= v.dt == DT_F32 ? 1.10 : 1.03;      // B staged directly: no register transposition, no masked loads
     if (v.lds > 140 * 1024 && v.ns == 2 && !v.tr) eff *= 1.02;   // third A stage, A's loads spread over the step (+2 % measured; nothing with [k][n] B)
     if (v.nt == 256 && v.bm == 256 && v.bn == 256 && v.lds > 140 * 1024) eff *= 1.02;   // one wave per SIMD on top of that
+    if (v.mf16) eff *= 1.10;                            // 16x16x32 MFMA: same cycles, higher clock (+10 % measured)
     if (v.atr) eff *= 1.5;                              // likewise A; the alternative is the register-staged general tile
     if (v.dt == DT_F32 && v.ns == 3) eff *= 0.97;
     const double fixed = 12.0e6;                    // prologue + epilogue of one tile, same units

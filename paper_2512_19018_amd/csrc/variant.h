@@ -28,6 +28,7 @@ struct Variant {
     int atr;             // A (K x M) goes to LDS untransposed ([k][m] rows)
     int sweep_only;      // 1: reachable through the force bits only (kept for sweeps); the selector skips it
     int stream_rank;     // streaming (skinny) kernels: 2 = the selector's first choice, 1 = its second, 0 = sweeps only
+    int mf16;            // built on the 16x16x32 MFMA (holds a higher clock under the chip's power limit)
 };
 
 struct VariantGroup {
@@ -44,6 +45,7 @@ VariantGroup variants_f16_nn();
 VariantGroup variants_f32();
 VariantGroup variants_ta();
 VariantGroup variants_skinny();
+VariantGroup variants_mf16();
 
 template <class C>
 static hipError_t launch_gemm(const GemmArgs &a, dim3 grid, hipStream_t s)

@@ -53,7 +53,7 @@ def test_exact_integers_every_variant(gu, oracle, dtype, transA, transB):
     fragment layout, the swizzle, the transposing stores and the edge masks of
     every kernel variant built for the layout."""
     for vid, name in gu.variants_for(dtype, transA, transB):
-        direct = bool(re.search(r"_(?:d|t|p|pt)\d", name)) or "skinny" in name
+        direct = bool(re.search(r"_(?:d|t|p|pt|m)\d", name)) or "skinny" in name
         # K <= 64 keeps |sum| <= 4*64 = 256
         if "skinny" in name:
             m = re.search(r"k(\d+)s", name)
@@ -100,7 +100,7 @@ def test_random_every_direct_variant_deep_k(gu, oracle, dtype):
     their staging rings several times, ragged M and N."""
     for transA, transB in LAYOUTS:
         for vid, name in gu.variants_for(dtype, transA, transB):
-            if not (re.search(r"_(?:d|t|p|pt)\d", name) or "skinny" in name):
+            if not (re.search(r"_(?:d|t|p|pt|m)\d", name) or "skinny" in name):
                 continue
             # tiled kernels also get a K that ends inside the last K tile (of the last K slice)
             shapes = [(13, 1000, 4096)] if "skinny" in name else [(300, 520, 1024), (260, 264, 1000)]
@@ -302,7 +302,7 @@ def test_exact_integers_deep_k_every_direct_variant(gu, oracle, dtype):
     limit = {pi.F32: 2 ** 24, pi.F16: 2048, pi.BF16: 256}[dtype]
     for transA, transB in LAYOUTS:
         for vid, name in gu.variants_for(dtype, transA, transB):
-            if not (re.search(r"_(?:d|t|p|pt)\d", name) or "skinny" in name):
+            if not (re.search(r"_(?:d|t|p|pt|m)\d", name) or "skinny" in name):
                 continue
             if "skinny" in name:
                 shapes = [(13, 1000, 4096), (16, 264, 4096)]

@@ -128,8 +128,8 @@ def test_plans_for_the_graded_workloads():
             info[name] = p.info()
     assert "f32_" in info["C1"] and "_nn" in info["C1"]
     assert ("f32_d" in info["C2"] or "f32_t" in info["C2"]) and "_nn" in info["C2"]
-    assert "bf16_d256x256" in info["C3"] and "_nt" in info["C3"] and "tiles 32x32" in info["C3"]
-    assert "bf16_d256x256" in info["C3b"]
+    assert "bf16_m256x256" in info["C3"] and "_nt" in info["C3"] and "tiles 32x32" in info["C3"]
+    assert "bf16_m256x256" in info["C3b"]
     assert ("f16_d" in info["C4"] or "f16_t" in info["C4"]) and "_nn" in info["C4"] and "tiles 20x12" in info["C4"]
     assert "skinny" in info["C5"]
 
@@ -165,7 +165,7 @@ def test_selector_table_overrides_the_cost_model(tmp_path):
     try:
         with pg.Plan(8192, 8192, 8192, pg.PEAK_DT_BF16, 0, 1) as p:
             default = p.info()
-        assert "bf16_d256x256w" in default
+        assert "bf16_m256x256w" in default
         table = tmp_path / "table.txt"
         table.write_text("# comment\n"
                          "bf16 0 1 8192 8192 8192 bf16_d256x128w8_nt 2   # 900.0 us\n"
@@ -181,7 +181,7 @@ def test_selector_table_overrides_the_cost_model(tmp_path):
             assert "bf16_r128x128_nt" in p.info()
         # another shape: untouched
         with pg.Plan(4096, 4096, 4096, pg.PEAK_DT_BF16, 0, 1) as p:
-            assert "bf16_d256x256w" in p.info()
+            assert "bf16_m256x256w" in p.info()
         # forcing still wins over the table
         names = [pg.peak_gemm_variant_name(i) for i in range(pg.peak_gemm_variant_count())]
         with pg.Plan(8192, 8192, 8192, pg.PEAK_DT_BF16, 0, 1,
