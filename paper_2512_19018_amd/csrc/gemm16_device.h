@@ -1,5 +1,5 @@
 // Tiled kernel built on the 16x16x32 MFMA (v_mfma_f32_16x16x32_{bf16,f16}) for
-// 16-bit operands that both run along K in memory: 256x256 workgroup tile, four
+// 16-bit operands in any of the four layouts: 256x256 workgroup tile, four
 // waves (one per SIMD) with a 128x128 wave tile each, i.e. 8 x 8 blocks of 16x16
 // whose 256 accumulator registers sit in the accumulation half of the register
 // file.  Measured on MI355X, the chip is power limited under a matrix load and
@@ -12,7 +12,10 @@
 // staging (Pipelining: three A stages and two B stages of 64 k, filled by
 // direct-to-LDS buffer loads), the XOR placement of 16-byte chunks (Offset), the
 // tile order (Block-Swizzle), Split-K slices and the epilogue are those of
-// gemm_kernel.
+// gemm_kernel.  An operand that does not run along K in memory (A stored K x M,
+// B stored K x N) is staged as it lies, [k][m] or [k][n] rows, and its fragments
+// come back through the transposing LDS read (the paper's Transpose, done by the
+// LDS hardware on the way out instead of in registers on the way in).
 #pragma once
 
 #include "gemm_device.h"
@@ -21,10 +24,12 @@ namespace peak {
 
 typedef float f32x4v __attribute__((ext_vector_type(4)));
 
-template <int DT_>
+template <int DT_, bool A_KM_ = false, bool B_KN_ = false>
 struct Cfg16 {
     static_assert(DT_ == DT_F16 || DT_ == DT_BF16, "16-bit storage");
     static constexpr int DT = DT_;
+    static constexpr bool A_KM = A_KM_;                      // A stored K x M: staged as [k][m] rows
+    static constexpr bool B_KN = B_KN_;                      // B stored K x N: staged as [k][n] rows
     static constexpr int ESZ = 2, EPC = 8;
     static constexpr int BM = 256, BN = 256, RB = 128, CPR = 8, BK = 64;
     static constexpr int WAVES_M = 2, WAVES_N = 2, NW = 4, NT = 256;
@@ -53,6 +58,12 @@ __global__ __launch_bounds__(C::NT) void gemm16_kernel(const GemmArgs p)
     const int lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int wm = wave / C::WAVES_N, wn = wave % C::WAVES_N;
     const int r16 = lane & 15, q = lane >> 4;
+#ifdef PEAK_TRACE
+    // Diagnostic build only: per wave, shader-clock time stamps of the kernel's phases and the
+    // cycles spent at the K loop's waits, written to the workspace.
+    const uint64_t tr_start = __builtin_amdgcn_s_memtime();
+    uint64_t tr_loop0 = 0, tr_loop1 = 0, tr_w0 = 0, tr_w1 = 0, tr_wait_sum = 0, tr_wait_max = 0;
+#endif
 
     const int tiles = p.tiles_m * p.tiles_n;
     const int bid = blockIdx.x;
@@ -76,8 +87,9 @@ __global__ __launch_bounds__(C::NT) void gemm16_kernel(const GemmArgs p)
 #pragma unroll
         for (int nb = 0; nb < C::NB; ++nb) acc[mb][nb] = f32x4v{0.0f, 0.0f, 0.0f, 0.0f};
 
-    // fragment of k-step ks: lane reads row (lane % 16) of its block, chunk 4 * ks + lane / 16
-    // (8 k).  One address per operand and k-step; blocks and stages go into the immediate.
+    // Fragment of k-step ks for an operand staged along K: lane reads row (lane % 16) of its
+    // block, chunk 4 * ks + lane / 16 (8 k).  One address per operand and k-step; blocks and
+    // stages go into the read's immediate offset.
     int a_base[C::KS], b_base[C::KS];
 #pragma unroll
     for (int ks = 0; ks < C::KS; ++ks) {
@@ -85,35 +97,119 @@ __global__ __launch_bounds__(C::NT) void gemm16_kernel(const GemmArgs p)
         a_base[ks] = ra * C::RB + (((4 * ks + q) ^ C::swizzle(ra)) << 4);
         b_base[ks] = C::NSA * C::A_BYTES + rb * C::RB + (((4 * ks + q) ^ C::swizzle(rb)) << 4);
     }
-    auto read_a = [&](auto stagec, auto ksc, auto ic) -> u32x4 {
-        constexpr int off = decltype(stagec)::value * C::A_BYTES + decltype(ic)::value * 16 * C::RB;
-        return *(const u32x4 *)(lds + a_base[decltype(ksc)::value] + off);
+    // Operand staged as [k][x] rows (x = m or n; 512 bytes per k-row, chunk c of row k at
+    // c ^ 4 * (k & 3)): the transposing read works on groups of 16 lanes, which together
+    // point at 4 k-rows x 16 x (lane i of the group at k-row i / 4, columns 4 * (i % 4) .. + 3)
+    // and each get the 4 k of one x.  Group lane / 16 takes k-rows 8 * (lane / 16) .. + 3, a
+    // second read 4 rows on takes the other half of the lane's 8 k.  One address per block
+    // (the swizzle does not commute with the block's column offset); k-step (32 rows), the
+    // second read (4 rows) and the stage go into the immediate.
+    int a_kx[C::A_KM ? C::MB : 1], a_kx2[C::A_KM ? C::MB : 1], b_kx[C::B_KN ? C::NB : 1];
+    {
+        const int krow = 8 * q + (r16 >> 2);
+        if constexpr (C::A_KM) {
+#pragma unroll
+            for (int i = 0; i < C::MB; ++i) {
+                const int col = wm * C::WTM + i * 16 + 4 * (r16 & 3);
+                a_kx[i] = krow * (C::BM * C::ESZ) + (((col >> 3) ^ (4 * (krow & 3))) << 4) + (r16 & 1) * 8;
+                a_kx2[i] = a_kx[i] + 2 * C::A_BYTES;
+            }
+        }
+        if constexpr (C::B_KN) {
+#pragma unroll
+            for (int i = 0; i < C::NB; ++i) {
+                const int col = wn * C::WTN + i * 16 + 4 * (r16 & 3);
+                b_kx[i] = C::NSA * C::A_BYTES + krow * (C::BN * C::ESZ) + (((col >> 3) ^ (4 * (krow & 3))) << 4) + (r16 & 1) * 8;
+            }
+        }
+    }
+    const uint32_t lds_b0 = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) char *)lds;
+    u32x4 af[2][C::MB], bf[2][C::NB];
+    // halves of the fragments read with the transposing read, which goes out as assembly: the
+    // compiler's wait-count pass would put a wait for every outstanding direct-to-LDS load in
+    // front of it (it takes them to alias).  They are handed over by settle() at the start of the
+    // k-step that uses them, after a wait for everything the wave has asked of LDS.
+    u32x2 al[2][C::A_KM ? C::MB : 1], ah[2][C::A_KM ? C::MB : 1], bl[2][C::B_KN ? C::NB : 1], bh[2][C::B_KN ? C::NB : 1];
+    auto read_a = [&](auto stagec, auto ksc, auto ic, auto setc) {
+        constexpr int stage = decltype(stagec)::value, ks = decltype(ksc)::value, i = decltype(ic)::value, set = decltype(setc)::value;
+        if constexpr (C::A_KM) {
+            // (the immediate holds 16 bits: the third stage goes through an address of its own)
+            constexpr int off = (stage % 2) * C::A_BYTES + ks * 32 * (C::BM * C::ESZ);
+            const uint32_t a0 = lds_b0 + (stage < 2 ? a_kx[i] : a_kx2[i]);
+            u32x2 &lo = al[set][i], &hi = ah[set][i];
+            asm volatile("ds_read_b64_tr_b16 %0, %1 offset:%2" : "=v"(lo) : "v"(a0), "n"(off) : "memory");
+            asm volatile("ds_read_b64_tr_b16 %0, %1 offset:%2" : "=v"(hi) : "v"(a0), "n"(off + 4 * C::BM * C::ESZ) : "memory");
+        } else {
+            constexpr int off = stage * C::A_BYTES + i * 16 * C::RB;
+            af[set][i] = *(const u32x4 *)(lds + a_base[ks] + off);
+        }
     };
-    auto read_b = [&](auto stagec, auto ksc, auto ic) -> u32x4 {
-        constexpr int off = decltype(stagec)::value * C::B_BYTES + decltype(ic)::value * 16 * C::RB;
-        return *(const u32x4 *)(lds + b_base[decltype(ksc)::value] + off);
+    auto read_b = [&](auto stagec, auto ksc, auto ic, auto setc) {
+        constexpr int stage = decltype(stagec)::value, ks = decltype(ksc)::value, i = decltype(ic)::value, set = decltype(setc)::value;
+        if constexpr (C::B_KN) {
+            constexpr int off = stage * C::B_BYTES + ks * 32 * (C::BN * C::ESZ);
+            const uint32_t a0 = lds_b0 + b_kx[i];
+            u32x2 &lo = bl[set][i], &hi = bh[set][i];
+            asm volatile("ds_read_b64_tr_b16 %0, %1 offset:%2" : "=v"(lo) : "v"(a0), "n"(off) : "memory");
+            asm volatile("ds_read_b64_tr_b16 %0, %1 offset:%2" : "=v"(hi) : "v"(a0), "n"(off + 4 * C::BN * C::ESZ) : "memory");
+        } else {
+            constexpr int off = stage * C::B_BYTES + i * 16 * C::RB;
+            bf[set][i] = *(const u32x4 *)(lds + b_base[ks] + off);
+        }
+    };
+    // the assembly-read halves of `set` have arrived: hand them to the compiler
+    auto settle = [&](auto setc) {
+        constexpr int set = decltype(setc)::value;
+        if constexpr (C::A_KM || C::B_KN) {
+            __builtin_amdgcn_s_waitcnt(waitcnt_imm(63, 0));
+            if constexpr (C::A_KM) {
+#pragma unroll
+                for (int i = 0; i < C::MB; ++i) {
+                    u32x2 &lo = al[set][i], &hi = ah[set][i];
+                    asm volatile("" : "+v"(lo), "+v"(hi));
+                    af[set][i] = u32x4{lo[0], lo[1], hi[0], hi[1]};
+                }
+            }
+            if constexpr (C::B_KN) {
+#pragma unroll
+                for (int i = 0; i < C::NB; ++i) {
+                    u32x2 &lo = bl[set][i], &hi = bh[set][i];
+                    asm volatile("" : "+v"(lo), "+v"(hi));
+                    bf[set][i] = u32x4{lo[0], lo[1], hi[0], hi[1]};
+                }
+            }
+            __builtin_amdgcn_sched_barrier(0);
+        }
     };
 
     LoaderDirect<C, C::BM> dA;
     LoaderDirect<C, C::BN> dB;
-    constexpr int LA = LoaderDirect<C, C::BM>::PER_WAVE, LB = LoaderDirect<C, C::BN>::PER_WAVE;
-    static_assert(LoaderDirect<C, C::BM>::NINST % C::NW == 0 && LoaderDirect<C, C::BN>::NINST % C::NW == 0,
+    LoaderDirectKN<C, C::BM> nA;
+    LoaderDirectKN<C, C::BN> nB;
+    constexpr int LA = C::A_KM ? LoaderDirectKN<C, C::BM>::PER_WAVE : LoaderDirect<C, C::BM>::PER_WAVE;
+    constexpr int LB = C::B_KN ? LoaderDirectKN<C, C::BN>::PER_WAVE : LoaderDirect<C, C::BN>::PER_WAVE;
+    static_assert((C::A_KM ? LoaderDirectKN<C, C::BM>::NINST : LoaderDirect<C, C::BM>::NINST) % C::NW == 0 &&
+                  (C::B_KN ? LoaderDirectKN<C, C::BN>::NINST : LoaderDirect<C, C::BN>::NINST) % C::NW == 0,
                   "every wave issues the same number of loads");
     const int tail_k = __builtin_amdgcn_readfirstlane((int)(p.K - (int64_t)(p.ktiles_total - 1) * C::BK));
     const int tail_tile = tail_k < C::BK ? p.ktiles_total - 1 - kt_begin : -1;   // relative to the slice
-    dA.init(p.A, p.lda, m0, p.M, kbase, p.K, tail_k, wave, lane);
-    dB.init(p.B, p.ldb, n0, p.N, kbase, p.K, tail_k, wave, lane);
+    if constexpr (C::A_KM) nA.init(p.A, p.lda, m0, p.M, kbase, p.K, tail_k, wave, lane);
+    else dA.init(p.A, p.lda, m0, p.M, kbase, p.K, tail_k, wave, lane);
+    if constexpr (C::B_KN) nB.init(p.B, p.ldb, n0, p.N, kbase, p.K, tail_k, wave, lane);
+    else dB.init(p.B, p.ldb, n0, p.N, kbase, p.K, tail_k, wave, lane);
     auto a_stage = [&](int s) { return lds + s * C::A_BYTES; };
     auto b_stage = [&](int s) { return lds + C::NSA * C::A_BYTES + s * C::B_BYTES; };
     // Loads of tile kt, part PART of the wave's LA (LB) instructions.  Past the end the last
     // tile is fetched again into a free stage, so the count in flight stays what the waits assume.
     auto issue_a = [&](int kt, int sa, auto part) {
         const int kr = kt < KT ? kt : KT - 1;
-        dA.template issue<decltype(part)::value, LA>(a_stage(sa), kr, kr == tail_tile, wave);
+        if constexpr (C::A_KM) nA.template issue<decltype(part)::value, LA>(a_stage(sa), kr, kr == tail_tile, wave);
+        else dA.template issue<decltype(part)::value, LA>(a_stage(sa), kr, kr == tail_tile, wave);
     };
     auto issue_b = [&](int kt, int sb, auto part) {
         const int kr = kt < KT ? kt : KT - 1;
-        dB.template issue<decltype(part)::value, LB>(b_stage(sb), kr, kr == tail_tile, wave);
+        if constexpr (C::B_KN) nB.template issue<decltype(part)::value, LB>(b_stage(sb), kr, kr == tail_tile, wave);
+        else dB.template issue<decltype(part)::value, LB>(b_stage(sb), kr, kr == tail_tile, wave);
     };
 
     // Main loop.  One wave per SIMD: nothing else hides this wave's stalls, so the order of
@@ -127,13 +223,12 @@ __global__ __launch_bounds__(C::NT) void gemm16_kernel(const GemmArgs p)
     constexpr int NM = C::MB * C::NB;                        // MFMAs per k-step
     constexpr int NFR = C::MB + C::NB;                       // fragments per k-step
     static_assert(C::KS == 2 && LA % 2 == 0 && 2 * NFR <= NM, "slot plan below");
-    u32x4 af[2][C::MB], bf[2][C::NB];
     // fragment f of a k-step in the order the MFMAs first need them: B0, A0 .. A7, B1 .. B7
     auto fetch_one = [&](auto sac, auto sbc, auto ksc, auto fc) {
-        constexpr int f = decltype(fc)::value, set = decltype(ksc)::value;
-        if constexpr (f == 0) bf[set][0] = read_b(sbc, ksc, IC<0>{});
-        else if constexpr (f <= C::MB) af[set][f - 1] = read_a(sac, ksc, IC<f - 1>{});
-        else bf[set][f - C::MB] = read_b(sbc, ksc, IC<f - C::MB>{});
+        constexpr int f = decltype(fc)::value;
+        if constexpr (f == 0) read_b(sbc, ksc, IC<0>{}, ksc);
+        else if constexpr (f <= C::MB) read_a(sac, ksc, IC<f - 1>{}, ksc);
+        else read_b(sbc, ksc, IC<f - C::MB>{}, ksc);
     };
     auto mfma_one = [&](auto setc, auto jc) {
         constexpr int set = decltype(setc)::value, j = decltype(jc)::value;
@@ -160,6 +255,9 @@ __global__ __launch_bounds__(C::NT) void gemm16_kernel(const GemmArgs p)
     static_for<LB>([&](auto pc) { issue_b(1, 1, pc); });
     static_for<LA>([&](auto pc) { issue_a(1, 1, pc); });
     static_for<NFR>([&](auto fc) { fetch_one(IC<0>{}, IC<0>{}, IC<0>{}, fc); });
+#ifdef PEAK_TRACE
+    tr_loop0 = __builtin_amdgcn_s_memtime();
+#endif
     constexpr int U = 6;                                     // tiles per trip: both stage indices static
     for (int kt0 = 0; kt0 < KT; kt0 += U) {
         static_for<U>([&](auto uc) {
@@ -168,6 +266,14 @@ __global__ __launch_bounds__(C::NT) void gemm16_kernel(const GemmArgs p)
             const int kt = kt0 + u;
             if (kt < KT) {
                 // k-step 0
+                settle(IC<0>{});
+#ifdef PEAK_TRACE
+                {
+                    const uint64_t dw = tr_w1 - tr_w0;       // the wait of the tile before: stamps long since returned
+                    tr_wait_sum += dw;
+                    tr_wait_max = dw > tr_wait_max ? dw : tr_wait_max;
+                }
+#endif
                 __builtin_amdgcn_sched_barrier(0);
                 static_for<NM>([&](auto jc) {
                     constexpr int j = decltype(jc)::value;
@@ -177,8 +283,15 @@ __global__ __launch_bounds__(C::NT) void gemm16_kernel(const GemmArgs p)
                     __builtin_amdgcn_sched_barrier(0);
                 });
                 // k-step 1
+#ifdef PEAK_TRACE
+                tr_w0 = __builtin_amdgcn_s_memtime();
+#endif
                 wait_vmcnt<PENDING>();                       // own loads of tile kt+1
                 lds_barrier();                               // tile kt+1 complete, tile kt read
+#ifdef PEAK_TRACE
+                tr_w1 = __builtin_amdgcn_s_memtime();
+#endif
+                settle(IC<1>{});
                 __builtin_amdgcn_sched_barrier(0);
                 static_for<NM>([&](auto jc) {
                     constexpr int j = decltype(jc)::value;
@@ -191,8 +304,12 @@ __global__ __launch_bounds__(C::NT) void gemm16_kernel(const GemmArgs p)
             }
         });
     }
+    settle(IC<0>{});    // reads issued as assembly feed nothing here, but must have returned before their registers are reused
     // 16x16x32 MFMA: 4 passes of 4 cycles; an accumulator may be read 10 wait states after the issue
     asm volatile("s_nop 15" ::: "memory");
+#ifdef PEAK_TRACE
+    tr_loop1 = __builtin_amdgcn_s_memtime();
+#endif
     static_for<NM>([&](auto jc) {
         constexpr int j = decltype(jc)::value;
         f32x4v &c = acc[j % C::MB][j / C::MB];
@@ -234,6 +351,17 @@ __global__ __launch_bounds__(C::NT) void gemm16_kernel(const GemmArgs p)
             }
     };
     epilogue_slabs<C, C::WTM / 32>(p, lds, wave, lane, wm, wn, m0, n0, slice, write_slab, write16);
+#ifdef PEAK_TRACE
+    if (p.split == 1 && p.ws && lane == 0) {
+        const uint64_t tr_end = __builtin_amdgcn_s_memtime();
+        uint32_t hwid, xcc;
+        asm volatile("s_getreg_b32 %0, hwreg(HW_REG_HW_ID)" : "=s"(hwid));
+        asm volatile("s_getreg_b32 %0, hwreg(HW_REG_XCC_ID)" : "=s"(xcc));
+        uint64_t *dst = (uint64_t *)p.ws + ((size_t)blockIdx.x * C::NW + wave) * 8;
+        dst[0] = tr_start; dst[1] = tr_loop0; dst[2] = tr_loop1; dst[3] = tr_end;
+        dst[4] = tr_wait_sum; dst[5] = tr_wait_max; dst[6] = (uint64_t)hwid | ((uint64_t)xcc << 32); dst[7] = (uint64_t)p.ktiles_total;
+    }
+#endif
 #endif
 }
 

@@ -11,14 +11,21 @@ static hipError_t launch_gemm16(const GemmArgs &a, dim3 grid, hipStream_t s)
     return hipGetLastError();
 }
 
-#define TILED_MF16(NAME, DT)                                                                           \
-    {NAME, KIND_TILED, DT, 0, 0, 1, Cfg16<DT>::BM, Cfg16<DT>::BN, Cfg16<DT>::BK, Cfg16<DT>::NT, Cfg16<DT>::NSB,   \
-     Cfg16<DT>::LDS_BYTES, 0, &launch_gemm16<Cfg16<DT>>, 0, 0, 0, 0, 1}
+// AKM: A stored K x M, staged as [k][m] rows; BKN: B stored K x N, staged as [k][n] rows
+#define TILED_MF16(NAME, DT, AKM, BKN)                                                                 \
+    {NAME, KIND_TILED, DT, AKM, BKN, 1, 256, 256, 64, 256, 2,                                          \
+     Cfg16<DT, AKM != 0, BKN != 0>::LDS_BYTES, 0, &launch_gemm16<Cfg16<DT, AKM != 0, BKN != 0>>, BKN, AKM, 0, 0, 1}
 
 static const Variant rows_mf16[] = {
     // one wave per SIMD, 128x128 per wave as 8 x 8 blocks of 16x16, three A stages and two B stages
-    TILED_MF16("bf16_m256x256w4a3_nt", DT_BF16),
-    TILED_MF16("f16_m256x256w4a3_nt", DT_F16),
+    TILED_MF16("bf16_m256x256w4a3_nt", DT_BF16, 0, 0),
+    TILED_MF16("f16_m256x256w4a3_nt", DT_F16, 0, 0),
+    TILED_MF16("bf16_m256x256w4a3_nn", DT_BF16, 0, 1),
+    TILED_MF16("f16_m256x256w4a3_nn", DT_F16, 0, 1),
+    TILED_MF16("bf16_m256x256w4a3_tt", DT_BF16, 1, 0),
+    TILED_MF16("f16_m256x256w4a3_tt", DT_F16, 1, 0),
+    TILED_MF16("bf16_m256x256w4a3_tn", DT_BF16, 1, 1),
+    TILED_MF16("f16_m256x256w4a3_tn", DT_F16, 1, 1),
 };
 
 PEAK_VARIANT_GROUP(variants_mf16, rows_mf16)
