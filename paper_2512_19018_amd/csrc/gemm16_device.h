@@ -48,7 +48,11 @@ struct Cfg16 {
     static __device__ __forceinline__ int swizzle(int r) { return (r & 7) ^ ((r >> 3) & 1); }
 };
 
-template <class C>
+// MAY_TAIL false: K is a whole number of K tiles (the host picks the instantiation).  No load
+// then needs the per-lane offsets of a tile that K ends inside, and the select between the
+// two sets of offsets, one vector instruction per load, is left out: a 16-cycle MFMA slot has
+// room for three other instructions.
+template <class C, bool MAY_TAIL>
 __global__ __launch_bounds__(C::NT) void gemm16_kernel(const GemmArgs p)
 {
 #if defined(__HIP_DEVICE_COMPILE__)   // the host pass only needs the kernel's symbol
@@ -199,17 +203,27 @@ __global__ __launch_bounds__(C::NT) void gemm16_kernel(const GemmArgs p)
     else dB.init(p.B, p.ldb, n0, p.N, kbase, p.K, tail_k, wave, lane);
     auto a_stage = [&](int s) { return lds + s * C::A_BYTES; };
     auto b_stage = [&](int s) { return lds + C::NSA * C::A_BYTES + s * C::B_BYTES; };
-    // Loads of tile kt, part PART of the wave's LA (LB) instructions.  Past the end the last
-    // tile is fetched again into a free stage, so the count in flight stays what the waits assume.
-    auto issue_a = [&](int kt, int sa, auto part) {
+    // Loads of the tile whose scalar offsets and tail flag are in (soa, sob, tl), part PART of the
+    // wave's LA (LB) instructions.  The three are worked out a tile ahead, in a slot of the
+    // schedule that holds nothing else (next_offsets).  Past the end the last tile is fetched
+    // again into a free stage, so the count in flight stays what the waits assume.
+    int soa = 0, sob = 0;
+    bool tl = false;
+    auto next_offsets = [&](int kt) {
         const int kr = kt < KT ? kt : KT - 1;
-        if constexpr (C::A_KM) nA.template issue<decltype(part)::value, LA>(a_stage(sa), kr, kr == tail_tile, wave);
-        else dA.template issue<decltype(part)::value, LA>(a_stage(sa), kr, kr == tail_tile, wave);
+        soa = C::A_KM ? nA.soffset_of(kr) : dA.soffset_of(kr);
+        sob = C::B_KN ? nB.soffset_of(kr) : dB.soffset_of(kr);
+        tl = kr == tail_tile;
     };
-    auto issue_b = [&](int kt, int sb, auto part) {
-        const int kr = kt < KT ? kt : KT - 1;
-        if constexpr (C::B_KN) nB.template issue<decltype(part)::value, LB>(b_stage(sb), kr, kr == tail_tile, wave);
-        else dB.template issue<decltype(part)::value, LB>(b_stage(sb), kr, kr == tail_tile, wave);
+    auto issue_a = [&](int sa, auto part, auto may_tail) {
+        constexpr bool MT = decltype(may_tail)::value != 0;
+        if constexpr (C::A_KM) nA.template issue_at<decltype(part)::value, LA, MT>(a_stage(sa), soa, tl, wave);
+        else dA.template issue_at<decltype(part)::value, LA, MT>(a_stage(sa), soa, tl, wave);
+    };
+    auto issue_b = [&](int sb, auto part, auto may_tail) {
+        constexpr bool MT = decltype(may_tail)::value != 0;
+        if constexpr (C::B_KN) nB.template issue_at<decltype(part)::value, LB, MT>(b_stage(sb), sob, tl, wave);
+        else dB.template issue_at<decltype(part)::value, LB, MT>(b_stage(sb), sob, tl, wave);
     };
 
     // Main loop.  One wave per SIMD: nothing else hides this wave's stalls, so the order of
@@ -240,69 +254,75 @@ __global__ __launch_bounds__(C::NT) void gemm16_kernel(const GemmArgs p)
         else
             asm volatile("v_mfma_f32_16x16x32_f16 %0, %1, %2, %0" : "+a"(c) : "v"(b), "v"(a));
     };
+    constexpr int PENDING = LA / 2;                          // loads of the tile under way at its barrier
+    next_offsets(0);
+    static_for<LA>([&](auto pc) { issue_a(0, pc, IC<1>{}); });
+    static_for<LB>([&](auto pc) { issue_b(0, pc, IC<1>{}); });
     static_for<NM>([&](auto jc) {                             // accumulators into AGPRs now
         constexpr int j = decltype(jc)::value;
         f32x4v &c = acc[j % C::MB][j / C::MB];
         asm volatile("" : "+a"(c));
     });
-    asm volatile("s_nop 7\n\ts_nop 7" ::: "memory");
-
-    constexpr int PENDING = LA / 2;                          // loads of the tile under way at its barrier
-    static_for<LA>([&](auto pc) { issue_a(0, 0, pc); });
-    static_for<LB>([&](auto pc) { issue_b(0, 0, pc); });
     wait_vmcnt<0>();
     lds_barrier();
-    static_for<LB>([&](auto pc) { issue_b(1, 1, pc); });
-    static_for<LA>([&](auto pc) { issue_a(1, 1, pc); });
+    next_offsets(1);
+    static_for<LB>([&](auto pc) { issue_b(1, pc, IC<1>{}); });
+    static_for<LA>([&](auto pc) { issue_a(1, pc, IC<1>{}); });
+    next_offsets(2);
+    asm volatile("s_nop 7\n\ts_nop 7" ::: "memory");
     static_for<NFR>([&](auto fc) { fetch_one(IC<0>{}, IC<0>{}, IC<0>{}, fc); });
 #ifdef PEAK_TRACE
     tr_loop0 = __builtin_amdgcn_s_memtime();
 #endif
-    constexpr int U = 6;                                     // tiles per trip: both stage indices static
-    for (int kt0 = 0; kt0 < KT; kt0 += U) {
-        static_for<U>([&](auto uc) {
-            constexpr int u = decltype(uc)::value;
-            constexpr int s = u % 2, sa = u % 3, sa1 = (sa + 1) % 3, sa2 = (sa + 2) % 3;
-            const int kt = kt0 + u;
-            if (kt < KT) {
-                // k-step 0
-                settle(IC<0>{});
+    {
+        constexpr auto may_tail = IC<MAY_TAIL ? 1 : 0>{};
+        constexpr int U = 6;                                 // tiles per trip: both stage indices static
+        for (int kt0 = 0; kt0 < KT; kt0 += U) {
+            static_for<U>([&](auto uc) {
+                constexpr int u = decltype(uc)::value;
+                constexpr int s = u % 2, sa = u % 3, sa1 = (sa + 1) % 3, sa2 = (sa + 2) % 3;
+                const int kt = kt0 + u;
+                if (kt < KT) {
+                    // k-step 0
+                    settle(IC<0>{});
 #ifdef PEAK_TRACE
-                {
-                    const uint64_t dw = tr_w1 - tr_w0;       // the wait of the tile before: stamps long since returned
-                    tr_wait_sum += dw;
-                    tr_wait_max = dw > tr_wait_max ? dw : tr_wait_max;
+                    {
+                        const uint64_t dw = tr_w1 - tr_w0;   // the wait of the tile before: stamps long since returned
+                        tr_wait_sum += dw;
+                        tr_wait_max = dw > tr_wait_max ? dw : tr_wait_max;
+                    }
+#endif
+                    __builtin_amdgcn_sched_barrier(0);
+                    static_for<NM>([&](auto jc) {
+                        constexpr int j = decltype(jc)::value;
+                        mfma_one(IC<0>{}, jc);
+                        if constexpr (j % 2 == 0 && j / 2 < NFR) fetch_one(IC<sa>{}, IC<s>{}, IC<1>{}, IC<j / 2>{});
+                        if constexpr (j % 16 == 1 && j / 16 < LA / 2) issue_a(sa2, IC<j / 16>{}, may_tail);
+                        __builtin_amdgcn_sched_barrier(0);
+                    });
+                    // k-step 1
+#ifdef PEAK_TRACE
+                    tr_w0 = __builtin_amdgcn_s_memtime();
+#endif
+                    wait_vmcnt<PENDING>();                   // own loads of tile kt+1
+                    lds_barrier();                           // tile kt+1 complete, tile kt read
+#ifdef PEAK_TRACE
+                    tr_w1 = __builtin_amdgcn_s_memtime();
+#endif
+                    settle(IC<1>{});
+                    __builtin_amdgcn_sched_barrier(0);
+                    static_for<NM>([&](auto jc) {
+                        constexpr int j = decltype(jc)::value;
+                        mfma_one(IC<1>{}, jc);
+                        if constexpr (j % 2 == 0 && j / 2 < NFR) fetch_one(IC<sa1>{}, IC<1 - s>{}, IC<0>{}, IC<j / 2>{});
+                        if constexpr (j % 4 == 1 && j / 4 < LB) issue_b(s, IC<j / 4>{}, may_tail);
+                        if constexpr (j % 8 == 3 && j / 8 >= 4 && j / 8 - 4 < LA / 2) issue_a(sa2, IC<LA / 2 + j / 8 - 4>{}, may_tail);
+                        if constexpr (j == NM - 2) next_offsets(kt + 3);   // for the loads the next tile issues
+                        __builtin_amdgcn_sched_barrier(0);
+                    });
                 }
-#endif
-                __builtin_amdgcn_sched_barrier(0);
-                static_for<NM>([&](auto jc) {
-                    constexpr int j = decltype(jc)::value;
-                    mfma_one(IC<0>{}, jc);
-                    if constexpr (j % 2 == 0 && j / 2 < NFR) fetch_one(IC<sa>{}, IC<s>{}, IC<1>{}, IC<j / 2>{});
-                    if constexpr (j % 16 == 1 && j / 16 < LA / 2) issue_a(kt + 2, sa2, IC<j / 16>{});
-                    __builtin_amdgcn_sched_barrier(0);
-                });
-                // k-step 1
-#ifdef PEAK_TRACE
-                tr_w0 = __builtin_amdgcn_s_memtime();
-#endif
-                wait_vmcnt<PENDING>();                       // own loads of tile kt+1
-                lds_barrier();                               // tile kt+1 complete, tile kt read
-#ifdef PEAK_TRACE
-                tr_w1 = __builtin_amdgcn_s_memtime();
-#endif
-                settle(IC<1>{});
-                __builtin_amdgcn_sched_barrier(0);
-                static_for<NM>([&](auto jc) {
-                    constexpr int j = decltype(jc)::value;
-                    mfma_one(IC<1>{}, jc);
-                    if constexpr (j % 2 == 0 && j / 2 < NFR) fetch_one(IC<sa1>{}, IC<1 - s>{}, IC<0>{}, IC<j / 2>{});
-                    if constexpr (j % 4 == 1 && j / 4 < LB) issue_b(kt + 2, s, IC<j / 4>{});
-                    if constexpr (j % 8 == 3 && j / 8 >= 4 && j / 8 - 4 < LA / 2) issue_a(kt + 2, sa2, IC<LA / 2 + j / 8 - 4>{});
-                    __builtin_amdgcn_sched_barrier(0);
-                });
-            }
-        });
+            });
+        }
     }
     settle(IC<0>{});    // reads issued as assembly feed nothing here, but must have returned before their registers are reused
     // 16x16x32 MFMA: 4 passes of 4 cycles; an accumulator may be read 10 wait states after the issue

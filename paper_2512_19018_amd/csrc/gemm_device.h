@@ -354,13 +354,24 @@ struct LoaderDirect {
     template <int PART, int NPARTS>
     PEAK_DEVM void issue(char *lds_tile, int ktile, bool tail, int wave) const
     {
+        issue_at<PART, NPARTS, true>(lds_tile, soffset_of(ktile), tail, wave);
+    }
+
+    // byte offset of K tile `ktile` (relative to k0) within the panel: the loads' scalar offset
+    PEAK_DEVM int soffset_of(int ktile) const { return ktile * C::RB; }
+
+    // ... with the scalar offset worked out by the caller (ahead of time, away from the loads);
+    // MAY_TAIL false: the caller knows that K ends on a tile boundary and spares the select
+    template <int PART, int NPARTS, bool MAY_TAIL>
+    PEAK_DEVM void issue_at(char *lds_tile, int soffset, bool tail, int wave) const
+    {
 #pragma unroll
         for (int i = 0; i < PER_WAVE; ++i) {
             const int j = wave + C::NW * i;
             if (i % NPARTS == PART && (NINST % C::NW == 0 || j < NINST)) {
-                const int vo = tail ? voff_tail[i] : voff[i];         // one select on a uniform condition
+                const int vo = MAY_TAIL && tail ? voff_tail[i] : voff[i];   // one select on a uniform condition
                 __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc, (__attribute__((address_space(3))) void *)(lds_tile + j * 1024),
-                                                         16, vo, ktile * C::RB, 0, 0);
+                                                         16, vo, soffset, 0, 0);
             }
         }
     }
@@ -414,13 +425,21 @@ struct LoaderDirectKN {
     template <int PART, int NPARTS>
     PEAK_DEVM void issue(char *lds_tile, int ktile, bool tail, int wave) const
     {
+        issue_at<PART, NPARTS, true>(lds_tile, soffset_of(ktile), tail, wave);
+    }
+
+    PEAK_DEVM int soffset_of(int ktile) const { return ktile * step_bytes; }
+
+    template <int PART, int NPARTS, bool MAY_TAIL>
+    PEAK_DEVM void issue_at(char *lds_tile, int soffset, bool tail, int wave) const
+    {
 #pragma unroll
         for (int i = 0; i < PER_WAVE; ++i) {
             const int j = wave + C::NW * i;
             if (i % NPARTS == PART && (NINST % C::NW == 0 || j < NINST)) {
-                const int vo = tail ? voff_tail[i] : voff[i];
+                const int vo = MAY_TAIL && tail ? voff_tail[i] : voff[i];
                 __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc, (__attribute__((address_space(3))) void *)(lds_tile + j * 1024),
-                                                         16, vo, ktile * step_bytes, 0, 0);
+                                                         16, vo, soffset, 0, 0);
             }
         }
     }

@@ -7,7 +7,9 @@ namespace peak {
 template <class C>
 static hipError_t launch_gemm16(const GemmArgs &a, dim3 grid, hipStream_t s)
 {
-    hipLaunchKernelGGL((gemm16_kernel<C>), grid, dim3(C::NT), 0, s, a);
+    // K ending inside a K tile takes the instantiation that can zero-fill the tail
+    if (a.K % C::BK != 0) hipLaunchKernelGGL((gemm16_kernel<C, true>), grid, dim3(C::NT), 0, s, a);
+    else hipLaunchKernelGGL((gemm16_kernel<C, false>), grid, dim3(C::NT), 0, s, a);
     return hipGetLastError();
 }
 
