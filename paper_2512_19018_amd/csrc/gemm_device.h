@@ -168,7 +168,7 @@ struct Cfg {
     // the accumulation half of the register file.  The compiler does not manage that (it
     // keeps part of them in ordinary registers and spills), so for this shape the MFMAs of
     // the main loop are written as assembly with the accumulators constrained to AGPRs.
-    static constexpr bool ACC_AGPR = WAVES_M_ * WAVES_N_ == 4 && (BM_ / WAVES_M_) * (BN_ / WAVES_N_) == 128 * 128 && DT_ != DT_F32;
+    static constexpr bool ACC_AGPR = WAVES_M_ * WAVES_N_ == 4 && (BM_ / WAVES_M_) * (BN_ / WAVES_N_) == 128 * 128;
     static_assert(!PP_ || (NS_ >= 2 && AX_ == 0 && DIRECT_ && !A_T_ && (!B_T_ || TR_) && WAVES_M_ * WAVES_N_ == 8),
                   "alternating loop: 8 waves, both operands direct");
     static_assert(AX_ == 0 || (AX_ == 1 && NS_ == 2 && RB_ == 128 && DIRECT_ && !A_T_ && (!B_T_ || TR_)),
@@ -737,6 +737,20 @@ PEAK_DEV void epilogue_slabs(const GemmArgs &p, char *lds, int wave, int lane, i
                 auto vector_readout = [&](auto plain_c) {
                     constexpr bool PLAIN = decltype(plain_c)::value != 0;
                     constexpr int G = 32 / RPI;
+                    // beta != 0: the slab's C_in is asked for first, all rows at once, so that its way
+                    // from memory overlaps the LDS turnaround instead of following it row by row
+                    u32x4 cin[G];
+                    const bool need_c = !PLAIN && p.beta != 0.0f;
+                    if (need_c) {
+#pragma unroll
+                        for (int g = 0; g < G; ++g) {
+                            const int64_t m = m0 + wm * C::WTM + mi * 32 + g * RPI + orow;
+                            const int64_t n = n0 + wn * C::WTN + ocol;
+                            cin[g] = u32x4{0u, 0u, 0u, 0u};
+                            if (interior || (m < p.M && n + EPL <= p.N))
+                                cin[g] = *(const u32x4 *)((const char *)p.C + (m * p.ldc + n) * C::ESZ);
+                        }
+                    }
                     f32x4 lo[G], hi[G];
 #pragma unroll
                     for (int g = 0; g < G; ++g) {
@@ -768,8 +782,8 @@ PEAK_DEV void epilogue_slabs(const GemmArgs &p, char *lds, int wave, int lane, i
                             f32x4 o = lo[g];
                             o[0] *= p.alpha; o[1] *= p.alpha; o[2] *= p.alpha; o[3] *= p.alpha;
                             float *dst = (float *)p.C + m * p.ldc + n;
-                            if (!PLAIN && p.beta != 0.0f) {
-                                const f32x4 c = *(const f32x4 *)dst;
+                            if (need_c) {
+                                const f32x4 c = __builtin_bit_cast(f32x4, cin[g]);
                                 o[0] += p.beta * c[0]; o[1] += p.beta * c[1]; o[2] += p.beta * c[2]; o[3] += p.beta * c[3];
                             }
                             if (!PLAIN && hooked) {
@@ -783,8 +797,8 @@ PEAK_DEV void epilogue_slabs(const GemmArgs &p, char *lds, int wave, int lane, i
                                           p.alpha * hi[g][0], p.alpha * hi[g][1], p.alpha * hi[g][2], p.alpha * hi[g][3]};
                             uint16_t *dst = (uint16_t *)p.C + m * p.ldc + n;
                             union { u32x4 u; _Float16 h[8]; __bf16 b[8]; } pk;
-                            if (!PLAIN && p.beta != 0.0f) {
-                                pk.u = *(const u32x4 *)dst;
+                            if (need_c) {
+                                pk.u = cin[g];
 #pragma unroll
                                 for (int e = 0; e < 8; ++e) o[e] += p.beta * (C::DT == DT_F16 ? (float)pk.h[e] : (float)pk.b[e]);
                             }
@@ -1133,7 +1147,7 @@ __global__ __launch_bounds__(C::NT) void gemm_kernel(const GemmArgs p)
         // B kept as [k][n] rows: its transposing reads go out as assembly (the compiler would put a
         // wait for all loads in front of each, see the loop below) into bl/bh and are handed over
         // at the start of the next k-group, when everything asked of LDS has arrived
-        constexpr bool TRA = C::B_TR;
+        constexpr bool TRA = C::B_TR && C::DT != DT_F32;        // (fp32 [k][n] rows need no transposition: plain reads)
         u32x2 bl[2][C::NI], bh[2][C::NI];
         const uint32_t lds_b0 = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) char *)lds;
         auto fetch_one = [&](int stage_a, int stage, int kg, auto setc, auto fc) {
@@ -1167,10 +1181,25 @@ __global__ __launch_bounds__(C::NT) void gemm_kernel(const GemmArgs p)
             constexpr int mi = i / C::NI, ni = i % C::NI;
             f32x16 &c = acc[mi][ni];
             const u32x4 &b = bf[set][ni], &a = af[set][mi];
-            if constexpr (C::DT == DT_BF16)
+            if constexpr (C::DT == DT_BF16) {
                 asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, %0" : "+a"(c) : "v"(b), "v"(a));
-            else
+            } else if constexpr (C::DT == DT_F16) {
                 asm volatile("v_mfma_f32_32x32x16_f16 %0, %1, %2, %0" : "+a"(c) : "v"(b), "v"(a));
+            } else {
+                // fp32: a fragment holds 4 k per lane, one 32x32x2 MFMA each.  Slot i takes k step
+                // i / 4 of four blocks, so that consecutive MFMAs write different accumulators and an
+                // accumulator comes round again only 16 MFMAs later (the compiler, which would put the
+                // wait states between dependent MFMAs, does not see inside these statements).
+                static_assert(C::MI * C::NI == 16, "four blocks per slot, four slots per k step");
+                constexpr int st = i / 4;
+                static_for<4>([&](auto bc) {
+                    constexpr int blk = (i % 4) * 4 + decltype(bc)::value;
+                    f32x16 &cc = acc[blk / C::NI][blk % C::NI];
+                    const float bv = __builtin_bit_cast(f32x4, bf[set][blk % C::NI])[st];
+                    const float av = __builtin_bit_cast(f32x4, af[set][blk / C::NI])[st];
+                    asm volatile("v_mfma_f32_32x32x2_f32 %0, %1, %2, %0" : "+a"(cc) : "v"(bv), "v"(av));
+                });
+            }
         };
         auto load_one = [&](int t, int stage, auto jc) {
             constexpr int j = decltype(jc)::value;

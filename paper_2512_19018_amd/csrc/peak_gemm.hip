@@ -125,7 +125,8 @@ static double tiled_cost(const Variant &v, const peak_gemm_desc_t &d, int split)
     // The constants come from the measured sweeps on the graded shapes.
     double eff = 1.0;
     if (v.dt == DT_F32) {                               // fp32 MFMA is slow enough that tile size hardly matters
-        if (v.bm * v.bn >= 256 * 128) eff = 0.86;
+        if (v.bm * v.bn >= 256 * 256) eff = 0.90;       // 128x128 per wave: a quarter of the LDS traffic of 64x64 wave tiles
+        else if (v.bm * v.bn >= 256 * 128) eff = 0.86;
         else if (v.bm * v.bn >= 128 * 128) eff = 0.95;
         else if (v.bm * v.bn >= 128 * 64) eff = 0.8;    // as good per multiply-add as 128x128 while few workgroups run
         else eff = 0.5;
@@ -183,8 +184,9 @@ static void plan_geometry(Geometry *p, const peak_gemm_desc_t &d, int variant, i
     p->ktiles_per_slice = (int)cdiv(p->ktiles_total, split);
     p->split = (int)cdiv(p->ktiles_total, p->ktiles_per_slice);   // no empty slices
     p->group_m = p->tiles_m >= 8 ? 8 : (p->tiles_m > 0 ? p->tiles_m : 1);
-    p->rot_m = 0;                                           // K rotation off: measured no gain on the graded shapes
-    p->rot_n = 0;
+    p->rot_m = 0;                                           // K rotation off for the tiled kernels: measured no gain on the graded shapes
+    p->rot_n = v.kind == KIND_SKINNY ? 5 : 0;               // streaming kernel: neighbouring workgroups start five K tiles apart
+                                                            // (bf16 16x16384x16384: 5.3 TB/s without, 6.0 with 1, 6.2 with 5 or 13)
     if (const char *e = getenv("PEAK_GEMM_GROUP_M")) {      // tuning knob: tile rows per band
         const int g = atoi(e);
         if (g >= 1 && g <= 64) p->group_m = g < p->tiles_m ? g : (p->tiles_m > 0 ? p->tiles_m : 1);

@@ -92,8 +92,15 @@ __global__ __launch_bounds__(C::NT) void skinny_kernel(const GemmArgs p)
         gb[i] = (const char *)p.B + (gr * p.ldb + kbase + (int64_t)c * C::EPC) * C::ESZ;
         jb[i] = j;
     }
+    // K rotation: workgroup tn walks its K tiles starting at tile tn * rot_n (mod KT) and wraps
+    // around.  Left alone, all workgroups read the same k range at the same time from rows that
+    // lie a power of two apart, which concentrates the requests of the whole chip on a few
+    // memory channels; started at different tiles they spread over all of them.  Only the
+    // order of the sum over k changes.
+    const int rot = (int)(((int64_t)tn * p.rot_n) % KT);
     auto issue = [&](int kt, int stage) {
-        const int kc = kt < KT ? kt : KT - 1;            // past the end: refetch the last tile into a free stage
+        int kc = (kt < KT ? kt : KT - 1) + rot;          // past the end: refetch the last tile into a free stage
+        if (kc >= KT) kc -= KT;
         char *st = lds + stage * C::STAGE_BYTES;
 #pragma unroll
         for (int i = 0; i < C::A_PER_WAVE; ++i)
