@@ -68,9 +68,20 @@ typedef struct peak_gemm_plan peak_gemm_plan_t;
  * (16-bit operands, full-precision result: the accumulators are fp32 anyway, so
  * alpha*acc + beta*C is then stored unrounded); ldc counts fp32 elements and C
  * must be 4-byte aligned.  With dtype == PEAK_DT_F32 the bit changes nothing.
- * Other bits must be zero.
+ * PEAK_GEMM_STREAMK_ON / PEAK_GEMM_STREAMK_OFF (bits 17, 18; not both): hybrid
+ * stream-K, the Split-K step of Section 4.1 (Table 2) applied to the last round of
+ * tiles only.  When the tiles do not fill a whole number of rounds over the compute
+ * units, the tiles of the last, partial round are cut into K slices, one workgroup
+ * each, and their fp32 partial tiles are summed in slice order by a second kernel, so
+ * that the round lasts a slice instead of a tile.  ON takes it wherever the kernel
+ * variant supports it and the shape leaves a partial round after at least one full
+ * one (else the bit changes nothing); OFF never takes it; neither: the cost model
+ * decides.  A forced K split (bits 8..15) rules it out.  Results stay bit-identical
+ * from run to run.  Other bits must be zero.
  */
 #define PEAK_GEMM_C_F32 0x10000u
+#define PEAK_GEMM_STREAMK_ON 0x20000u
+#define PEAK_GEMM_STREAMK_OFF 0x40000u
 typedef struct {
     int64_t M, N, K;
     int64_t lda, ldb, ldc;
@@ -230,6 +241,7 @@ const char *peak_gemm_variant_name(int id);
  *
  * `path` names a text file in host memory's file system, one entry per line:
  *     <dtype f32|f16|bf16> <transA 0|1> <transB 0|1> <M> <N> <K> <variant name> <split>
+ * (split 0 stands for hybrid stream-K, see PEAK_GEMM_STREAMK_ON)
  * ('#' starts a comment; further columns are ignored).  After a successful
  * load, peak_gemm_create() with no forced variant uses the entry whose first
  * six columns equal the descriptor's, provided that variant fits the

@@ -8,6 +8,7 @@ from .binding import (  # noqa: F401
     PEAK_DT_F32, PEAK_DT_F16, PEAK_DT_BF16,
     PEAK_OK, PEAK_ERR_INVALID_ARG, PEAK_ERR_UNSUPPORTED, PEAK_ERR_WORKSPACE, PEAK_ERR_HIP, PEAK_ERR_ALLOC,
     PEAK_BIAS_NONE, PEAK_BIAS_PER_COLUMN, PEAK_BIAS_PER_ROW, PEAK_ACT_NONE, PEAK_ACT_RELU, PEAK_ACT_GELU_TANH, PEAK_GEMM_C_F32,
+    PEAK_GEMM_STREAMK_ON, PEAK_GEMM_STREAMK_OFF,
     PeakGemmDesc, PeakGemmEpilogue, PeakError, lib_path, load_library,
     peak_gemm_create, peak_gemm_workspace_bytes, peak_gemm_run, peak_gemm_run_fused, peak_gemm_run_static,
     PEAK_GEMM_STATIC_WORKSPACE_BYTES, peak_gemm_destroy,

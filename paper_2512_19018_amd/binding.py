@@ -16,6 +16,7 @@ PEAK_DT_F32, PEAK_DT_F16, PEAK_DT_BF16 = 0, 1, 2
 PEAK_BIAS_NONE, PEAK_BIAS_PER_COLUMN, PEAK_BIAS_PER_ROW = 0, 1, 2
 PEAK_ACT_NONE, PEAK_ACT_RELU, PEAK_ACT_GELU_TANH = 0, 1, 2
 PEAK_GEMM_C_F32 = 0x10000
+PEAK_GEMM_STREAMK_ON, PEAK_GEMM_STREAMK_OFF = 0x20000, 0x40000
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
 _LIB = None
@@ -102,9 +103,13 @@ def peak_gemm_load_tuning(path) -> int:
     return load_library().peak_gemm_load_tuning(None if path is None else os.fsencode(path))
 
 
-def force_flags(variant: int | None = None, split: int | None = None, c_f32: bool = False) -> int:
-    """Descriptor flags that force a variant id and/or a K split, and ask for an fp32 C."""
+def force_flags(variant: int | None = None, split: int | None = None, c_f32: bool = False,
+                streamk: bool | None = None) -> int:
+    """Descriptor flags that force a variant id and/or a K split, ask for an fp32 C, and
+    switch hybrid stream-K on or off (None: the cost model decides)."""
     f = PEAK_GEMM_C_F32 if c_f32 else 0
+    if streamk is not None:
+        f |= PEAK_GEMM_STREAMK_ON if streamk else PEAK_GEMM_STREAMK_OFF
     if variant is not None:
         f |= (variant + 1) & 0xFF
     if split is not None:

@@ -82,15 +82,31 @@ __global__ __launch_bounds__(C::NT) void gemm16_kernel(const GemmArgs p)
     uint64_t tr_loop0 = 0, tr_loop1 = 0, tr_w0 = 0, tr_w1 = 0, tr_wait_sum = 0, tr_wait_max = 0;
 #endif
 
+    // Which tile, which K slice.  Split-K: slice s of tile t is workgroup s * tiles + t.  Hybrid
+    // stream-K: the first tiles - sk_tiles workgroups take one tile each over the whole of K;
+    // the rest (the last, partial round of workgroups) share the remaining sk_tiles tiles,
+    // `split` K slices each, so that the round ends after a slice instead of a tile.
     const int tiles = p.tiles_m * p.tiles_n;
     const int bid = blockIdx.x;
-    const int slice = __builtin_amdgcn_readfirstlane(bid / tiles);
+    const int whole = tiles - p.sk_tiles;                   // stream-K: tiles that are not cut
+    int slice, tile, sk_pos = -1;
+    if (p.sk_tiles == 0) {
+        slice = __builtin_amdgcn_readfirstlane(bid / tiles);
+        tile = bid - slice * tiles;
+    } else if (bid < whole) {
+        slice = -1;                                         // the whole of K
+        tile = bid;
+    } else {
+        slice = __builtin_amdgcn_readfirstlane((bid - whole) / p.sk_tiles);
+        sk_pos = (bid - whole) - slice * p.sk_tiles;
+        tile = whole + sk_pos;
+    }
     int tm, tn;
-    tile_of_block(bid - slice * tiles, p.tiles_m, p.tiles_n, p.group_m, tm, tn);
+    tile_of_block(tile, p.tiles_m, p.tiles_n, p.group_m, tm, tn);
     const int64_t m0 = (int64_t)tm * C::BM, n0 = (int64_t)tn * C::BN;
 
-    const int kt_begin = slice * p.ktiles_per_slice;
-    int kt_end = kt_begin + p.ktiles_per_slice;
+    const int kt_begin = slice < 0 ? 0 : slice * p.ktiles_per_slice;
+    int kt_end = slice < 0 ? p.ktiles_total : kt_begin + p.ktiles_per_slice;
     if (kt_end > p.ktiles_total) kt_end = p.ktiles_total;
     const int KT = __builtin_amdgcn_readfirstlane(kt_end - kt_begin);   // >= 1 by construction of the plan
     const int64_t kbase = (int64_t)kt_begin * C::BK;
@@ -388,7 +404,13 @@ __global__ __launch_bounds__(C::NT) void gemm16_kernel(const GemmArgs p)
                 *(u32x2 *)(scr16 + (16 * h + r16) * SROW16 + grp * 8) = pk.u;
             }
     };
-    epilogue_slabs<C, C::WTM / 32>(p, lds, wave, lane, wm, wn, m0, n0, slice, write_slab, write16);
+    PartialOut po = splitk_out(p, slice < 0 ? 0 : slice);
+    if (p.sk_tiles != 0) {
+        po = PartialOut{nullptr, 0, 0, 0, false};
+        if (slice >= 0)     // partial tile, stored densely: [slice][position among the cut tiles][BM][BN]
+            po = PartialOut{p.ws + ((int64_t)slice * p.sk_tiles + sk_pos) * (C::BM * C::BN), C::BN, m0, n0, true};
+    }
+    epilogue_slabs<C, C::WTM / 32>(p, lds, wave, lane, wm, wn, m0, n0, po, write_slab, write16);
 #ifdef PEAK_TRACE
     if (p.split == 1 && p.ws && lane == 0) {
         const uint64_t tr_end = __builtin_amdgcn_s_memtime();

@@ -63,6 +63,8 @@ struct GemmArgs {
     int32_t ktiles_total;     // ceil(K / BK)
     int32_t group_m;          // tile rows per band of the tile order
     int32_t rot_m, rot_n;     // K rotation per tile row / tile column within an XCD's patch of tiles
+    int32_t sk_tiles;         // hybrid stream-K: the last sk_tiles tiles of the tile order are cut into `split` K slices
+                              // (fp32 partials [slice][tile][BM][BN] in ws), all others take the whole of K; 0: off
     uint32_t flags;
     Hook hook;
 };
@@ -616,12 +618,28 @@ PEAK_DEV void tile_of_block(int t, int tiles_m, int tiles_n, int group_m, int &t
 //   write16(s, scr16)     (16-bit kernels) alpha * acc rounded to the storage type, 8 bytes per 4-column
 //                         group g = col / 4 at scr16[row * SROW16 + 8 * (g ^ (row >> 4))], SROW16 = WTN * 2 + 16
 // ---------------------------------------------------------------------------
+// Where a workgroup that holds a K slice puts its fp32 partial tile: element (m, n) of C goes to
+// base[(m - m_org) * ld + (n - n_org)].  base == nullptr: the workgroup holds the whole of K
+// and writes C itself.
+struct PartialOut {
+    float *base;
+    int64_t ld, m_org, n_org;
+    bool vec;                 // rows allow 16-byte access
+};
+
+// Split-K: slice s of every tile goes to its own M x N plane of the workspace.
+PEAK_DEV PartialOut splitk_out(const GemmArgs &p, int slice)
+{
+    if (p.split <= 1) return PartialOut{nullptr, 0, 0, 0, false};
+    return PartialOut{p.ws + (int64_t)slice * p.M * p.N, p.N, 0, 0, (p.flags & GF_WS_VEC) != 0};
+}
+
 template <class C, int SLABS, class WriteSlab, class Write16>
 PEAK_DEV void epilogue_slabs(const GemmArgs &p, char *lds, int wave, int lane, int wm, int wn, int64_t m0, int64_t n0,
-                             int slice, WriteSlab &&write_slab, Write16 &&write16)
+                             const PartialOut &po, WriteSlab &&write_slab, Write16 &&write16)
 {
-    const bool c_vec = p.flags & GF_C_VEC, ws_vec = p.flags & GF_WS_VEC;
-    float *wsl = p.split > 1 ? p.ws + (int64_t)slice * p.M * p.N : nullptr;
+    const bool c_vec = p.flags & GF_C_VEC, ws_vec = po.vec;
+    float *wsl = po.base;
     const bool interior = m0 + C::BM <= p.M && n0 + C::BN <= p.N;      // whole tile inside C: no masks
     // Each wave turns its 32-row slabs around in LDS (fp32, padded rows) so that a
     // store instruction writes whole row segments of the wave tile (16 bytes per
@@ -714,7 +732,7 @@ PEAK_DEV void epilogue_slabs(const GemmArgs &p, char *lds, int wave, int lane, i
                                 const int nvalid = left >= 4 ? 4 : (int)left;
                                 const f32x4 t = *(const f32x4 *)(src + q * 16);
                                 const float x[4] = {t[0], t[1], t[2], t[3]};
-                                if (wsl) store4<DT_F32>(wsl, m * p.N + nn, x, 1.0f, 0.0f, ws_vec, nvalid);
+                                if (wsl) store4<DT_F32>(wsl, (m - po.m_org) * po.ld + (nn - po.n_org), x, 1.0f, 0.0f, ws_vec, nvalid);
                                 else {
                                     const bool per_row = p.hook.bias_kind == BIAS_PER_ROW;
                                     const float b[4] = {per_row ? br : bcol[q * 4 + 0], per_row ? br : bcol[q * 4 + 1],
@@ -1584,7 +1602,7 @@ __global__ __launch_bounds__(C::NT) void gemm_kernel(const GemmArgs p)
                 *(u32x2 *)(scr16 + r32 * SROW16 + grp * 8) = pk.u;
             }
     };
-    epilogue_slabs<C, C::MI>(p, lds, wave, lane, wm, wn, m0, n0, slice, write_slab, write16);
+    epilogue_slabs<C, C::MI>(p, lds, wave, lane, wm, wn, m0, n0, splitk_out(p, slice), write_slab, write16);
 #ifdef PEAK_TRACE
     trace_store();
 #endif
@@ -1617,6 +1635,30 @@ __global__ __launch_bounds__(256) void splitk_reduce_kernel(const GemmArgs p)
         }
     }
     store4<DT>(p.C, m * p.ldc + n, x, p.alpha, p.beta, p.flags & GF_C_VEC, nvalid, p.hook, m, n);
+}
+
+// Hybrid stream-K, second step: the tiles that were cut along K are summed over their slices,
+// in slice order, and stored like any other tile.  One thread per 4 consecutive outputs of a
+// tile row; blockIdx.y is the tile's position among the cut tiles.
+template <int DT, int BM, int BN>
+__global__ __launch_bounds__(256) void streamk_reduce_kernel(const GemmArgs p)
+{
+    const int r = blockIdx.y;
+    const int q = blockIdx.x * 256 + threadIdx.x;                 // 4-column group within the tile
+    if (q >= BM * (BN / 4)) return;
+    int tm, tn;
+    tile_of_block(p.tiles_m * p.tiles_n - p.sk_tiles + r, p.tiles_m, p.tiles_n, p.group_m, tm, tn);
+    const int row = q / (BN / 4), col = (q % (BN / 4)) * 4;
+    const int64_t m = (int64_t)tm * BM + row, n = (int64_t)tn * BN + col;
+    if (m >= p.M || n >= p.N) return;
+    const int nvalid = p.N - n >= 4 ? 4 : (int)(p.N - n);
+    float x[4] = {0.0f, 0.0f, 0.0f, 0.0f};
+    for (int s = 0; s < p.split; ++s) {
+        const f32x4 t = *(const f32x4 *)(p.ws + ((int64_t)s * p.sk_tiles + r) * (BM * BN) + row * BN + col);
+        x[0] += t[0]; x[1] += t[1]; x[2] += t[2]; x[3] += t[3];
+    }
+    if (p.flags & GF_C_F32) store4<DT_F32>(p.C, m * p.ldc + n, x, p.alpha, p.beta, p.flags & GF_C_VEC, nvalid, p.hook, m, n);
+    else store4<DT>(p.C, m * p.ldc + n, x, p.alpha, p.beta, p.flags & GF_C_VEC, nvalid, p.hook, m, n);
 }
 
 // C = hook(beta * C) (alpha == 0 or K == 0).  beta == 0 writes without reading.

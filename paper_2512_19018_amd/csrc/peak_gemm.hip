@@ -66,6 +66,7 @@ using namespace peak;
 struct Geometry {
     int variant;          // index into the variant table, -1: nothing to launch
     int tiles_m, tiles_n, split, ktiles_total, ktiles_per_slice, group_m, rot_m, rot_n;
+    int sk_tiles;         // hybrid stream-K: tiles of the last, partial round that are cut into `split` K slices; 0: off
     size_t ws_bytes;
 };
 
@@ -168,10 +169,42 @@ static int choose_split(const Variant &v, const peak_gemm_desc_t &d)
     return best;
 }
 
-static void plan_geometry(Geometry *p, const peak_gemm_desc_t &d, int variant, int forced_split)
+// Hybrid stream-K (the paper's Split-K of Section 4.1, Table 2, applied to the last round only):
+// with T tiles on P compute units the last round holds T mod P tiles and leaves the other units
+// idle for a whole tile's time.  Those tiles are cut into S = floor(P / (T mod P)) K slices each,
+// so the round takes a slice's time plus the ordered sum of the partial tiles.  Returns S (0: not
+// applicable or not worth it by the cost model); *sk_tiles receives T mod P.
+static int streamk_split(const Variant &v, const peak_gemm_desc_t &d, int *sk_tiles)
+{
+    *sk_tiles = 0;
+    if (!v.mf16) return 0;                                   // built into the 16x16x32 kernels only
+    const int64_t tiles = cdiv(d.M, v.bm) * cdiv(d.N, v.bn), P = num_cu();
+    const int64_t rem = tiles % P, ktiles = cdiv(d.K, v.bk);
+    if (tiles < P || rem == 0) return 0;
+    int64_t S = P / rem;
+    if (S > ktiles / 4) S = ktiles / 4;                      // at least four K tiles per slice
+    if (S > 255) S = 255;
+    if (S < 2) return 0;
+    *sk_tiles = (int)rem;
+    return (int)S;
+}
+
+// cost-model estimate, in the units of tiled_cost: is the cut round cheaper than a whole one?
+static bool streamk_pays(const Variant &v, const peak_gemm_desc_t &d, int S, int sk_tiles)
+{
+    const double tile = (double)v.bm * v.bn * v.bk * (double)cdiv(d.K, v.bk);
+    const double fixed = 12.0e6;
+    const double partials = (double)S * sk_tiles * v.bm * v.bn;
+    const double cut = tile / S + fixed + (4.0 * partials <= 64.0e6 ? 4.5 : 9.0) * partials + 8.0e6;
+    return cut < 0.9 * (tile + fixed);
+}
+
+// streamk: 1 take hybrid stream-K wherever it applies, -1 never, 0 let the cost model decide
+static void plan_geometry(Geometry *p, const peak_gemm_desc_t &d, int variant, int forced_split, int streamk = 0)
 {
     const Variant &v = g_variants[variant];
     p->variant = variant;
+    p->sk_tiles = 0;
     p->tiles_m = (int)cdiv(d.M, v.bm);
     p->tiles_n = (int)cdiv(d.N, v.bn);
     p->ktiles_total = (int)cdiv(d.K, v.bk);
@@ -196,6 +229,17 @@ static void plan_geometry(Geometry *p, const peak_gemm_desc_t &d, int variant, i
         if (sscanf(e, "%d,%d", &a, &b) == 2 && a >= 0 && b >= 0) { p->rot_m = a; p->rot_n = b; }
     }
     p->ws_bytes = p->split > 1 ? (size_t)p->split * (size_t)d.M * (size_t)d.N * sizeof(float) : 0;
+    // hybrid stream-K where nothing forces a K split: PEAK_GEMM_STREAMK_ON / _OFF decide, else the cost model
+    if (forced_split <= 0 && p->split == 1 && streamk >= 0) {
+        int sk_tiles = 0;
+        const int S = streamk_split(v, d, &sk_tiles);
+        if (S >= 2 && (streamk > 0 || streamk_pays(v, d, S, sk_tiles))) {
+            p->ktiles_per_slice = (int)cdiv(p->ktiles_total, S);
+            p->split = (int)cdiv(p->ktiles_total, p->ktiles_per_slice);
+            p->sk_tiles = sk_tiles;
+            p->ws_bytes = (size_t)p->split * (size_t)sk_tiles * (size_t)v.bm * v.bn * sizeof(float);
+        }
+    }
 }
 
 // The selector's own choice among the variants that fit (cost model); with
@@ -254,7 +298,7 @@ static int load_tuning_file(const char *path)
         e.variant = n >= 7 ? variant_by_name(name) : -1;
         e.M = M; e.N = N; e.K = K;
         ok = n == 8 && e.dt >= 0 && e.variant >= 0 && (e.ta | 1) == 1 && (e.tb | 1) == 1 && M > 0 && N > 0 && K > 0 &&
-             e.split >= 1 && e.split <= 255 && g_variants[e.variant].dt == e.dt;
+             e.split >= 0 && e.split <= 255 && g_variants[e.variant].dt == e.dt;
         if (ok) table.push_back(e);
     }
     fclose(f);
@@ -334,7 +378,8 @@ peak_status_t peak_gemm_create(const peak_gemm_desc_t *desc, peak_gemm_plan_t **
     if (d.M < 0 || d.N < 0 || d.K < 0) return PEAK_ERR_INVALID_ARG;
     if (d.dtype != PEAK_DT_F32 && d.dtype != PEAK_DT_F16 && d.dtype != PEAK_DT_BF16) return PEAK_ERR_INVALID_ARG;
     if ((d.transA != 0 && d.transA != 1) || (d.transB != 0 && d.transB != 1)) return PEAK_ERR_INVALID_ARG;
-    if (d.flags & ~(0xFFFFu | PEAK_GEMM_C_F32)) return PEAK_ERR_INVALID_ARG;
+    if (d.flags & ~(0xFFFFu | PEAK_GEMM_C_F32 | PEAK_GEMM_STREAMK_ON | PEAK_GEMM_STREAMK_OFF)) return PEAK_ERR_INVALID_ARG;
+    if ((d.flags & PEAK_GEMM_STREAMK_ON) && (d.flags & PEAK_GEMM_STREAMK_OFF)) return PEAK_ERR_INVALID_ARG;
     const int64_t min_lda = d.transA ? d.M : d.K, min_ldb = d.transB ? d.K : d.N;
     if (d.lda < (min_lda > 1 ? min_lda : 1) || d.ldb < (min_ldb > 1 ? min_ldb : 1) || d.ldc < (d.N > 1 ? d.N : 1))
         return PEAK_ERR_INVALID_ARG;
@@ -370,7 +415,7 @@ peak_status_t peak_gemm_create(const peak_gemm_desc_t *desc, peak_gemm_plan_t **
         pick = forced;
     } else if (const TuneEntry *t = tuned(d)) {
         pick = t->variant;
-        table_split = t->split;
+        table_split = t->split > 0 ? t->split : -1;
     } else {
         pick = select_variant(d, false);
         if (pick < 0) {
@@ -378,7 +423,10 @@ peak_status_t peak_gemm_create(const peak_gemm_desc_t *desc, peak_gemm_plan_t **
             return PEAK_ERR_UNSUPPORTED;
         }
     }
-    plan_geometry(&p->g, d, pick, forced_split > 0 ? forced_split : table_split);
+    // a table entry with split 0 stands for hybrid stream-K
+    int streamk = (d.flags & PEAK_GEMM_STREAMK_ON) ? 1 : (d.flags & PEAK_GEMM_STREAMK_OFF) ? -1 : 0;
+    if (forced_split <= 0 && streamk == 0 && table_split < 0) streamk = 1;
+    plan_geometry(&p->g, d, pick, forced_split > 0 ? forced_split : (table_split > 0 ? table_split : 0), streamk);
     // Leading dimensions are known here, base addresses only at run time: a variant that copies
     // 16-byte chunks gets a register-staged stand-in for runs whose A or B base is off that alignment
     if (g_variants[pick].direct) {
@@ -386,7 +434,7 @@ peak_status_t peak_gemm_create(const peak_gemm_desc_t *desc, peak_gemm_plan_t **
         if (alt >= 0) plan_geometry(&p->alt, d, alt, forced_split);
     }
     p->ws_bytes = p->g.ws_bytes > p->alt.ws_bytes ? p->g.ws_bytes : p->alt.ws_bytes;
-    const int64_t grid = (int64_t)p->g.tiles_m * p->g.tiles_n * p->g.split;
+    const int64_t grid = (int64_t)p->g.tiles_m * p->g.tiles_n * p->g.split;   // (an upper bound for a stream-K plan)
     const int64_t grid_alt = p->alt.variant < 0 ? 0 : (int64_t)p->alt.tiles_m * p->alt.tiles_n * p->alt.split;
     if (grid > 0x7FFFFFFF || grid_alt > 0x7FFFFFFF) {
         delete p;
@@ -398,6 +446,13 @@ peak_status_t peak_gemm_create(const peak_gemm_desc_t *desc, peak_gemm_plan_t **
 
 size_t peak_gemm_workspace_bytes(const peak_gemm_plan_t *plan) { return plan ? plan->ws_bytes : 0; }
 
+// workgroups of the GEMM launch
+static int64_t grid_blocks(const Geometry &g)
+{
+    const int64_t tiles = (int64_t)g.tiles_m * g.tiles_n;
+    return g.sk_tiles ? tiles - g.sk_tiles + (int64_t)g.sk_tiles * g.split : tiles * g.split;
+}
+
 int peak_gemm_plan_info(const peak_gemm_plan_t *p, char *buf, size_t n)
 {
     if (!p) return snprintf(buf, n, "null plan");
@@ -408,10 +463,10 @@ int peak_gemm_plan_info(const peak_gemm_plan_t *p, char *buf, size_t n)
     const Variant &v = g_variants[g.variant];
     return snprintf(buf, n,
                     "variant=%d:%s tile=%dx%dx%d threads=%d stages=%d lds=%d split=%d ktiles/slice=%d "
-                    "grid=%lld (tiles %dx%d) group_m=%d workspace=%zu unaligned=%s",
+                    "grid=%lld (tiles %dx%d) group_m=%d workspace=%zu unaligned=%s streamk=%d",
                     g.variant, v.name, v.bm, v.bn, v.bk, v.nt, v.ns, v.lds, g.split, g.ktiles_per_slice,
-                    (long long)g.tiles_m * g.tiles_n * g.split, g.tiles_m, g.tiles_n, g.group_m, p->ws_bytes,
-                    p->alt.variant >= 0 ? g_variants[p->alt.variant].name : "same");
+                    (long long)grid_blocks(g), g.tiles_m, g.tiles_n, g.group_m, p->ws_bytes,
+                    p->alt.variant >= 0 ? g_variants[p->alt.variant].name : "same", g.sk_tiles);
 }
 
 static peak_status_t run_plan(peak_gemm_plan_t *p, float alpha, const void *A, const void *B, float beta, void *C,
@@ -484,13 +539,22 @@ static peak_status_t run_plan(peak_gemm_plan_t *p, float alpha, const void *A, c
     a.group_m = g->group_m;
     a.rot_m = g->rot_m;
     a.rot_n = g->rot_n;
+    a.sk_tiles = g->sk_tiles;
 
-    int64_t nblocks = (int64_t)g->tiles_m * g->tiles_n * g->split;
+    int64_t nblocks = grid_blocks(*g);
     if (v.kind == KIND_SKINNY_REG) nblocks = cdiv((int64_t)g->tiles_n * g->split, v.nt / 64);   // one wave per row group and slice
     dim3 grid((unsigned)nblocks);
     if (v.launch(a, grid, stream) != hipSuccess) return PEAK_ERR_HIP;
 
-    if (g->split > 1) {
+    if (g->sk_tiles) {
+        // the cut tiles: ordered sum of their slices (the 16x16x32 kernels' tile is 256 x 256)
+        dim3 rgrid(256 * (256 / 4) / 256, (unsigned)g->sk_tiles);
+        if (c_dt == PEAK_DT_F32 || d.dtype == PEAK_DT_BF16)
+            hipLaunchKernelGGL((streamk_reduce_kernel<DT_BF16, 256, 256>), rgrid, dim3(256), 0, stream, a);
+        else
+            hipLaunchKernelGGL((streamk_reduce_kernel<DT_F16, 256, 256>), rgrid, dim3(256), 0, stream, a);
+        if (hipGetLastError() != hipSuccess) return PEAK_ERR_HIP;
+    } else if (g->split > 1) {
         const int64_t quads = d.M * cdiv(d.N, 4);
         dim3 rgrid((unsigned)cdiv(quads, 256));
         if (c_dt == PEAK_DT_F32) hipLaunchKernelGGL(splitk_reduce_kernel<DT_F32>, rgrid, dim3(256), 0, stream, a);

@@ -222,6 +222,9 @@ WORKLOADS = {
                         "paper shape f16 2048^2 NN"),
     "P4k_f16": Workload("P4k_f16", F16, 4096, 4096, 4096, 0, 0, 1.0, 0.0, "uniform", 1.0, 8,
                         "paper shape f16 4096^2 NN"),
+    # 576 tiles of 256 x 256: two full rounds over 256 compute units and a quarter of a third (hybrid stream-K)
+    "SK_bf16": Workload("SK_bf16", BF16, 8192, 4608, 8192, 0, 1, 1.0, 0.0, "normal", 1.0 / math.sqrt(8192.0), 11,
+                        "bf16 8192x4608x8192 NT, 2.25 rounds of tiles"),
     # the two layouts with A stored K x M, as context for the [k][m] staging path
     "T4k_bf16_tn": Workload("T4k_bf16_tn", BF16, 4096, 4096, 4096, 1, 0, 1.0, 0.0, "normal", 1.0 / math.sqrt(4096.0), 9,
                             "bf16 4096^3 TN (A stored K x M, B stored K x N)"),

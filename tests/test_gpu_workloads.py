@@ -38,7 +38,7 @@ def _sample_rows(M, info, per_tile_row, seed):
 CASES = [("C1", 256, None), ("C2", 2, None), ("C3", 3, None), ("C3b", 3, None), ("C4", 3, None), ("C5", 16, None),
          ("C4", 2, 2), ("C4", 2, 3),
          ("P2k_f32", 2, None), ("P4k_f32", 2, None), ("P2k_f16", 3, None), ("P4k_f16", 3, None),
-         ("T4k_bf16_tn", 3, None), ("T4k_bf16_tt", 3, None)]
+         ("T4k_bf16_tn", 3, None), ("T4k_bf16_tt", 3, None), ("SK_bf16", 2, None)]
 
 
 @pytest.mark.parametrize("name,per_tile_row,split", CASES)

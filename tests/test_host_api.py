@@ -130,7 +130,7 @@ def test_plans_for_the_graded_workloads():
     assert ("f32_d" in info["C2"] or "f32_t" in info["C2"]) and "_nn" in info["C2"]
     assert "bf16_m256x256" in info["C3"] and "_nt" in info["C3"] and "tiles 32x32" in info["C3"]
     assert "bf16_m256x256" in info["C3b"]
-    assert ("f16_d" in info["C4"] or "f16_t" in info["C4"]) and "_nn" in info["C4"] and "tiles 20x12" in info["C4"]
+    assert "f16_m256x256" in info["C4"] and "_nn" in info["C4"] and "tiles 20x12" in info["C4"]
     assert "skinny" in info["C5"]
 
 
@@ -266,7 +266,7 @@ def test_fp32_c_flag_is_accepted_and_other_high_bits_are_not():
     st, h = pg.peak_gemm_create(_desc(dtype=pg.PEAK_DT_F32, flags=pg.PEAK_GEMM_C_F32))
     assert st == pg.PEAK_OK
     pg.peak_gemm_destroy(h)
-    for bad in (0x20000, 0x80000000, pg.PEAK_GEMM_C_F32 | 0x40000):
+    for bad in (0x80000, 0x80000000, pg.PEAK_GEMM_C_F32 | 0x100000, pg.PEAK_GEMM_STREAMK_ON | pg.PEAK_GEMM_STREAMK_OFF):
         st, h = pg.peak_gemm_create(_desc(flags=bad))
         assert st == pg.PEAK_ERR_INVALID_ARG and h is None
     assert pg.force_flags(3, 2, c_f32=True) == (4 | (2 << 8) | pg.PEAK_GEMM_C_F32)
@@ -343,3 +343,29 @@ def test_calibration_calls_check_their_arguments():
     assert pg.peak_calib_read(0, 1 << 20, 0x1000) == pg.PEAK_ERR_INVALID_ARG
     assert pg.peak_calib_read(0x1008, 1 << 20, 0x1000) == pg.PEAK_ERR_INVALID_ARG
     assert pg.peak_calib_read(0x1000, 8, 0x1000) == pg.PEAK_ERR_INVALID_ARG
+
+
+def test_hybrid_stream_k_plans():
+    """576 tiles of 256x256 on 256 compute units: two full rounds and 64 tiles over.  The cut
+    round: 64 tiles x 4 K slices, dense fp32 partial tiles in the workspace."""
+    env = {"PEAK_GEMM_NUM_CU": "256", "PEAK_GEMM_TUNING": ""}
+    code = ("import sys; sys.path.insert(0, %r); import paper_2512_19018_amd as pg\n"
+            "for sk in (True, False, None):\n"
+            "    with pg.Plan(8192, 4608, 8192, pg.PEAK_DT_BF16, 0, 1, flags=pg.force_flags(streamk=sk)) as p: print(p.info(), p.workspace_bytes)\n"
+            "with pg.Plan(8192, 8192, 8192, pg.PEAK_DT_BF16, 0, 1, flags=pg.force_flags(streamk=True)) as p: print(p.info(), p.workspace_bytes)\n"
+            "with pg.Plan(8192, 4608, 8192, pg.PEAK_DT_BF16, 0, 1, flags=pg.force_flags(split=2, streamk=True)) as p: print(p.info(), p.workspace_bytes)\n"
+            "with pg.Plan(8192, 4608, 8192, pg.PEAK_DT_F32, 0, 1, flags=pg.force_flags(streamk=True)) as p: print(p.info(), p.workspace_bytes)\n" % ROOT)
+    import subprocess
+    import sys
+    e = dict(os.environ)
+    e.update(env)
+    r = subprocess.run([sys.executable, "-c", code], capture_output=True, text=True, timeout=120, env=e)
+    assert r.returncode == 0, r.stderr
+    on, off, auto, exact, forced_split, f32 = r.stdout.strip().split("\n")
+    assert "bf16_m256x256w4a3_nt" in on and "streamk=64" in on and "split=4 " in on and "ktiles/slice=32" in on
+    assert "grid=%d " % (512 + 64 * 4) in on and on.endswith(" %d" % (4 * 64 * 256 * 256 * 4))
+    assert "streamk=0" in off and "split=1 " in off and off.endswith(" 0")
+    assert "streamk=64" in auto                              # a quarter round for a whole one: the cost model takes it
+    assert "streamk=0" in exact and "split=1 " in exact      # 1024 tiles: four whole rounds, nothing to cut
+    assert "streamk=0" in forced_split and "split=2 " in forced_split
+    assert "streamk=0" in f32                                # the fp32 kernels do not have it
