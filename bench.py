@@ -58,9 +58,16 @@ def measured_traffic(name, plan_info):
 
 def smi_snapshot():
     """Clocks and power as rocm-smi reports them (a child process; context only)."""
+    import shutil
     import subprocess
     try:
-        r = subprocess.run(["rocm-smi", "--showclocks", "--showpower", "--json"], capture_output=True, text=True, timeout=30)
+        # rocm-smi is a script: run it with this interpreter (no re-exec through env), and without a
+        # profiler's preloaded tool library, which would initialise the GPU in the child as well
+        tool = shutil.which("rocm-smi") or "/opt/rocm/bin/rocm-smi"
+        env = {k: v for k, v in os.environ.items()
+               if k not in ("LD_PRELOAD", "HSA_TOOLS_LIB", "ROCP_TOOL_LIBRARIES") and not k.startswith("ROCPROF")}
+        r = subprocess.run([sys.executable, tool, "--showclocks", "--showpower", "--json"], capture_output=True, text=True,
+                           timeout=30, env=env)
         d = json.loads(r.stdout)
         card = d[sorted(d)[0]]
         keep = {}

@@ -42,10 +42,23 @@ struct Cfg16 {
     // Chunk c of tile row r sits at chunk position c ^ swizzle(r).  The swizzle depends on
     // r % 16 only, so the fragments of rows r, r + 16, r + 32, ... lie a constant 2 KB apart
     // and one address register serves all of them through the read's immediate offset.
-    // A fragment read takes rows r0 .. r0 + 15 at one logical chunk: even rows share one half
-    // of the 256-byte bank period, odd rows the other, and within a half the eight rows get
-    // eight different chunk positions.
-    static __device__ __forceinline__ int swizzle(int r) { return (r & 7) ^ ((r >> 3) & 1); }
+    // A fragment read has lane l on row r0 + l % 16, logical chunk c0 + l / 16.  The LDS takes
+    // a 16-byte read in four steps of 16 lanes, lanes 8 i .. 8 i + 7 together with lanes
+    // 32 + 8 i .. 32 + 8 i + 7 (measured: a swizzle that is conflict-free for 16 consecutive
+    // lanes but not for these groups showed a bank conflict on every read): eight consecutive
+    // rows, each at chunks c and c + 2.  Rows two apart share the banks of one half of the
+    // 256-byte bank period, so the four rows of a half must be given four chunk positions
+    // whose partners under "^ 2" are four others: bit 1 of the swizzle is the same for the
+    // eight rows of a group (and differs between the two groups of a block, which keeps
+    // sixteen consecutive lanes conflict-free as well), bits 0 and 2 count the row pairs.
+    static __device__ __forceinline__ int swizzle(int r) { return ((r >> 1) & 1) | (((r >> 2) & 1) << 2) | (((r >> 3) & 1) << 1); }
+    // Tiles kept as [k][x] rows (512 bytes each, so all rows start in the same bank): chunk c of
+    // row k sits at c ^ kn_swizzle(k).  A transposing read has its four groups of 16 lanes on
+    // k-rows 8 q .. 8 q + 3 (q = lane / 16), 32 bytes of each.  4 * (k & 3) sends the four rows of
+    // a group to four different 64-byte bank groups; the second term moves the rows of groups
+    // q = 1 and q = 2 into the other 32-byte half, so that whichever two groups the LDS takes in
+    // one step (0 with 1 and 2 with 3, or 0 with 2 and 1 with 3) miss each other.
+    static __device__ __forceinline__ int kn_swizzle(int k) { return (4 * (k & 3)) ^ (2 * (((k >> 3) ^ (k >> 4)) & 1)); }
 };
 
 // Slot plan of the main loop: which fragment read (0 .. 15 of the next k-step), which of A's
@@ -131,7 +144,7 @@ __global__ __launch_bounds__(C::NT) void gemm16_kernel(const GemmArgs p)
         b_base[ks] = C::NSA * C::A_BYTES + rb * C::RB + (((4 * ks + q) ^ C::swizzle(rb)) << 4);
     }
     // Operand staged as [k][x] rows (x = m or n; 512 bytes per k-row, chunk c of row k at
-    // c ^ 4 * (k & 3)): the transposing read works on groups of 16 lanes, which together
+    // c ^ kn_swizzle(k)): the transposing read works on groups of 16 lanes, which together
     // point at 4 k-rows x 16 x (lane i of the group at k-row i / 4, columns 4 * (i % 4) .. + 3)
     // and each get the 4 k of one x.  Group lane / 16 takes k-rows 8 * (lane / 16) .. + 3, a
     // second read 4 rows on takes the other half of the lane's 8 k.  One address per block
@@ -144,7 +157,7 @@ __global__ __launch_bounds__(C::NT) void gemm16_kernel(const GemmArgs p)
 #pragma unroll
             for (int i = 0; i < C::MB; ++i) {
                 const int col = wm * C::WTM + i * 16 + 4 * (r16 & 3);
-                a_kx[i] = krow * (C::BM * C::ESZ) + (((col >> 3) ^ (4 * (krow & 3))) << 4) + (r16 & 1) * 8;
+                a_kx[i] = krow * (C::BM * C::ESZ) + (((col >> 3) ^ C::kn_swizzle(krow)) << 4) + (r16 & 1) * 8;
                 a_kx2[i] = a_kx[i] + 2 * C::A_BYTES;
             }
         }
@@ -152,7 +165,7 @@ __global__ __launch_bounds__(C::NT) void gemm16_kernel(const GemmArgs p)
 #pragma unroll
             for (int i = 0; i < C::NB; ++i) {
                 const int col = wn * C::WTN + i * 16 + 4 * (r16 & 3);
-                b_kx[i] = C::NSA * C::A_BYTES + krow * (C::BN * C::ESZ) + (((col >> 3) ^ (4 * (krow & 3))) << 4) + (r16 & 1) * 8;
+                b_kx[i] = C::NSA * C::A_BYTES + krow * (C::BN * C::ESZ) + (((col >> 3) ^ C::kn_swizzle(krow)) << 4) + (r16 & 1) * 8;
             }
         }
     }

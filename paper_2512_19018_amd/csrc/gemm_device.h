@@ -156,6 +156,8 @@ struct Cfg {
     static constexpr int B_BYTES = BN_ * RB_;
     // chunk c of tile row r sits at chunk position c ^ swizzle(r)
     static __device__ __forceinline__ int swizzle(int r) { return swz<RB_ / 16>(r); }
+    // ... and chunk c of row k of a 16-bit tile kept as [k][n] (or [k][m]) rows at c ^ kn_swizzle(k)
+    static __device__ __forceinline__ int kn_swizzle(int k) { return 4 * (k & 3); }
     // LDS: NSA stages of the A tile, then NSB stages of the B tile.  AX extra A
     // stages let A's loads run one more step ahead than B's when LDS cannot hold
     // another full stage of both (asymmetric ring, prefetch loops only).
@@ -417,7 +419,7 @@ struct LoaderDirectKN {
             const int j = wave + C::NW * i;
             const int row = j * RPI + lane / CPRN;
             const int pos = lane % CPRN;
-            int c = C::DT == DT_F32 ? pos : pos ^ (4 * (row & 3));           // fp32 reads are row-wise: no swizzle
+            int c = C::DT == DT_F32 ? pos : pos ^ C::kn_swizzle(row);       // fp32 reads are row-wise: no swizzle
             if (c > last_chunk) c = last_chunk;
             voff[i] = (int)((row * ld + (int64_t)c * C::EPC) * C::ESZ);
             voff_tail[i] = row >= tail_k ? OOB_VOFFSET : voff[i];
