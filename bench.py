@@ -41,10 +41,11 @@ PEAK_HBM_GBS = 8000.0
 # A figure belongs to the kernel variant it was measured on: it is reported only
 # when the plan of this run selects that very variant and split, else null.
 MEASURED_TRAFFIC = {
-    "C3": ("bf16_d256x256w4a3_nt", 1, 1.752e9),
-    "C5": ("bf16_skinny64k512s2_nt", 1, 5.424e8),
-    "C2": ("f32_t256x128w8_nn", 1, 9.20e8),
-    "C4": ("f16_t256x256w4a3_nn", 1, 7.63e8),
+    "C3": ("bf16_m256x256w4a3_nt", 1, 1.784e9),
+    "C3b": ("bf16_m256x256w4a3_nt", 1, 2.352e8),
+    "C5": ("bf16_skinny16s3_nt", 1, 5.564e8),
+    "C2": ("f32_t256x256w4a3_nn", 1, 5.380e8),
+    "C4": ("f16_m256x256w4a3_nn", 1, 7.340e8),
 }
 
 

@@ -14,7 +14,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 OBJ = os.path.join(CSRC, "_build")
 OUT = os.path.join(HERE, "libpeak_gemm.so")
-HEADERS = [os.path.join(CSRC, h) for h in ("gemm_device.h", "gemm16_device.h", "skinny_device.h", "variant.h",
+HEADERS = [os.path.join(CSRC, h) for h in ("gemm_device.h", "gemm16_device.h", "skinny_device.h", "variant.h", "planner.h",
                                            "variants_16nt.inc", "variants_16nn.inc")]
 HEADERS.append(os.path.join(HERE, "..", "include", "peak_gemm.h"))
 
@@ -26,7 +26,8 @@ HIPCC_FLAGS = [
 
 
 def sources():
-    return sorted(glob.glob(os.path.join(CSRC, "*.hip")))
+    # the kernels' translation units and the host-only planner (plain C++, compiled by the same driver)
+    return sorted(glob.glob(os.path.join(CSRC, "*.hip"))) + [os.path.join(CSRC, "planner.cpp")]
 
 
 def _hipcc():
@@ -34,7 +35,7 @@ def _hipcc():
 
 
 def _obj_of(src):
-    return os.path.join(OBJ, os.path.basename(src)[:-4] + ".o")
+    return os.path.join(OBJ, os.path.splitext(os.path.basename(src))[0] + ".o")
 
 
 def _stale(target, deps):

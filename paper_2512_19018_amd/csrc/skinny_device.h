@@ -8,6 +8,7 @@
 #pragma once
 
 #include "gemm_device.h"
+#include "planner.h"
 
 namespace peak {
 
@@ -40,19 +41,6 @@ struct SkinnyCfg {
 // chunk c of tile row r sits at position c ^ (r & 15) (in units of 16 bytes,
 // within the aligned group of 16 chunks c belongs to)
 PEAK_DEV int skinny_pos(int r, int c) { return c ^ (r & 15); }
-
-// Number of K slices: one workgroup per CU is enough once it streams (measured:
-// splitting further only adds the reduction pass), at least 4 stages each.
-static inline int skinny_split(int64_t N, int64_t K, int bn, int kstep)
-{
-    const int64_t tiles_n = (N + bn - 1) / bn;
-    const int64_t ktiles = (K + kstep - 1) / kstep;
-    int64_t s = (256 + tiles_n - 1) / tiles_n;
-    if (s > ktiles / 4) s = ktiles / 4;
-    if (s < 1) s = 1;
-    if (s > 64) s = 64;
-    return (int)s;
-}
 
 template <class C>
 __global__ __launch_bounds__(C::NT) void skinny_kernel(const GemmArgs p)
@@ -189,18 +177,6 @@ struct SkinnyRegCfg {
     static constexpr int KIT = 64;                      // k per iteration
     static constexpr int LDS_BYTES = 0;
 };
-
-// K slices for the register-streaming kernel: aim at >= 8 waves per CU
-static inline int skinny_reg_split(int64_t N, int64_t K)
-{
-    const int64_t groups = (N + 15) / 16;
-    const int64_t iters = K / 64;
-    int64_t s = (2048 + groups - 1) / groups;
-    if (s > iters / 16) s = iters / 16;
-    if (s < 1) s = 1;
-    if (s > 64) s = 64;
-    return (int)s;
-}
 
 template <class C>
 __global__ __launch_bounds__(C::NT) void skinny_reg_kernel(const GemmArgs p)

@@ -8,33 +8,9 @@
 #include <hip/hip_runtime.h>
 
 #include "gemm_device.h"
+#include "planner.h"
 
 namespace peak {
-
-typedef hipError_t (*launch_fn)(const GemmArgs &, dim3 grid, hipStream_t);
-
-enum Kind { KIND_TILED = 0, KIND_SKINNY = 1, KIND_SKINNY_REG = 2 };
-
-struct Variant {
-    const char *name;
-    int kind;
-    int dt;
-    int a_t, b_t;        // operand layouts the kernel was built for (1: stored K rows x M/N)
-    int direct;          // needs 16-byte aligned operand bases and rows (tiled: K a whole number of 16-byte chunks; skinny: K % BK == 0)
-    int bm, bn, bk, nt, ns, lds;
-    int max_m;           // skinny kernels: largest M
-    launch_fn launch;
-    int tr;              // B (K x N) goes to LDS untransposed ([k][n] rows)
-    int atr;             // A (K x M) goes to LDS untransposed ([k][m] rows)
-    int sweep_only;      // 1: reachable through the force bits only (kept for sweeps); the selector skips it
-    int stream_rank;     // streaming (skinny) kernels: 2 = the selector's first choice, 1 = its second, 0 = sweeps only
-    int mf16;            // built on the 16x16x32 MFMA (holds a higher clock under the chip's power limit)
-};
-
-struct VariantGroup {
-    const Variant *rows;
-    int count;
-};
 
 // one per translation unit
 VariantGroup variants_general();
@@ -48,10 +24,10 @@ VariantGroup variants_skinny();
 VariantGroup variants_mf16();
 
 template <class C>
-static hipError_t launch_gemm(const GemmArgs &a, dim3 grid, hipStream_t s)
+static int launch_gemm(const GemmArgs &a, unsigned grid, void *stream)
 {
-    hipLaunchKernelGGL((gemm_kernel<C>), grid, dim3(C::NT), 0, s, a);
-    return hipGetLastError();
+    hipLaunchKernelGGL((gemm_kernel<C>), dim3(grid), dim3(C::NT), 0, (hipStream_t)stream, a);
+    return hipGetLastError() == hipSuccess ? 0 : 1;
 }
 
 #define PEAK_BK(DT, RB) ((RB) / ((DT) == DT_F32 ? 4 : 2))

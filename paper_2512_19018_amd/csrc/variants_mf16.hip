@@ -5,12 +5,12 @@
 namespace peak {
 
 template <class C>
-static hipError_t launch_gemm16(const GemmArgs &a, dim3 grid, hipStream_t s)
+static int launch_gemm16(const GemmArgs &a, unsigned grid, void *stream)
 {
     // K ending inside a K tile takes the instantiation that can zero-fill the tail
-    if (a.K % C::BK != 0) hipLaunchKernelGGL((gemm16_kernel<C, true>), grid, dim3(C::NT), 0, s, a);
-    else hipLaunchKernelGGL((gemm16_kernel<C, false>), grid, dim3(C::NT), 0, s, a);
-    return hipGetLastError();
+    if (a.K % C::BK != 0) hipLaunchKernelGGL((gemm16_kernel<C, true>), dim3(grid), dim3(C::NT), 0, (hipStream_t)stream, a);
+    else hipLaunchKernelGGL((gemm16_kernel<C, false>), dim3(grid), dim3(C::NT), 0, (hipStream_t)stream, a);
+    return hipGetLastError() == hipSuccess ? 0 : 1;
 }
 
 // AKM: A stored K x M, staged as [k][m] rows; BKN: B stored K x N, staged as [k][n] rows
