@@ -392,7 +392,9 @@ struct LoaderDirect {
 // number of chunks; a chunk that would start at or past column N fetches the
 // row's last valid chunk instead (it only feeds columns of C that are never
 // stored), so every access stays inside the matrix.
-template <class C, int COLS>
+// SWZ: chunk positions go through C::kn_swizzle (the tiled fp32 kernels read their [k][n] tile row-wise
+// and leave it out)
+template <class C, int COLS, bool SWZ = (C::DT != DT_F32)>
 struct LoaderDirectKN {
     static constexpr int ROWB = COLS * C::ESZ;                    // bytes per k-row of the tile
     static constexpr int CPRN = ROWB / 16;
@@ -419,7 +421,8 @@ struct LoaderDirectKN {
             const int j = wave + C::NW * i;
             const int row = j * RPI + lane / CPRN;
             const int pos = lane % CPRN;
-            int c = C::DT == DT_F32 ? pos : pos ^ C::kn_swizzle(row);       // fp32 reads are row-wise: no swizzle
+            int c = pos;
+            if constexpr (SWZ) c = pos ^ C::kn_swizzle(row);
             if (c > last_chunk) c = last_chunk;
             voff[i] = (int)((row * ld + (int64_t)c * C::EPC) * C::ESZ);
             voff_tail[i] = row >= tail_k ? OOB_VOFFSET : voff[i];

@@ -60,8 +60,9 @@ static bool variant_fits(const Variant &v, const peak_gemm_desc_t &d)
             if ((a_along_k || b_along_k) && (d.K * es) % 16 != 0) return false;
             if (v.tr && (d.N * es) % 16 != 0) return false;
             if (v.atr && (d.M * es) % 16 != 0) return false;
-        } else if (d.K % v.bk != 0 || d.K < v.bk) {
-            return false;
+        } else {
+            if (d.K % v.bk != 0 || d.K < v.bk) return false;
+            if (v.tr && (d.N * es) % 16 != 0) return false;
         }
         if ((d.lda * es) % 16 != 0 || (d.ldb * es) % 16 != 0) return false;
         // a workgroup's operand panel is addressed with 32-bit byte offsets
@@ -180,7 +181,7 @@ static void plan_geometry(Geometry *p, const peak_gemm_desc_t &d, int variant, i
     p->split = (int)cdiv(p->ktiles_total, p->ktiles_per_slice);   // no empty slices
     p->group_m = p->tiles_m >= 8 ? 8 : (p->tiles_m > 0 ? p->tiles_m : 1);
     p->rot_m = 0;                                           // K rotation off for the tiled kernels: measured no gain on the graded shapes
-    p->rot_n = v.kind == KIND_SKINNY ? 5 : 0;               // streaming kernel: neighbouring workgroups start five K tiles apart
+    p->rot_n = v.kind == KIND_SKINNY && !v.tr ? 5 : 0;               // streaming kernel: neighbouring workgroups start five K tiles apart
                                                             // (bf16 16x16384x16384: 5.3 TB/s without, 6.0 with 1, 6.2 with 5 or 13)
     if (const char *e = getenv("PEAK_GEMM_GROUP_M")) {      // tuning knob: tile rows per band
         const int g = atoi(e);
@@ -210,12 +211,22 @@ static int select_variant(const peak_gemm_desc_t &d, bool staged_only)
 {
     double best = 0.0;
     int pick = -1, stream[4] = {-1, -1, -1, -1};            // first fitting streaming kernel of each rank
+    // streaming kernels: only those with the fewest rows of the M x K operand that hold M
+    int stream_bm = 0;
+    for (int i = 0; i < NUM_VARIANTS; ++i) {
+        const Variant &v = g_variants[i];
+        if (v.kind == KIND_TILED || v.sweep_only || (staged_only && v.direct) || !variant_fits(v, d)) continue;
+        if (stream_bm == 0 || v.bm < stream_bm) stream_bm = v.bm;
+    }
     for (int i = 0; i < NUM_VARIANTS; ++i) {
         const Variant &v = g_variants[i];
         if (v.sweep_only || (staged_only && v.direct) || !variant_fits(v, d)) continue;
         if (v.kind != KIND_TILED) {
-            // rank 3 only where one workgroup per tile of its (larger) BN fills four fifths of the chip
-            if (v.stream_rank == 3 && cdiv(d.N, v.bn) * 5 < (int64_t)num_cu() * 4) continue;
+            if (v.bm != stream_bm) continue;
+            // rank 3 only where one workgroup per tile of its (larger) BN fills four fifths of the chip, or where
+            // the M x K operand is tall enough for its re-reads to matter (every workgroup reads its K slice of
+            // all of it: bf16 64x8192x28672 takes 101.9 us with 128 rows per workgroup, 126.4 us with 64)
+            if (v.stream_rank == 3 && v.bm < 64 && cdiv(d.N, v.bn) * 5 < (int64_t)num_cu() * 4) continue;
             if (stream[v.stream_rank] < 0) stream[v.stream_rank] = i;
             continue;
         }

@@ -57,12 +57,14 @@ struct Geometry {
 int64_t grid_blocks(const Geometry &g);
 
 // Number of K slices: one workgroup per CU is enough once it streams (measured:
-// splitting further only adds the reduction pass), at least 4 stages each.
+// splitting further only adds the reduction pass), at least 4 stages each.  Workgroups on
+// four fifths of the CUs already count as enough (bf16 16x28672x8192 with 128 rows per
+// workgroup: 224 workgroups unsplit 74.9 us, 448 in two slices 87.1 us).
 static inline int skinny_split(int64_t N, int64_t K, int bn, int kstep)
 {
     const int64_t tiles_n = (N + bn - 1) / bn;
     const int64_t ktiles = (K + kstep - 1) / kstep;
-    int64_t s = (256 + tiles_n - 1) / tiles_n;
+    int64_t s = (256 + tiles_n / 4) / tiles_n;
     if (s > ktiles / 4) s = ktiles / 4;
     if (s < 1) s = 1;
     if (s > 64) s = 64;

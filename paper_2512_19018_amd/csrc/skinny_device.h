@@ -1,8 +1,9 @@
-// Streaming kernel for skinny products (M <= 16, both operands running along K
+// Streaming kernel for skinny products (M <= 64, both operands running along K
 // in memory): the N x K operand is read from HBM exactly once and that read is
 // the whole cost, so the kernel is built around keeping many direct-to-LDS
-// loads in flight per CU, not around the matrix cores (one 16x16x32 MFMA per
-// 32 k still does the arithmetic).  K is cut into slices (the paper's Split-K,
+// loads in flight per CU, not around the matrix cores (one 16x16 MFMA per
+// 16 rows of either operand and 32 k - 16 k in fp32 - still does the arithmetic).
+// K is cut into slices (the paper's Split-K,
 // Section 4.1 Table 2) so that enough workgroups stream at once; the fp32
 // partials are summed in slice order by splitk_reduce_kernel.
 #pragma once
@@ -12,12 +13,15 @@
 
 namespace peak {
 
-template <int DT_, int BN_, int KSTEP_, int NS_>
+// MBLK: 16-row blocks of the M x K operand (M <= 16 * MBLK); each wave multiplies all of them
+// with its 16 rows of the other operand.
+template <int DT_, int BN_, int KSTEP_, int NS_, int MBLK_ = 1>
 struct SkinnyCfg {
     static constexpr int DT = DT_;
-    static_assert(DT_ != DT_F32, "16-bit storage only");
-    static constexpr int ESZ = 2, EPC = 8;
-    static constexpr int BM = 16, BN = BN_, KSTEP = KSTEP_, NS = NS_;
+    static constexpr int ESZ = DT_ == DT_F32 ? 4 : 2, EPC = 16 / ESZ;
+    static constexpr int MBLK = MBLK_;
+    static constexpr int KMMA = 4 * EPC;                  // k per round of fragment reads: 4 chunks of 16 bytes
+    static constexpr int BM = 16 * MBLK_, BN = BN_, KSTEP = KSTEP_, NS = NS_;
     static constexpr int RB = KSTEP_ * ESZ;               // bytes per tile row and stage
     static constexpr int CPR = RB / 16;                   // 16-byte chunks per tile row
     static constexpr int NW = BN_ / 16;                   // one wave per 16 rows of the N x K operand
@@ -107,7 +111,9 @@ __global__ __launch_bounds__(C::NT) void skinny_kernel(const GemmArgs p)
     const int a_sw = r16, b_sw = (wave * 16 + r16) & 15;       // both equal r16; kept apart for clarity
 
     typedef float f32x4v __attribute__((ext_vector_type(4)));
-    f32x4v acc = {0.0f, 0.0f, 0.0f, 0.0f};
+    f32x4v acc[C::MBLK];
+#pragma unroll
+    for (int mb = 0; mb < C::MBLK; ++mb) acc[mb] = f32x4v{0.0f, 0.0f, 0.0f, 0.0f};
 
     constexpr int P = C::NS - 1;
 #pragma unroll
@@ -123,36 +129,52 @@ __global__ __launch_bounds__(C::NT) void skinny_kernel(const GemmArgs p)
                 issue(kt + P, (s + P) % C::NS);
                 const char *st = lds + s * C::STAGE_BYTES;
 #pragma unroll
-                for (int kg = 0; kg < C::KSTEP / 32; ++kg) {
+                for (int kg = 0; kg < C::KSTEP / C::KMMA; ++kg) {
                     const int c = kg * 4 + q;
-                    const u32x4 af = *(const u32x4 *)(st + a_row + (((c & ~15) | ((c & 15) ^ a_sw)) << 4));
                     const u32x4 bf = *(const u32x4 *)(st + b_row + (((c & ~15) | ((c & 15) ^ b_sw)) << 4));
-                    if (C::DT == DT_BF16)
-                        acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, bf),
-                                                                      __builtin_bit_cast(bf16x8, af), acc, 0, 0, 0);
-                    else
-                        acc = __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(f16x8, bf),
-                                                                     __builtin_bit_cast(f16x8, af), acc, 0, 0, 0);
+#pragma unroll
+                    for (int mb = 0; mb < C::MBLK; ++mb) {
+                        const u32x4 af = *(const u32x4 *)(st + a_row + mb * 16 * C::RB + (((c & ~15) | ((c & 15) ^ a_sw)) << 4));
+                        if constexpr (C::DT == DT_BF16)
+                            acc[mb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, bf),
+                                                                              __builtin_bit_cast(bf16x8, af), acc[mb], 0, 0, 0);
+                        else if constexpr (C::DT == DT_F16)
+                            acc[mb] = __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(f16x8, bf),
+                                                                             __builtin_bit_cast(f16x8, af), acc[mb], 0, 0, 0);
+                        else {
+                            // fp32: the chunk holds 4 k per lane; MFMA s takes element s of both chunks, so its
+                            // four k are 16 * kg + 4 * (lane / 16) + s over the four lane groups
+#pragma unroll
+                            for (int e = 0; e < 4; ++e) {
+                                const uint32_t be = bf[e], ae = af[e];      // (a bit cast straight from the vector's element takes element 0)
+                                acc[mb] = __builtin_amdgcn_mfma_f32_16x16x4f32(__builtin_bit_cast(float, be),
+                                                                               __builtin_bit_cast(float, ae), acc[mb], 0, 0, 0);
+                            }
+                        }
+                    }
                 }
             }
         }
     }
     wait_vmcnt<0>();        // the refetches past the end must land before this workgroup's LDS is given away
 
-    // acc[v] <-> m = lane % 16, n = n0 + wave*16 + 4*(lane/16) + v
-    const int64_t m = r16;
+    // acc[mb][v] <-> m = 16*mb + lane % 16, n = n0 + wave*16 + 4*(lane/16) + v
     const int64_t n = n0 + wave * 16 + q * 4;
     const int64_t left = p.N - n;
-    if (m < p.M && left > 0) {
-        const int nvalid = left >= 4 ? 4 : (int)left;
-        const float x[4] = {acc[0], acc[1], acc[2], acc[3]};
-        if (p.split > 1)
-            store4<DT_F32>(p.ws + (int64_t)slice * p.M * p.N, m * p.N + n, x, 1.0f, 0.0f, p.flags & GF_WS_VEC, nvalid);
-        else {
-            if (p.flags & GF_C_F32)
-                store4<DT_F32>(p.C, m * p.ldc + n, x, p.alpha, p.beta, p.flags & GF_C_VEC, nvalid, p.hook, m, n);
-            else
-                store4<C::DT>(p.C, m * p.ldc + n, x, p.alpha, p.beta, p.flags & GF_C_VEC, nvalid, p.hook, m, n);
+#pragma unroll
+    for (int mb = 0; mb < C::MBLK; ++mb) {
+        const int64_t m = mb * 16 + r16;
+        if (m < p.M && left > 0) {
+            const int nvalid = left >= 4 ? 4 : (int)left;
+            const float x[4] = {acc[mb][0], acc[mb][1], acc[mb][2], acc[mb][3]};
+            if (p.split > 1)
+                store4<DT_F32>(p.ws + (int64_t)slice * p.M * p.N, m * p.N + n, x, 1.0f, 0.0f, p.flags & GF_WS_VEC, nvalid);
+            else {
+                if (p.flags & GF_C_F32)
+                    store4<DT_F32>(p.C, m * p.ldc + n, x, p.alpha, p.beta, p.flags & GF_C_VEC, nvalid, p.hook, m, n);
+                else
+                    store4<C::DT>(p.C, m * p.ldc + n, x, p.alpha, p.beta, p.flags & GF_C_VEC, nvalid, p.hook, m, n);
+            }
         }
     }
 }
@@ -247,6 +269,220 @@ __global__ __launch_bounds__(C::NT) void skinny_reg_kernel(const GemmArgs p)
                 store4<C::DT>(p.C, m * p.ldc + n, x, p.alpha, p.beta, p.flags & GF_C_VEC, nvalid, p.hook, m, n);
         }
     }
+}
+
+// ---------------------------------------------------------------------------
+// Streaming kernel for skinny products whose N-side operand is stored K x N
+// (B with transB = 0; A runs along K): the same idea, with the big operand kept
+// in LDS as [k][n] rows of 512 bytes.  A workgroup owns 512 bytes of every k-row
+// (256 columns in 16 bits, 128 in fp32) over one K slice; a stage is 128 bytes of
+// K per row of A (64 k in 16 bits, 32 in fp32).  All workgroups walk the same
+// k-rows at the same time, which are contiguous in memory across the workgroups,
+// so the requests spread over the memory channels without a rotation.
+//   16 bits: the N-side fragments of the 16x16x32 MFMA come from transposing reads
+//            (ds_read_b64_tr_b16), with the tile's chunks placed as in the 16x16x32 tiled kernels.
+//   fp32:    16x16x4 MFMA; a lane needs one element of a k-row, read as such; chunk c of
+//            k-row k sits at c ^ 4 * ((k >> 2) & 3), so the four k-rows of one read fall
+//            into four different groups of 16 banks.
+// ---------------------------------------------------------------------------
+template <int DT_, int NS_, int MBLK_, int NW_ = 8>
+struct SkinnyKnCfg {
+    static constexpr int DT = DT_;
+    static constexpr int ESZ = DT_ == DT_F32 ? 4 : 2, EPC = 16 / ESZ;
+    static constexpr int MBLK = MBLK_, NS = NS_, NW = NW_, NT = NW_ * 64;
+    static constexpr int RB = 128;                        // bytes of K per stage row of A
+    static constexpr int CPR = RB / 16;
+    static constexpr int BK = RB / ESZ, KSTEP = BK;       // k per stage
+    static constexpr int ROWB = 512;                      // bytes per k-row of the N-side tile
+    static constexpr int BM = 16 * MBLK_, BN = ROWB / ESZ;
+    static constexpr int NBW = BN / 16 / NW_;             // 16-column blocks per wave
+    static_assert(NBW >= 1 && NBW * 16 * NW_ == BN, "whole blocks per wave");
+    static constexpr int A_BYTES = BM * RB, B_BYTES = BK * ROWB;
+    static constexpr int STAGE_BYTES = A_BYTES + B_BYTES;
+    static constexpr int LDS_BYTES = STAGE_BYTES * NS_;
+    static constexpr int A_INST = BM * CPR / 64;          // 1024-byte wave loads per stage of A
+    static_assert(A_INST % NW_ == 0 || NW_ % A_INST == 0, "A loads split evenly");
+    static constexpr int A_PER_WAVE = A_INST >= NW_ ? A_INST / NW_ : 1;   // waves beyond A_INST repeat one of another wave
+    // chunk c of A's tile row r sits at c ^ swizzle(r): a fragment read's step takes 8 rows at chunk c and the
+    // same rows at chunk c + 2; bits 0 and 2 separate the rows of one parity, bit 1 is left to the chunk
+    static __device__ __forceinline__ int swizzle(int r) { return ((r >> 1) & 1) | (((r >> 2) & 1) << 2); }
+    static __device__ __forceinline__ int kn_swizzle(int k)
+    {
+        if constexpr (DT_ == DT_F32) return 4 * ((k >> 2) & 3);
+        else return (4 * (k & 3)) ^ (2 * (((k >> 3) ^ (k >> 4)) & 1));
+    }
+};
+
+template <class C>
+__global__ __launch_bounds__(C::NT) void skinny_kn_kernel(const GemmArgs p)
+{
+    __shared__ __attribute__((aligned(1024))) char lds[C::LDS_BYTES];
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int tn = blockIdx.x % p.tiles_n, slice = blockIdx.x / p.tiles_n;
+    const int64_t n0 = (int64_t)tn * C::BN;
+    const int r16 = lane & 15, q = lane >> 4;
+
+    const int kt_begin = slice * p.ktiles_per_slice;
+    int kt_end = kt_begin + p.ktiles_per_slice;
+    if (kt_end > p.ktiles_total) kt_end = p.ktiles_total;
+    const int KT = kt_end - kt_begin;
+    const int64_t kbase = (int64_t)kt_begin * C::KSTEP;
+
+    // A: this lane's direct loads at the slice's first k
+    const char *ga[C::A_PER_WAVE];
+    int ja[C::A_PER_WAVE];
+#pragma unroll
+    for (int i = 0; i < C::A_PER_WAVE; ++i) {
+        const int j = (wave + C::NW * i) % C::A_INST;
+        const int row = j * (64 / C::CPR) + lane / C::CPR, pos = lane % C::CPR;
+        const int c = pos ^ C::swizzle(row);
+        int64_t gr = row;
+        if (gr > p.M - 1) gr = p.M - 1;
+        ga[i] = (const char *)p.A + (gr * p.lda + kbase + (int64_t)c * C::EPC) * C::ESZ;
+        ja[i] = j;
+    }
+    LoaderDirectKN<C, C::BN, true> nB;
+    nB.init(p.B, p.ldb, n0, p.N, kbase, p.K, C::BK, wave, lane);
+    constexpr int LB = LoaderDirectKN<C, C::BN, true>::PER_WAVE;
+    static_assert(LoaderDirectKN<C, C::BN, true>::NINST % C::NW == 0, "every wave issues the same number of loads");
+    constexpr int DLOADS = C::A_PER_WAVE + LB;
+
+    auto issue = [&](int kt, int stage) {
+        const int kc = kt < KT ? kt : KT - 1;             // past the end: refetch the last tile into a free stage
+        char *st = lds + stage * C::STAGE_BYTES;
+#pragma unroll
+        for (int i = 0; i < C::A_PER_WAVE; ++i)
+            __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)(ga[i] + (int64_t)kc * C::RB),
+                                             (__attribute__((address_space(3))) void *)(st + ja[i] * 1024), 16, 0, 0);
+        nB.template issue_at<0, 1, false>(st + C::A_BYTES, nB.soffset_of(kc), false, wave);
+    };
+
+    // fragment addresses within a stage
+    //   A: lane reads tile row 16 mb + lane % 16, chunk 4 g + lane / 16 of k-group g (a quarter of the stage's K)
+    const int a_addr0 = r16 * C::RB + ((q ^ C::swizzle(r16)) << 4);          // g = 0; g = 1 flips chunk bit 2
+    const int a_addr1 = r16 * C::RB + (((4 + q) ^ C::swizzle(r16)) << 4);
+    //   N side, 16 bits: see the 16x16x32 tiled kernels (k-rows 8 q + r16 / 4 and four rows on, 4 columns per lane)
+    //   N side, fp32: element (k-row 16 g + 4 q + e, column block's lane % 16)
+    int b_addr[C::NBW];
+#pragma unroll
+    for (int i = 0; i < C::NBW; ++i) {
+        if constexpr (C::DT == DT_F32) {
+            const int col = (wave * C::NBW + i) * 16 + r16;
+            b_addr[i] = C::A_BYTES + (4 * q) * C::ROWB + (((col >> 2) ^ C::kn_swizzle(4 * q)) << 4) + (col & 3) * 4;
+        } else {
+            const int krow = 8 * q + (r16 >> 2);
+            const int col = (wave * C::NBW + i) * 16 + 4 * (r16 & 3);
+            b_addr[i] = C::A_BYTES + krow * C::ROWB + (((col >> 3) ^ C::kn_swizzle(krow)) << 4) + (r16 & 1) * 8;
+        }
+    }
+    const uint32_t lds_b0 = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) char *)lds;
+
+    typedef float f32x4v __attribute__((ext_vector_type(4)));
+    f32x4v acc[C::MBLK][C::NBW];
+#pragma unroll
+    for (int mb = 0; mb < C::MBLK; ++mb)
+#pragma unroll
+        for (int i = 0; i < C::NBW; ++i) acc[mb][i] = f32x4v{0.0f, 0.0f, 0.0f, 0.0f};
+
+    constexpr int P = C::NS - 1;
+#pragma unroll
+    for (int s = 0; s < P; ++s) issue(s, s);
+
+    for (int kt0 = 0; kt0 < KT; kt0 += C::NS) {
+        static_for<C::NS>([&](auto sc) {
+            constexpr int s = decltype(sc)::value;
+            const int kt = kt0 + s;
+            if (kt < KT) {
+                wait_vmcnt<(P - 1) * DLOADS>();
+                lds_barrier();
+                issue(kt + P, (s + P) % C::NS);
+                const char *st = lds + s * C::STAGE_BYTES;
+                u32x4 af[2][C::MBLK];
+#pragma unroll
+                for (int mb = 0; mb < C::MBLK; ++mb) {
+                    af[0][mb] = *(const u32x4 *)(st + a_addr0 + mb * 16 * C::RB);
+                    af[1][mb] = *(const u32x4 *)(st + a_addr1 + mb * 16 * C::RB);
+                }
+                if constexpr (C::DT == DT_F32) {
+                    float bv[2][4][C::NBW];
+#pragma unroll
+                    for (int g = 0; g < 2; ++g)
+#pragma unroll
+                        for (int e = 0; e < 4; ++e)
+#pragma unroll
+                            for (int i = 0; i < C::NBW; ++i) bv[g][e][i] = *(const float *)(st + b_addr[i] + (16 * g + e) * C::ROWB);
+#pragma unroll
+                    for (int g = 0; g < 2; ++g)
+#pragma unroll
+                        for (int e = 0; e < 4; ++e)
+#pragma unroll
+                            for (int i = 0; i < C::NBW; ++i)
+#pragma unroll
+                                for (int mb = 0; mb < C::MBLK; ++mb) {
+                                    const uint32_t ae = af[g][mb][e];
+                                    acc[mb][i] = __builtin_amdgcn_mfma_f32_16x16x4f32(bv[g][e][i], __builtin_bit_cast(float, ae),
+                                                                                      acc[mb][i], 0, 0, 0);
+                                }
+                } else {
+                    // the transposing reads go out as assembly (the compiler would put a wait for every outstanding
+                    // direct-to-LDS load in front of them); one wait for everything asked of LDS hands them over
+                    u32x2 lo[2][C::NBW], hi[2][C::NBW];
+                    static_for<2>([&](auto gc) {
+                        constexpr int g = decltype(gc)::value;
+                        static_for<C::NBW>([&](auto ic) {
+                            constexpr int i = decltype(ic)::value;
+                            constexpr int off = g * 32 * C::ROWB;               // (the immediate holds 16 bits: the stage goes into the address)
+                            const uint32_t a0 = lds_b0 + b_addr[i] + s * C::STAGE_BYTES;
+                            u32x2 &l = lo[g][i], &h = hi[g][i];
+                            asm volatile("ds_read_b64_tr_b16 %0, %1 offset:%2" : "=v"(l) : "v"(a0), "n"(off) : "memory");
+                            asm volatile("ds_read_b64_tr_b16 %0, %1 offset:%2" : "=v"(h) : "v"(a0), "n"(off + 4 * C::ROWB) : "memory");
+                        });
+                    });
+                    __builtin_amdgcn_s_waitcnt(waitcnt_imm(63, 0));
+#pragma unroll
+                    for (int g = 0; g < 2; ++g)
+#pragma unroll
+                        for (int i = 0; i < C::NBW; ++i) {
+                            u32x2 &l = lo[g][i], &h = hi[g][i];
+                            asm volatile("" : "+v"(l), "+v"(h));
+                            const u32x4 bf = u32x4{l[0], l[1], h[0], h[1]};
+#pragma unroll
+                            for (int mb = 0; mb < C::MBLK; ++mb) {
+                                if constexpr (C::DT == DT_BF16)
+                                    acc[mb][i] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, bf),
+                                                                                         __builtin_bit_cast(bf16x8, af[g][mb]), acc[mb][i], 0, 0, 0);
+                                else
+                                    acc[mb][i] = __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(f16x8, bf),
+                                                                                        __builtin_bit_cast(f16x8, af[g][mb]), acc[mb][i], 0, 0, 0);
+                            }
+                        }
+                }
+            }
+        });
+    }
+    wait_vmcnt<0>();        // the refetches past the end must land before this workgroup's LDS is given away
+
+    // acc[mb][i][v] <-> m = 16 mb + lane % 16, n = n0 + 16 (wave NBW + i) + 4 (lane / 16) + v
+#pragma unroll
+    for (int mb = 0; mb < C::MBLK; ++mb)
+#pragma unroll
+        for (int i = 0; i < C::NBW; ++i) {
+            const int64_t m = mb * 16 + r16;
+            const int64_t n = n0 + (wave * C::NBW + i) * 16 + q * 4;
+            const int64_t left = p.N - n;
+            if (m < p.M && left > 0) {
+                const int nvalid = left >= 4 ? 4 : (int)left;
+                const float x[4] = {acc[mb][i][0], acc[mb][i][1], acc[mb][i][2], acc[mb][i][3]};
+                if (p.split > 1)
+                    store4<DT_F32>(p.ws + (int64_t)slice * p.M * p.N, m * p.N + n, x, 1.0f, 0.0f, p.flags & GF_WS_VEC, nvalid);
+                else {
+                    if (p.flags & GF_C_F32)
+                        store4<DT_F32>(p.C, m * p.ldc + n, x, p.alpha, p.beta, p.flags & GF_C_VEC, nvalid, p.hook, m, n);
+                    else
+                        store4<C::DT>(p.C, m * p.ldc + n, x, p.alpha, p.beta, p.flags & GF_C_VEC, nvalid, p.hook, m, n);
+                }
+            }
+        }
 }
 
 }  // namespace peak

@@ -225,6 +225,17 @@ WORKLOADS = {
     # 576 tiles of 256 x 256: two full rounds over 256 compute units and a quarter of a third (hybrid stream-K)
     "SK_bf16": Workload("SK_bf16", BF16, 8192, 4608, 8192, 0, 1, 1.0, 0.0, "normal", 1.0 / math.sqrt(8192.0), 11,
                         "bf16 8192x4608x8192 NT, 2.25 rounds of tiles"),
+    # skinny products outside M <= 16 / 16 bits / B along K: the streaming path's other cases (HBM bound)
+    "S32_bf16": Workload("S32_bf16", BF16, 32, 28672, 8192, 0, 1, 1.0, 0.0, "normal", 0.02, 12,
+                         "bf16 skinny 32x28672x8192 NT (HBM bound)"),
+    "S64_f16": Workload("S64_f16", F16, 64, 28672, 8192, 0, 1, 1.0, 0.0, "normal", 0.02, 13,
+                        "f16 skinny 64x28672x8192 NT (HBM bound)"),
+    "S16_f32": Workload("S16_f32", F32, 16, 16384, 16384, 0, 1, 1.0, 0.0, "normal", 0.02, 14,
+                        "fp32 skinny 16x16384x16384 NT (HBM bound)"),
+    "S16_bf16_kn": Workload("S16_bf16_kn", BF16, 16, 28672, 8192, 0, 0, 1.0, 0.0, "normal", 0.02, 15,
+                            "bf16 skinny 16x28672x8192 NN, B stored K x N (HBM bound)"),
+    "S16_f32_kn": Workload("S16_f32_kn", F32, 16, 28672, 8192, 0, 0, 1.0, 0.0, "normal", 0.02, 16,
+                           "fp32 skinny 16x28672x8192 NN, B stored K x N (HBM bound)"),
     # the two layouts with A stored K x M, as context for the [k][m] staging path
     "T4k_bf16_tn": Workload("T4k_bf16_tn", BF16, 4096, 4096, 4096, 1, 0, 1.0, 0.0, "normal", 1.0 / math.sqrt(4096.0), 9,
                             "bf16 4096^3 TN (A stored K x M, B stored K x N)"),

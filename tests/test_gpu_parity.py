@@ -39,6 +39,12 @@ def _stored(seed, dtype, M, N, K, transA, transB, pad=(0, 0, 0), ints=False, dis
     return A, B, C
 
 
+def _skinny_max_m(name):
+    """Largest M of a streaming variant: "_m<rows>n..." in the names that say it, else 16."""
+    m = re.search(r"skinny_m(\d+)n", name)
+    return int(m.group(1)) if m else 16
+
+
 def _check_padding(raw, C0, M, N):
     # everything outside the logical M x N block must be byte-identical to before
     assert np.array_equal(raw[:, N:].view(np.uint8), C0[:, N:].view(np.uint8))
@@ -58,7 +64,9 @@ def test_exact_integers_every_variant(gu, oracle, dtype, transA, transB):
         if "skinny" in name:
             m = re.search(r"k(\d+)s", name)
             ks = int(m.group(1)) if m else (64 if "skinnyreg" in name else 128)
-            shapes = [(16, 192, ks), (7, 130, 2 * ks), (1, 64, ks)]
+            mm = _skinny_max_m(name)
+            n2 = 130 if transB else 136                    # B as [k][n] rows: N a whole number of 16-byte chunks
+            shapes = [(mm, 192, ks), (mm - 9, n2, 2 * ks), (1, 64, ks)] + ([(mm - 15, 72, ks)] if mm > 16 else [])
         elif direct:
             bk = 32 if ("f32" in name or "k32" in name) else 64
             epc = 16 // pi.DTYPE_SIZE[dtype]
@@ -103,7 +111,7 @@ def test_random_every_direct_variant_deep_k(gu, oracle, dtype):
             if not (re.search(r"_(?:d|t|p|pt|m)\d", name) or "skinny" in name):
                 continue
             # tiled kernels also get a K that ends inside the last K tile (of the last K slice)
-            shapes = [(13, 1000, 4096)] if "skinny" in name else [(300, 520, 1024), (260, 264, 1000)]
+            shapes = [(_skinny_max_m(name) - 3, 1000, 4096)] if "skinny" in name else [(300, 520, 1024), (260, 264, 1000)]
             if transA and "skinny" not in name:
                 shapes = [(304, 520, 1024), (264, 264, 1000)] + ([(264, 264, 1003)] if not transB else [])
             for M, N, K in shapes:
@@ -305,7 +313,8 @@ def test_exact_integers_deep_k_every_direct_variant(gu, oracle, dtype):
             if not (re.search(r"_(?:d|t|p|pt|m)\d", name) or "skinny" in name):
                 continue
             if "skinny" in name:
-                shapes = [(13, 1000, 4096), (16, 264, 4096)]
+                mm = _skinny_max_m(name)
+                shapes = [(mm - 3, 1000, 4096), (mm, 264, 4096)]
             elif transA:
                 shapes = [(304, 520, 1024), (264, 264, 2056 if transB else 2051)]
             else:
@@ -336,8 +345,8 @@ def test_operand_base_off_16_bytes_with_aligned_rows(gu, oracle, dtype):
     es = pi.DTYPE_SIZE[dtype]
     for transA, transB in LAYOUTS:
         for M, N, K, split in [(264, 520, 1024, None), (264, 520, 2048, 4), (16, 512, 1024, None)]:
-            if M == 16 and (transA or not transB or dtype == pi.F32):
-                continue                                   # the streaming kernels: 16-bit, both operands along K
+            if M == 16 and (transA or not transB):
+                continue                                   # the streaming kernels: both operands along K
             A, B, C = _stored(3100 + M, dtype, M, N, K, transA, transB)
             with gu.pg.Plan(M, N, K, dtype, transA, transB, flags=gu.pg.force_flags(split=split)) as plan:
                 info = plan.info()

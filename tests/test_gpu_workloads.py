@@ -38,7 +38,10 @@ def _sample_rows(M, info, per_tile_row, seed):
 CASES = [("C1", 256, None), ("C2", 2, None), ("C3", 3, None), ("C3b", 3, None), ("C4", 3, None), ("C5", 16, None),
          ("C4", 2, 2), ("C4", 2, 3),
          ("P2k_f32", 2, None), ("P4k_f32", 2, None), ("P2k_f16", 3, None), ("P4k_f16", 3, None),
-         ("T4k_bf16_tn", 3, None), ("T4k_bf16_tt", 3, None), ("SK_bf16", 2, None)]
+         ("T4k_bf16_tn", 3, None), ("T4k_bf16_tt", 3, None), ("SK_bf16", 2, None),
+         # the streaming path beyond M <= 16 / 16 bits / B along K: every row
+         ("S32_bf16", 32, None), ("S64_f16", 64, None), ("S16_f32", 16, None), ("S16_bf16_kn", 16, None),
+         ("S16_f32_kn", 16, None)]
 
 
 @pytest.mark.parametrize("name,per_tile_row,split", CASES)
@@ -49,6 +52,8 @@ def test_workload_against_oracle(gu, oracle, name, per_tile_row, split):
     C0 = C if w.beta != 0 else gu.nan_fill(w.M, w.N, w.dtype)
     got, raw, info = gu.run_gemm(w.dtype, w.transA, w.transB, w.M, w.N, w.K, w.alpha, w.beta, A, B, C0, flags=flags)
     print(name, info)
+    if name.startswith("S") and name != "SK_bf16":
+        assert "skinny" in info, info
     if split is not None:
         assert "split=%d" % split in info, info
     rows = _sample_rows(w.M, info, per_tile_row, 7)

@@ -369,3 +369,30 @@ def test_hybrid_stream_k_plans():
     assert "streamk=0" in exact and "split=1 " in exact      # 1024 tiles: four whole rounds, nothing to cut
     assert "streamk=0" in forced_split and "split=2 " in forced_split
     assert "streamk=0" in f32                                # the fp32 kernels do not have it
+
+
+def test_streaming_plans_cover_m_up_to_64_fp32_and_b_stored_k_by_n():
+    """Skinny products (M <= 64) whose big operand can be streamed once go to a streaming
+    kernel: fewest 16-row blocks that hold M, fp32 as well as 16-bit storage, B along K or
+    stored K x N; other shapes and layouts stay with the tiled kernels."""
+    def info(M, N, K, dt, tA, tB):
+        with pg.Plan(M, N, K, dt, tA, tB) as p:
+            return p.info()
+    bf, f16, f32 = pg.PEAK_DT_BF16, pg.PEAK_DT_F16, pg.PEAK_DT_F32
+    assert "bf16_skinny128k256s2_nt" in info(16, 28672, 8192, bf, 0, 1)
+    assert "split=1 " in info(16, 28672, 8192, bf, 0, 1)              # 224 workgroups on 256 CUs: no K split
+    assert "skinny_m32n128" in info(17, 28672, 8192, bf, 0, 1)
+    assert "skinny_m32n64" in info(32, 4096, 4096, f16, 0, 1)
+    assert "skinny_m64n128" in info(33, 8192, 28672, bf, 0, 1)        # tall M x K operand: 128 rows per workgroup even when split
+    assert "skinny_m64n128" in info(64, 28672, 8192, f16, 0, 1)
+    assert "skinny" not in info(65, 28672, 8192, bf, 0, 1)
+    assert "f32_skinny_m16" in info(16, 16384, 16384, f32, 0, 1)
+    assert "f32_skinny_m64n64k64s3_nt" in info(64, 16384, 8192, f32, 0, 1)
+    # B stored K x N
+    assert "bf16_skinny_m16n256k64s4_nn" in info(16, 28672, 8192, bf, 0, 0)
+    assert "f16_skinny_m64n256k64s4_nn" in info(48, 28672, 8192, f16, 0, 0)
+    assert "f32_skinny_m32n128k32s6_nn" in info(20, 16384, 8192, f32, 0, 0)
+    assert "skinny" not in info(16, 28668, 8192, bf, 0, 0)            # N not a whole number of 16-byte chunks
+    assert "skinny" not in info(16, 28672, 8200, bf, 0, 0)            # K not a whole number of stages
+    # A stored K x M: no streaming kernel
+    assert "skinny" not in info(16, 28672, 8192, bf, 1, 1) and "skinny" not in info(16, 28672, 8192, bf, 1, 0)
