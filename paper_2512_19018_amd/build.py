@@ -14,7 +14,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 OBJ = os.path.join(CSRC, "_build")
 OUT = os.path.join(HERE, "libpeak_gemm.so")
-HEADERS = [os.path.join(CSRC, h) for h in ("gemm_device.h", "gemm16_device.h", "skinny_device.h", "variant.h", "planner.h",
+HEADERS = [os.path.join(CSRC, h) for h in ("gemm_device.h", "gemm16_device.h", "skinny_device.h", "variant.h", "variant16.h", "planner.h",
                                            "variants_16nt.inc", "variants_16nn.inc")]
 HEADERS.append(os.path.join(HERE, "..", "include", "peak_gemm.h"))
 

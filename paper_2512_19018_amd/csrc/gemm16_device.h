@@ -24,16 +24,21 @@ namespace peak {
 
 typedef float f32x4v __attribute__((ext_vector_type(4)));
 
-template <int DT_, bool A_KM_ = false, bool B_KN_ = false>
+// TILE: 256 (the large problems: one workgroup per CU, one wave per SIMD, 128x128 per wave) or
+// 128 (mid-size problems: 64x64 per wave, 80 KB of LDS and half the registers, so two workgroups
+// share a CU and cover each other's waits)
+template <int DT_, bool A_KM_ = false, bool B_KN_ = false, int TILE_ = 256>
 struct Cfg16 {
     static_assert(DT_ == DT_F16 || DT_ == DT_BF16, "16-bit storage");
+    static_assert(TILE_ == 256 || TILE_ == 128, "workgroup tile");
     static constexpr int DT = DT_;
     static constexpr bool A_KM = A_KM_;                      // A stored K x M: staged as [k][m] rows
     static constexpr bool B_KN = B_KN_;                      // B stored K x N: staged as [k][n] rows
     static constexpr int ESZ = 2, EPC = 8;
-    static constexpr int BM = 256, BN = 256, RB = 128, CPR = 8, BK = 64;
+    static constexpr int BM = TILE_, BN = TILE_, RB = 128, CPR = 8, BK = 64;
     static constexpr int WAVES_M = 2, WAVES_N = 2, NW = 4, NT = 256;
-    static constexpr int WTM = 128, WTN = 128;
+    static constexpr int WAVES_PER_EU = 256 / TILE_;        // workgroups per CU the register budget is cut for
+    static constexpr int WTM = BM / 2, WTN = BN / 2;
     static constexpr int MB = WTM / 16, NB = WTN / 16;      // 16x16 blocks per wave tile
     static constexpr int KS = BK / 32;                      // MFMA k-steps per K tile
     static constexpr int NSA = 3, NSB = 2;
@@ -68,18 +73,28 @@ struct Cfg16 {
 // (1503 TFLOP/s in that run): reads after each of the first 16 MFMAs and the loads after them
 // 1371, all loads in the second half of the k-step 1410, one load after every 8th MFMA
 // throughout the same within 0.3 %.
+// The 128 x 128 tile has 16 MFMAs and 8 fragments per k-step: the reads follow the first 8 MFMAs
+// (so the last has returned when the k-step ends), the loads the other 8, evenly spaced.
 constexpr int slot_pick(bool hit, int idx, int count) { return hit && idx >= 0 && idx < count ? idx : -1; }
-constexpr int slot_read_of(int j) { return slot_pick(j % 2 == 0, j / 2, 16); }
-constexpr int slot_a0_of(int j, int n) { return slot_pick(j % 16 == 1, j / 16, n); }
-constexpr int slot_b1_of(int j, int n) { return slot_pick(j % 4 == 1, j / 4, n); }
-constexpr int slot_a1_of(int j, int n) { return slot_pick(j % 8 == 3 && j / 8 >= 4, j / 8 - 4, n); }
+constexpr int slot_read_of(int j, int nm, int nfr) { return nm >= 4 * nfr ? slot_pick(j % 2 == 0, j / 2, nfr) : slot_pick(true, j, nfr); }
+// position t of n loads spread over the slots behind the reads (the small tile's plan)
+constexpr int slot_late(int j, int nm, int nfr, int n) { return j >= nfr && n > 0 && (j - nfr) % ((nm - nfr) / n) == 0 ? (j - nfr) / ((nm - nfr) / n) : -1; }
+constexpr int slot_a0_of(int j, int n, int nm, int nfr) { return nm >= 4 * nfr ? slot_pick(j % 16 == 1, j / 16, n) : slot_pick(true, slot_late(j, nm, nfr, n), n); }
+constexpr int slot_b1_of(int j, int n, int nm, int nfr, int na1)
+{
+    return nm >= 4 * nfr ? slot_pick(j % 4 == 1, j / 4, n) : slot_pick(true, slot_late(j, nm, nfr, n + na1), n);
+}
+constexpr int slot_a1_of(int j, int n, int nm, int nfr, int nb1)
+{
+    return nm >= 4 * nfr ? slot_pick(j % 8 == 3 && j / 8 >= 4, j / 8 - 4, n) : slot_pick(true, slot_late(j, nm, nfr, n + nb1) - nb1, n);
+}
 
 // MAY_TAIL false: K is a whole number of K tiles (the host picks the instantiation).  No load
 // then needs the per-lane offsets of a tile that K ends inside, and the select between the
 // two sets of offsets, one vector instruction per load, is left out: a 16-cycle MFMA slot has
 // room for three other instructions.
 template <class C, bool MAY_TAIL>
-__global__ __launch_bounds__(C::NT) void gemm16_kernel(const GemmArgs p)
+__global__ __launch_bounds__(C::NT, C::WAVES_PER_EU) void gemm16_kernel(const GemmArgs p)
 {
 #if defined(__HIP_DEVICE_COMPILE__)   // the host pass only needs the kernel's symbol
     __shared__ __attribute__((aligned(1024))) char lds[C::LDS_BYTES];
@@ -338,10 +353,10 @@ __global__ __launch_bounds__(C::NT) void gemm16_kernel(const GemmArgs p)
     };
     constexpr int LA0 = LA / 2;                              // A's loads that go out in k-step 0
     constexpr int PENDING = LA0;                             // loads of the tile under way at its barrier
-    auto slot_read = [](int j) constexpr { return slot_read_of(j); };
-    auto slot_a0 = [](int j) constexpr { return slot_a0_of(j, LA0); };
-    auto slot_b1 = [](int j) constexpr { return slot_b1_of(j, LB); };
-    auto slot_a1 = [](int j) constexpr { return slot_a1_of(j, LA - LA0); };
+    auto slot_read = [](int j) constexpr { return slot_read_of(j, NM, NFR); };
+    auto slot_a0 = [](int j) constexpr { return slot_a0_of(j, LA0, NM, NFR); };
+    auto slot_b1 = [](int j) constexpr { return slot_b1_of(j, LB, NM, NFR, LA - LA0); };
+    auto slot_a1 = [](int j) constexpr { return slot_a1_of(j, LA - LA0, NM, NFR, LB); };
     next_offsets(0);
     static_for<LA>([&](auto pc) { issue_a(0, pc, IC<1>{}); });
     static_for<LB>([&](auto pc) { issue_b(0, pc, IC<1>{}); });

@@ -105,7 +105,10 @@ static double tiled_cost(const Variant &v, const peak_gemm_desc_t &d, int split)
     if (v.tr) eff *= v.dt == PEAK_DT_F32 ? 1.10 : 1.03;      // B staged directly: no register transposition, no masked loads
     if (v.lds > 140 * 1024 && v.ns == 2 && !v.tr) eff *= 1.02;   // third A stage, A's loads spread over the step (+2 % measured; nothing with [k][n] B)
     if (v.nt == 256 && v.bm == 256 && v.bn == 256 && v.lds > 140 * 1024) eff *= 1.02;   // one wave per SIMD on top of that
-    if (v.mf16) eff *= 1.10;                            // 16x16x32 MFMA: same cycles, higher clock (+10 % measured)
+    // 16x16x32 MFMA: same cycles, higher clock (256 x 256: +10 % measured; 128 x 128: 3-8 % ahead of the 32x32x16
+    // kernel of the same tile, and a fifth behind the 256 x 256 tile where both run full rounds: bf16 8192x4608x8192
+    // 542 us against 431)
+    if (v.mf16) eff *= v.bm == 256 ? 1.10 : 1.04;
     if (v.atr) eff *= 1.5;                              // likewise A; the alternative is the register-staged general tile
     if (v.dt == PEAK_DT_F32 && v.ns == 3) eff *= 0.97;
     const double fixed = 12.0e6;                    // prologue + epilogue of one tile, same units
@@ -140,7 +143,7 @@ static int choose_split(const Variant &v, const peak_gemm_desc_t &d)
 static int streamk_split(const Variant &v, const peak_gemm_desc_t &d, int *sk_tiles)
 {
     *sk_tiles = 0;
-    if (!v.mf16) return 0;                                   // built into the 16x16x32 kernels only
+    if (!v.mf16 || v.bm != 256 || v.bn != 256) return 0;     // built into the 256 x 256 16x16x32 kernels only
     const int64_t tiles = cdiv(d.M, v.bm) * cdiv(d.N, v.bn), P = num_cu();
     const int64_t rem = tiles % P, ktiles = cdiv(d.K, v.bk);
     if (tiles < P || rem == 0) return 0;
@@ -230,7 +233,18 @@ static int select_variant(const peak_gemm_desc_t &d, bool staged_only)
             if (stream[v.stream_rank] < 0) stream[v.stream_rank] = i;
             continue;
         }
-        const double c = tiled_cost(v, d, choose_split(v, d));
+        const int split = choose_split(v, d);
+        double c = tiled_cost(v, d, split);
+        if (split == 1) {
+            // a partial last round that hybrid stream-K will cut costs a slice and the reduction, not a whole tile
+            int sk_tiles = 0;
+            const int S = streamk_split(v, d, &sk_tiles);
+            if (S >= 2 && streamk_pays(v, d, S, sk_tiles)) {
+                const int64_t tiles = cdiv(d.M, v.bm) * cdiv(d.N, v.bn);
+                const double per_round = c / (double)cdiv(tiles, num_cu());
+                c -= per_round * (1.0 - 1.0 / S) * 0.8;              // four fifths of the saving that round counting predicts
+            }
+        }
         if (pick < 0 || c < best) { pick = i; best = c; }
     }
     // a streaming kernel wins whenever one applies

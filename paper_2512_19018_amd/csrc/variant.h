@@ -22,6 +22,7 @@ VariantGroup variants_f32();
 VariantGroup variants_ta();
 VariantGroup variants_skinny();
 VariantGroup variants_mf16();
+VariantGroup variants_mf16s();
 
 template <class C>
 static int launch_gemm(const GemmArgs &a, unsigned grid, void *stream)

@@ -350,7 +350,7 @@ def test_operand_base_off_16_bytes_with_aligned_rows(gu, oracle, dtype):
             A, B, C = _stored(3100 + M, dtype, M, N, K, transA, transB)
             with gu.pg.Plan(M, N, K, dtype, transA, transB, flags=gu.pg.force_flags(split=split)) as plan:
                 info = plan.info()
-                assert re.search(r"variant=\d+:\w+_(?:d|t)\d|skinny", info), info      # a variant with alignment needs
+                assert re.search(r"variant=\d+:\w+_(?:d|t|m)\d|skinny", info), info      # a variant with alignment needs
                 assert "unaligned=same" not in info, info
                 ws = torch.empty(max(plan.workspace_bytes, 256), dtype=torch.uint8, device="cuda")
                 for off_a, off_b in [(1, 0), (0, 1), (1, 1)]:
