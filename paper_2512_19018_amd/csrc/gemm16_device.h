@@ -24,10 +24,16 @@ namespace peak {
 
 typedef float f32x4v __attribute__((ext_vector_type(4)));
 
+constexpr int A_BYTES_OF(int tile) { return tile * 128; }    // one stage of one operand: tile rows x 64 k x 2 bytes
+
 // TILE: 256 (the large problems: one workgroup per CU, one wave per SIMD, 128x128 per wave) or
 // 128 (mid-size problems: 64x64 per wave, 80 KB of LDS and half the registers, so two workgroups
 // share a CU and cover each other's waits)
-template <int DT_, bool A_KM_ = false, bool B_KN_ = false, int TILE_ = 256>
+// PF: prefetch distance in K tiles (the loads of tile kt + PF go out during tile kt): PF + 1 stages of A,
+// PF of B.  2 for the large tile, whose K tile takes 2048 cycles of MFMAs; 4 for the small tile when a
+// workgroup has its CU to itself (512 cycles per K tile cover a fraction of a load's latency: measured 532
+// cycles of waiting per K tile at bf16 2048^3 with a distance of 2)
+template <int DT_, bool A_KM_ = false, bool B_KN_ = false, int TILE_ = 256, int PF_ = 2>
 struct Cfg16 {
     static_assert(DT_ == DT_F16 || DT_ == DT_BF16, "16-bit storage");
     static_assert(TILE_ == 256 || TILE_ == 128, "workgroup tile");
@@ -37,11 +43,13 @@ struct Cfg16 {
     static constexpr int ESZ = 2, EPC = 8;
     static constexpr int BM = TILE_, BN = TILE_, RB = 128, CPR = 8, BK = 64;
     static constexpr int WAVES_M = 2, WAVES_N = 2, NW = 4, NT = 256;
-    static constexpr int WAVES_PER_EU = 256 / TILE_;        // workgroups per CU the register budget is cut for
+    static constexpr int PF = PF_;
+    static constexpr int WAVES_PER_EU = PF_ == 2 ? 256 / TILE_ : 1;   // workgroups per CU the register budget is cut for
     static constexpr int WTM = BM / 2, WTN = BN / 2;
     static constexpr int MB = WTM / 16, NB = WTN / 16;      // 16x16 blocks per wave tile
     static constexpr int KS = BK / 32;                      // MFMA k-steps per K tile
-    static constexpr int NSA = 3, NSB = 2;
+    static constexpr int NSA = PF_ + 1, NSB = PF_;
+    static_assert(PF_ >= 2 && A_BYTES_OF(TILE_) * (PF_ + 1) + A_BYTES_OF(TILE_) * PF_ <= 160 * 1024, "stages fit the LDS");
     static constexpr int A_BYTES = BM * RB, B_BYTES = BN * RB;
     static constexpr int LDS_BYTES = A_BYTES * NSA + B_BYTES * NSB;
     // Chunk c of tile row r sits at chunk position c ^ swizzle(r).  The swizzle depends on
@@ -196,7 +204,8 @@ __global__ __launch_bounds__(C::NT, C::WAVES_PER_EU) void gemm16_kernel(const Ge
         if constexpr (C::A_KM) {
             // (the immediate holds 16 bits: the third stage goes through an address of its own)
             constexpr int off = (stage % 2) * C::A_BYTES + ks * 32 * (C::BM * C::ESZ);
-            const uint32_t a0 = lds_b0 + (stage < 2 ? a_kx[i] : a_kx2[i]);
+            constexpr int pair = stage / 2;                  // stages beyond the third: added at run time
+            const uint32_t a0 = lds_b0 + (pair == 0 ? a_kx[i] : pair == 1 ? a_kx2[i] : a_kx[i] + pair * 2 * C::A_BYTES);
             u32x2 &lo = al[set][i], &hi = ah[set][i];
             asm volatile("ds_read_b64_tr_b16 %0, %1 offset:%2" : "=v"(lo) : "v"(a0), "n"(off) : "memory");
             asm volatile("ds_read_b64_tr_b16 %0, %1 offset:%2" : "=v"(hi) : "v"(a0), "n"(off + 4 * C::BM * C::ESZ) : "memory");
@@ -352,11 +361,14 @@ __global__ __launch_bounds__(C::NT, C::WAVES_PER_EU) void gemm16_kernel(const Ge
             asm volatile("v_mfma_f32_16x16x32_f16 %0, %1, %2, %0" : "+a"(c) : "v"(b), "v"(a));
     };
     constexpr int LA0 = LA / 2;                              // A's loads that go out in k-step 0
-    constexpr int PENDING = LA0;                             // loads of the tile under way at its barrier
+    // loads that may still be under way at a tile's barrier: those of the tiles after the next one
+    constexpr int PENDING = (C::PF - 2) * (LA + LB) + LA0;
+    static_assert(PENDING < 64, "fits the wait's counter");
     auto slot_read = [](int j) constexpr { return slot_read_of(j, NM, NFR); };
     auto slot_a0 = [](int j) constexpr { return slot_a0_of(j, LA0, NM, NFR); };
     auto slot_b1 = [](int j) constexpr { return slot_b1_of(j, LB, NM, NFR, LA - LA0); };
     auto slot_a1 = [](int j) constexpr { return slot_a1_of(j, LA - LA0, NM, NFR, LB); };
+    constexpr int PF = C::PF;
     next_offsets(0);
     static_for<LA>([&](auto pc) { issue_a(0, pc, IC<1>{}); });
     static_for<LB>([&](auto pc) { issue_b(0, pc, IC<1>{}); });
@@ -365,12 +377,24 @@ __global__ __launch_bounds__(C::NT, C::WAVES_PER_EU) void gemm16_kernel(const Ge
         f32x4v &c = acc[j % C::MB][j / C::MB];
         asm volatile("" : "+a"(c));
     });
-    wait_vmcnt<0>();
-    lds_barrier();
-    next_offsets(1);
-    static_for<LB>([&](auto pc) { issue_b(1, pc, IC<1>{}); });
-    static_for<LA>([&](auto pc) { issue_a(1, pc, IC<1>{}); });
-    next_offsets(2);
+    if constexpr (PF == 2) {
+        wait_vmcnt<0>();
+        lds_barrier();
+        next_offsets(1);
+        static_for<LB>([&](auto pc) { issue_b(1, pc, IC<1>{}); });
+        static_for<LA>([&](auto pc) { issue_a(1, pc, IC<1>{}); });
+    } else {
+        // tiles 1 .. PF-1 right behind tile 0; only tile 0 has to have landed
+        static_for<PF - 1>([&](auto tc) {
+            constexpr int t = decltype(tc)::value + 1;
+            next_offsets(t);
+            static_for<LB>([&](auto pc) { issue_b(t, pc, IC<1>{}); });
+            static_for<LA>([&](auto pc) { issue_a(t, pc, IC<1>{}); });
+        });
+        wait_vmcnt<(PF - 1) * (LA + LB)>();
+        lds_barrier();
+    }
+    next_offsets(PF);
     asm volatile("s_nop 7\n\ts_nop 7" ::: "memory");
     static_for<NFR>([&](auto fc) { fetch_one(IC<0>{}, IC<0>{}, IC<0>{}, fc); });
 #ifdef PEAK_TRACE
@@ -378,11 +402,12 @@ __global__ __launch_bounds__(C::NT, C::WAVES_PER_EU) void gemm16_kernel(const Ge
 #endif
     {
         constexpr auto may_tail = IC<MAY_TAIL ? 1 : 0>{};
-        constexpr int U = 6;                                 // tiles per trip: both stage indices static
+        constexpr int U = C::NSA * C::NSB;                   // tiles per trip: both stage indices static (NSA and NSB differ by one)
         for (int kt0 = 0; kt0 < KT; kt0 += U) {
             static_for<U>([&](auto uc) {
                 constexpr int u = decltype(uc)::value;
-                constexpr int s = u % 2, sa = u % 3, sa1 = (sa + 1) % 3, sa2 = (sa + 2) % 3;
+                // stages of tile kt (B: s, A: sa), of tile kt+1 (s1, sa1) and of the tile whose loads go out now (B: s again, A: sa2)
+                constexpr int s = u % C::NSB, s1 = (u + 1) % C::NSB, sa = u % C::NSA, sa1 = (sa + 1) % C::NSA, sa2 = (sa + C::PF) % C::NSA;
                 const int kt = kt0 + u;
                 if (kt < KT) {
                     // k-step 0
@@ -419,10 +444,10 @@ __global__ __launch_bounds__(C::NT, C::WAVES_PER_EU) void gemm16_kernel(const Ge
                         if constexpr (slot_b1(j) >= 0) m0_b(s, IC<(slot_b1(j) >= 0 ? slot_b1(j) : 0)>{});
                         if constexpr (slot_a1(j) >= 0) m0_a(sa2, IC<(LA0 + (slot_a1(j) >= 0 ? slot_a1(j) : 0)) % LA>{});
                         mfma_one(IC<1>{}, jc);
-                        if constexpr (slot_read(j) >= 0) fetch_one(IC<sa1>{}, IC<1 - s>{}, IC<0>{}, IC<(slot_read(j) >= 0 ? slot_read(j) : 0)>{});
+                        if constexpr (slot_read(j) >= 0) fetch_one(IC<sa1>{}, IC<s1>{}, IC<0>{}, IC<(slot_read(j) >= 0 ? slot_read(j) : 0)>{});
                         if constexpr (slot_b1(j) >= 0) ld_b(IC<(slot_b1(j) >= 0 ? slot_b1(j) : 0)>{}, may_tail);
                         if constexpr (slot_a1(j) >= 0) ld_a(IC<(LA0 + (slot_a1(j) >= 0 ? slot_a1(j) : 0)) % LA>{}, may_tail);
-                        if constexpr (j == NM - 2) next_offsets(kt + 3);   // for the loads the next tile issues
+                        if constexpr (j == NM - 2) next_offsets(kt + 1 + C::PF);   // for the loads the next tile issues
                         __builtin_amdgcn_sched_barrier(0);
                     });
                 }

@@ -109,6 +109,9 @@ static double tiled_cost(const Variant &v, const peak_gemm_desc_t &d, int split)
     // kernel of the same tile, and a fifth behind the 256 x 256 tile where both run full rounds: bf16 8192x4608x8192
     // 542 us against 431)
     if (v.mf16) eff *= v.bm == 256 ? 1.10 : 1.04;
+    // ... with loads four K tiles ahead and the CU to itself: for at most one workgroup per CU, where it
+    // stands in for the second workgroup that would cover the loads' latency
+    if (v.mf16 && v.bm == 128 && v.ns > 2) eff *= tiles <= num_cu() ? 1.3 : 0.85;
     if (v.atr) eff *= 1.5;                              // likewise A; the alternative is the register-staged general tile
     if (v.dt == PEAK_DT_F32 && v.ns == 3) eff *= 0.97;
     const double fixed = 12.0e6;                    // prologue + epilogue of one tile, same units

@@ -15,9 +15,11 @@ static int launch_gemm16(const GemmArgs &a, unsigned grid, void *stream)
     return hipGetLastError() == hipSuccess ? 0 : 1;
 }
 
-// AKM: A stored K x M, staged as [k][m] rows; BKN: B stored K x N, staged as [k][n] rows; TILE: 256 or 128
-#define TILED_MF16(NAME, DT, AKM, BKN, TILE)                                                           \
-    {NAME, KIND_TILED, DT, AKM, BKN, 1, TILE, TILE, 64, 256, 2,                                        \
-     Cfg16<DT, AKM != 0, BKN != 0, TILE>::LDS_BYTES, 0, &launch_gemm16<Cfg16<DT, AKM != 0, BKN != 0, TILE>>, BKN, AKM, 0, 0, 1}
+// AKM: A stored K x M, staged as [k][m] rows; BKN: B stored K x N, staged as [k][n] rows; TILE: 256 or 128;
+// PF: prefetch distance in K tiles (PF + 1 stages of A, PF of B)
+#define TILED_MF16(NAME, DT, AKM, BKN, TILE, PF)                                                       \
+    {NAME, KIND_TILED, DT, AKM, BKN, 1, TILE, TILE, 64, 256, PF,                                       \
+     Cfg16<DT, AKM != 0, BKN != 0, TILE, PF>::LDS_BYTES, 0, &launch_gemm16<Cfg16<DT, AKM != 0, BKN != 0, TILE, PF>>,    \
+     BKN, AKM, 0, 0, 1}
 
 }  // namespace peak
