@@ -2,15 +2,16 @@
 // 16-bit operands in any of the four layouts: 256x256 workgroup tile, four
 // waves (one per SIMD) with a 128x128 wave tile each, i.e. 8 x 8 blocks of 16x16
 // whose 256 accumulator registers sit in the accumulation half of the register
-// file.  Measured on MI355X, the chip is power limited under a matrix load and
+// file; or, for mid-size problems, a 128x128 tile with 64x64 per wave, two
+// workgroups to a CU or one that loads four K tiles ahead.  Measured on MI355X, the chip is power limited under a matrix load and
 // this instruction does the same multiply-adds for less power than 32x32x16: an
 // MFMA-only loop sustains about 14 % more with it, and a GEMM built on it holds a
 // correspondingly higher clock at the same number of cycles.
 //
 // In the paper's vocabulary (Section 2.2, Section 4.1 Table 2) this is the
 // Tensor-Core / Tensor-Tiling step taken with another tile of the matrix unit;
-// staging (Pipelining: three A stages and two B stages of 64 k, filled by
-// direct-to-LDS buffer loads), the XOR placement of 16-byte chunks (Offset), the
+// staging (Pipelining: PF + 1 stages of A and PF of B, 64 k each, filled by
+// direct-to-LDS buffer loads PF K tiles ahead), the XOR placement of 16-byte chunks (Offset), the
 // tile order (Block-Swizzle), Split-K slices and the epilogue are those of
 // gemm_kernel.  An operand that does not run along K in memory (A stored K x M,
 // B stored K x N) is staged as it lies, [k][m] or [k][n] rows, and its fragments
@@ -33,23 +34,25 @@ constexpr int A_BYTES_OF(int tile) { return tile * 128; }    // one stage of one
 // PF of B.  2 for the large tile, whose K tile takes 2048 cycles of MFMAs; 4 for the small tile when a
 // workgroup has its CU to itself (512 cycles per K tile cover a fraction of a load's latency: measured 532
 // cycles of waiting per K tile at bf16 2048^3 with a distance of 2)
-template <int DT_, bool A_KM_ = false, bool B_KN_ = false, int TILE_ = 256, int PF_ = 2>
+// TILE_N: columns of the tile when it is not square (256 x 128: problems that fill the chip with neither
+// the 256 x 256 nor the 128 x 128 tile, and whose wave tile of 128 x 64 still spares the LDS)
+template <int DT_, bool A_KM_ = false, bool B_KN_ = false, int TILE_ = 256, int PF_ = 2, int TILE_N_ = TILE_>
 struct Cfg16 {
     static_assert(DT_ == DT_F16 || DT_ == DT_BF16, "16-bit storage");
-    static_assert(TILE_ == 256 || TILE_ == 128, "workgroup tile");
+    static_assert((TILE_ == 256 || TILE_ == 128) && (TILE_N_ == 256 || TILE_N_ == 128), "workgroup tile");
     static constexpr int DT = DT_;
     static constexpr bool A_KM = A_KM_;                      // A stored K x M: staged as [k][m] rows
     static constexpr bool B_KN = B_KN_;                      // B stored K x N: staged as [k][n] rows
     static constexpr int ESZ = 2, EPC = 8;
-    static constexpr int BM = TILE_, BN = TILE_, RB = 128, CPR = 8, BK = 64;
+    static constexpr int BM = TILE_, BN = TILE_N_, RB = 128, CPR = 8, BK = 64;
     static constexpr int WAVES_M = 2, WAVES_N = 2, NW = 4, NT = 256;
     static constexpr int PF = PF_;
-    static constexpr int WAVES_PER_EU = PF_ == 2 ? 256 / TILE_ : 1;   // workgroups per CU the register budget is cut for
+    static constexpr int WAVES_PER_EU = PF_ == 2 && TILE_ == 128 && TILE_N_ == 128 ? 2 : 1;   // workgroups per CU the register budget is cut for
     static constexpr int WTM = BM / 2, WTN = BN / 2;
     static constexpr int MB = WTM / 16, NB = WTN / 16;      // 16x16 blocks per wave tile
     static constexpr int KS = BK / 32;                      // MFMA k-steps per K tile
     static constexpr int NSA = PF_ + 1, NSB = PF_;
-    static_assert(PF_ >= 2 && A_BYTES_OF(TILE_) * (PF_ + 1) + A_BYTES_OF(TILE_) * PF_ <= 160 * 1024, "stages fit the LDS");
+    static_assert(PF_ >= 2 && A_BYTES_OF(TILE_) * (PF_ + 1) + A_BYTES_OF(TILE_N_) * PF_ <= 160 * 1024, "stages fit the LDS");
     static constexpr int A_BYTES = BM * RB, B_BYTES = BN * RB;
     static constexpr int LDS_BYTES = A_BYTES * NSA + B_BYTES * NSB;
     // Chunk c of tile row r sits at chunk position c ^ swizzle(r).  The swizzle depends on
@@ -96,6 +99,29 @@ constexpr int slot_a1_of(int j, int n, int nm, int nfr, int nb1)
 {
     return nm >= 4 * nfr ? slot_pick(j % 8 == 3 && j / 8 >= 4, j / 8 - 4, n) : slot_pick(true, slot_late(j, nm, nfr, n + nb1) - nb1, n);
 }
+
+// every fragment and every load of a K tile has exactly one slot, no slot holds a read and a load, and the
+// loads of k-step 1 come before the slot that works out the next tile's offsets (nm - 2)
+constexpr bool slot_plan_ok(int nm, int nfr, int la, int lb)
+{
+    const int la0 = la / 2, la1 = la - la0;
+    int reads = 0, a0 = 0, b1 = 0, a1 = 0;
+    for (int j = 0; j < nm; ++j) {
+        const int r = slot_read_of(j, nm, nfr), x = slot_a0_of(j, la0, nm, nfr);
+        const int y = slot_b1_of(j, lb, nm, nfr, la1), z = slot_a1_of(j, la1, nm, nfr, lb);
+        if (r >= 0 && (x >= 0 || y >= 0 || z >= 0)) return false;
+        if (y >= 0 && z >= 0) return false;
+        if ((y >= 0 || z >= 0) && j >= nm - 2) return false;
+        if (r >= 0) { if (r != reads) return false; ++reads; }
+        if (x >= 0) { if (x != a0) return false; ++a0; }
+        if (y >= 0) { if (y != b1) return false; ++b1; }
+        if (z >= 0) { if (z != a1) return false; ++a1; }
+    }
+    return reads == nfr && a0 == la0 && b1 == lb && a1 == la1;
+}
+static_assert(slot_plan_ok(64, 16, 8, 8), "slot plan of the 256 x 256 tile");
+static_assert(slot_plan_ok(16, 8, 4, 4), "slot plan of the 128 x 128 tile");
+static_assert(slot_plan_ok(32, 12, 8, 4), "slot plan of the 256 x 128 tile");
 
 // MAY_TAIL false: K is a whole number of K tiles (the host picks the instantiation).  No load
 // then needs the per-lane offsets of a tile that K ends inside, and the select between the
@@ -342,7 +368,7 @@ __global__ __launch_bounds__(C::NT, C::WAVES_PER_EU) void gemm16_kernel(const Ge
     //                         tile kt+2 into the stage tile kt has just left, rest of A's loads
     constexpr int NM = C::MB * C::NB;                        // MFMAs per k-step
     constexpr int NFR = C::MB + C::NB;                       // fragments per k-step
-    static_assert(C::KS == 2 && LA % 2 == 0 && 2 * NFR <= NM, "slot plan below");
+    static_assert(C::KS == 2 && LA % 2 == 0 && 2 * NFR <= NM && slot_plan_ok(NM, NFR, LA, LB), "slot plan below");
     // fragment f of a k-step in the order the MFMAs first need them: B0, A0 .. A7, B1 .. B7
     auto fetch_one = [&](auto sac, auto sbc, auto ksc, auto fc) {
         constexpr int f = decltype(fc)::value;

@@ -108,7 +108,7 @@ static double tiled_cost(const Variant &v, const peak_gemm_desc_t &d, int split)
     // 16x16x32 MFMA: same cycles, higher clock (256 x 256: +10 % measured; 128 x 128: 3-8 % ahead of the 32x32x16
     // kernel of the same tile, and a fifth behind the 256 x 256 tile where both run full rounds: bf16 8192x4608x8192
     // 542 us against 431)
-    if (v.mf16) eff *= v.bm == 256 ? 1.10 : 1.04;
+    if (v.mf16) eff *= v.bm * v.bn == 256 * 256 ? 1.10 : v.bm * v.bn == 256 * 128 ? 1.08 : 1.04;
     // ... with loads four K tiles ahead and the CU to itself: for at most one workgroup per CU, where it
     // stands in for the second workgroup that would cover the loads' latency
     if (v.mf16 && v.bm == 128 && v.ns > 2) eff *= tiles <= num_cu() ? 1.3 : 0.85;

@@ -23,6 +23,7 @@ VariantGroup variants_ta();
 VariantGroup variants_skinny();
 VariantGroup variants_mf16();
 VariantGroup variants_mf16s();
+VariantGroup variants_mf16r();
 
 template <class C>
 static int launch_gemm(const GemmArgs &a, unsigned grid, void *stream)

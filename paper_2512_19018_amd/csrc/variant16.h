@@ -22,4 +22,10 @@ static int launch_gemm16(const GemmArgs &a, unsigned grid, void *stream)
      Cfg16<DT, AKM != 0, BKN != 0, TILE, PF>::LDS_BYTES, 0, &launch_gemm16<Cfg16<DT, AKM != 0, BKN != 0, TILE, PF>>,    \
      BKN, AKM, 0, 0, 1}
 
+// ... with a tile of TM x TN
+#define TILED_MF16_MN(NAME, DT, AKM, BKN, TM, TN, PF)                                                  \
+    {NAME, KIND_TILED, DT, AKM, BKN, 1, TM, TN, 64, 256, PF,                                           \
+     Cfg16<DT, AKM != 0, BKN != 0, TM, PF, TN>::LDS_BYTES, 0,                                          \
+     &launch_gemm16<Cfg16<DT, AKM != 0, BKN != 0, TM, PF, TN>>, BKN, AKM, 0, 0, 1}
+
 }  // namespace peak
