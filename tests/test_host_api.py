@@ -210,6 +210,13 @@ def test_tuner_enumerates_only_accepted_settings():
     assert not any(n.startswith(("f16_", "f32_")) or n.endswith(("_nn", "_tt", "_tn")) for n in names)
     assert not any("skinny" in n for n in names)                   # M > 16
     assert len({(c[0], c[2]) for c in cands}) == len(cands)        # each (variant, effective split) once
+    # the library's own choice wins ties within the margin, a clearly faster setting does not lose to it
+    res = [(10.0, "a", 1), (10.1, "b", 2), (12.0, "c", 1)]
+    assert tune.pick(res, ("b", 2), 0.015) == (10.1, "b", 2)
+    assert tune.pick(res, ("c", 1), 0.015) == (10.0, "a", 1)
+    assert tune.pick(res, ("zz", 1), 0.015) == (10.0, "a", 1)
+    own = tune.own_choice(pg.PEAK_DT_BF16, 0, 1, 8192, 8192, 8192)
+    assert own == ("bf16_m256x256w4a3_nt", 1)
     line = tune.table_line(pg.PEAK_DT_BF16, 0, 1, 256, 512, 1024, "bf16_d256x256w8_nt", 4, 12.5)
     assert line.split()[:8] == ["bf16", "0", "1", "256", "512", "1024", "bf16_d256x256w8_nt", "4"]
 
