@@ -194,6 +194,24 @@ def main():
         torch.cuda.empty_cache()
         return read_stream["gbs"]
 
+    lds_path = {}
+
+    def lds_load_rate():
+        """Bytes per cycle one compute unit's path from the L2 into LDS delivers (direct-to-LDS loads and
+        nothing else, include/peak_calib.h): the second ceiling of a tiled kernel, next to the MFMA rate."""
+        cus = torch.cuda.get_device_properties(0).multi_processor_count
+        src = torch.empty(cus * 64 * 1024, dtype=torch.uint8, device="cuda")
+        src.random_(0, 255)
+        out = torch.zeros(2 * cus, dtype=torch.int64, device="cuda")
+        for rep in range(2):                                 # the second launch finds its pieces in the L2
+            st, nbytes, wgs = pg.peak_calib_lds_load(src.data_ptr(), src.numel(), 2000, out.data_ptr(), stream.cuda_stream)
+            if st != pg.PEAK_OK:
+                raise SystemExit("bench.py: peak_calib_lds_load: " + pg.peak_status_string(st))
+            stream.synchronize()
+        c = out.cpu().numpy().reshape(-1, 2)
+        lds_path["bytes_per_cycle_per_cu"] = float(nbytes / c[:wgs, 0].mean())
+        return lds_path["bytes_per_cycle_per_cu"]
+
     def cpu_leg(w, host, seconds, threads=None, label=None):
         """The oracle as it stands on a bounded sample of rows of C (all columns, full K)."""
         from oracle import gemm_oracle
@@ -257,7 +275,9 @@ def main():
                 if "gbs" not in read_stream:
                     hbm_read_sustained()
             else:
-                mfma_sustained(w.dtype)
+                if not lds_path:
+                    lds_load_rate()
+                mfma_sustained(w.dtype)                      # last: it leaves the chip in the state of a matrix load
         with pg.Plan(w.M, w.N, w.K, w.dtype, w.transA, w.transB, lda, ldb, ldc, flags) as plan:
             res["plan"] = plan.info()
             ws = torch.empty(max(plan.workspace_bytes, 256), dtype=torch.uint8, device="cuda")
@@ -324,6 +344,18 @@ def main():
                 res["roofline"]["mfma_only_clock_ghz"] = sus["clock_ghz"]
                 res["roofline"]["peak_at_measured_clock"] = pk * sus["clock_ghz"] / 2.4
                 res["roofline"]["frac_measured_clock"] = res["tflops_events"] / (pk * sus["clock_ghz"] / 2.4)
+            if lds_path:
+                # what the tile of the plan asks of the L2 -> LDS path at the full MFMA rate, against what the
+                # path delivers: bytes of A and B per K tile over the cycles its MFMAs take on four SIMDs
+                import re
+                m = re.search(r"tile=(\d+)x(\d+)x(\d+)", res["plan"])
+                if m:
+                    bm, bn, bk = (int(x) for x in m.groups())
+                    es = pi.DTYPE_SIZE[w.dtype]
+                    flops_per_cycle_cu = pk * 1e12 / (2.4e9 * 256)
+                    need = (bm + bn) * bk * es / (2.0 * bm * bn * bk / flops_per_cycle_cu)
+                    res["roofline"]["l2_to_lds_bytes_per_cycle_per_cu"] = lds_path["bytes_per_cycle_per_cu"]
+                    res["roofline"]["tile_needs_bytes_per_cycle_per_cu"] = need
         if with_torch:
             try:
                 tdt = {pi.F32: torch.float32, pi.F16: torch.float16, pi.BF16: torch.bfloat16}[w.dtype]

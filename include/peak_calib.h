@@ -5,7 +5,7 @@
  * the devices' documented peaks and Section 6 (Table 1) reports the fraction of
  * the vendor library reached.  A data-sheet peak assumes the data-sheet clock;
  * under a matrix-core load with random operands the chip is power limited and
- * runs slower.  These two calls measure, in the caller's process and clock
+ * runs slower.  These calls measure, in the caller's process and clock
  * state, what the device sustains when nothing but the matrix cores (or nothing
  * but memory reads) is busy, so that a GEMM time can be quoted against both
  * the published peak and the rate the box can actually issue.  They are used by
@@ -57,6 +57,28 @@ peak_status_t peak_calib_mfma(int32_t dtype, int32_t random_operands, int32_t it
  *            it keeps the loads alive)
  */
 peak_status_t peak_calib_read(const void *src_dev, size_t bytes, void *out_dev, void *hip_stream);
+
+/*
+ * Direct-to-LDS loads only: one workgroup of 4 waves per compute unit, each wave
+ * issuing `iters` x 8 loads of 1 KB (buffer_load_dwordx4 ... lds, the staging
+ * path of the tiled kernels) from the workgroup's own 64 KB piece of
+ * [src_dev, src_dev + bytes), which is served by the L2 after the first pass.
+ * bytes_per_workgroup / cycles is what one compute unit's path from the L2
+ * into LDS delivers; a 256 x 256 x 64 tile of 16-bit operands needs 64 KB per
+ * 2048 cycles of MFMAs, i.e. 32 bytes per cycle of it.
+ *
+ *   src_dev              16-byte aligned, bytes >= 64 KB x compute units of the device
+ *   out_dev              8-byte aligned, 16 bytes per compute unit, written by the kernel:
+ *                        out[2 b] = shader-clock cycles workgroup b took,
+ *                        out[2 b + 1] = ticks of the constant 100 MHz counter
+ *   bytes_per_workgroup  HOST pointer, may be NULL: bytes one workgroup loads per launch
+ *   workgroups           HOST pointer, may be NULL: workgroups launched (compute units)
+ *
+ * PEAK_ERR_INVALID_ARG: NULL or misaligned pointers, iters outside 1..2^20, too
+ * few bytes.  PEAK_ERR_HIP: no device, or the launch failed.
+ */
+peak_status_t peak_calib_lds_load(const void *src_dev, size_t bytes, int32_t iters, void *out_dev, void *hip_stream,
+                                  double *bytes_per_workgroup, int32_t *workgroups);
 
 #ifdef __cplusplus
 }

@@ -13,5 +13,5 @@ from .binding import (  # noqa: F401
     peak_gemm_create, peak_gemm_workspace_bytes, peak_gemm_run, peak_gemm_run_fused, peak_gemm_run_static,
     PEAK_GEMM_STATIC_WORKSPACE_BYTES, peak_gemm_destroy,
     peak_status_string, peak_gemm_plan_info, peak_gemm_variant_count, peak_gemm_variant_name,
-    peak_gemm_load_tuning, peak_calib_mfma, peak_calib_read, force_flags, Plan,
+    peak_gemm_load_tuning, peak_calib_mfma, peak_calib_read, peak_calib_lds_load, force_flags, Plan,
 )

@@ -81,6 +81,9 @@ def load_library():
         lib.peak_calib_mfma.argtypes = [ctypes.c_int32, ctypes.c_int32, ctypes.c_int32, P, P, ctypes.POINTER(ctypes.c_double)]
         lib.peak_calib_read.restype = ctypes.c_int
         lib.peak_calib_read.argtypes = [P, ctypes.c_size_t, P, P]
+        lib.peak_calib_lds_load.restype = ctypes.c_int
+        lib.peak_calib_lds_load.argtypes = [P, ctypes.c_size_t, ctypes.c_int32, P, P, ctypes.POINTER(ctypes.c_double),
+                                            ctypes.POINTER(ctypes.c_int32)]
         _LIB = lib
     return _LIB
 
@@ -158,6 +161,14 @@ def peak_calib_mfma(dtype: int, random_operands: bool, iters: int, out_dev: int,
     st = load_library().peak_calib_mfma(int(dtype), 1 if random_operands else 0, int(iters), out_dev or None,
                                         stream or None, ctypes.byref(flops))
     return st, flops.value
+
+
+def peak_calib_lds_load(src_dev: int, nbytes: int, iters: int, out_dev: int, stream: int = 0):
+    """include/peak_calib.h: enqueues the direct-to-LDS load loop; returns (status, bytes per workgroup, workgroups)."""
+    b, n = ctypes.c_double(0.0), ctypes.c_int32(0)
+    st = load_library().peak_calib_lds_load(src_dev or None, int(nbytes), int(iters), out_dev or None, stream or None,
+                                            ctypes.byref(b), ctypes.byref(n))
+    return st, b.value, n.value
 
 
 def peak_calib_read(src_dev: int, nbytes: int, out_dev: int, stream: int = 0) -> int:

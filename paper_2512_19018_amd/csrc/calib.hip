@@ -1,6 +1,7 @@
 // Measurement support for the bench: what the device sustains with nothing but
-// the matrix cores busy, and with nothing but reads from memory, measured in the
-// same process and clock state as the GEMM runs they are compared with.
+// the matrix cores busy, with nothing but reads from memory, and with nothing but
+// direct-to-LDS loads from the L2, measured in the same process and clock state
+// as the GEMM runs they are compared with.
 #include "../../include/peak_calib.h"
 
 #include <hip/hip_runtime.h>
@@ -114,6 +115,37 @@ __global__ __launch_bounds__(256) void read_only_kernel(const u32x4 *src, uint64
     if ((x[0] ^ x[1] ^ x[2] ^ x[3]) == 0x9E3779B9u && x[0] == 0x12345678u) out[3] = x[1];   // practically never taken
 }
 
+// Direct-to-LDS loads and nothing else: each wave of a 4-wave workgroup (one workgroup per compute unit) issues
+// `iters` x 8 loads of 1 KB (16 bytes per lane) from its workgroup's own 64 KB piece of the source, which stays
+// in the L2 after the first pass, into a ring in LDS.  out[2 b], out[2 b + 1] = shader-clock cycles workgroup b
+// took, and the constant 100 MHz counter's ticks.
+constexpr int LDSLOAD_REGION = 64 * 1024;
+__global__ __launch_bounds__(256) void lds_load_kernel(const char *src, uint64_t *out, int iters)
+{
+    __shared__ __attribute__((aligned(1024))) char ring[128 * 1024];
+    const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const char *base = src + (size_t)blockIdx.x * LDSLOAD_REGION;
+    __amdgpu_buffer_rsrc_t r = __builtin_amdgcn_make_buffer_rsrc((void *)base, 0, LDSLOAD_REGION, 0x00020000);
+    const long long c0 = clock64(), w0 = wall_clock64();
+    for (int it = 0; it < iters; ++it) {
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+            const int chunk = ((it * 8 + i) * 4 + wave) & 0xFFFF;          // 1 KB piece
+            const int off = (chunk * 1024) % LDSLOAD_REGION + lane * 16;     // inside the descriptor's 64 KB
+            __builtin_amdgcn_raw_ptr_buffer_load_lds(r, (__attribute__((address_space(3))) void *)(ring + (chunk % 128) * 1024), 16, off, 0, 0, 0);
+        }
+        if ((it & 3) == 3) asm volatile("s_waitcnt vmcnt(16)" ::: "memory");
+    }
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    const long long c1 = clock64(), w1 = wall_clock64();
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        out[2 * blockIdx.x] = (uint64_t)(c1 - c0);
+        out[2 * blockIdx.x + 1] = (uint64_t)(w1 - w0);
+    }
+    if (ring[threadIdx.x] == 0x5A && ring[threadIdx.x + 256] == 0x3C && iters < 0) out[0] = 0;   // keeps the ring alive; never taken
+}
+
 }  // namespace
 
 extern "C" {
@@ -151,6 +183,23 @@ peak_status_t peak_calib_read(const void *src_dev, size_t bytes, void *out_dev, 
     hipLaunchKernelGGL(read_only_kernel, dim3((unsigned)cus * 16), dim3(256), 0, (hipStream_t)hip_stream,
                        (const u32x4 *)src_dev, (uint64_t)(bytes / 16), (uint64_t *)out_dev);
     return hipGetLastError() == hipSuccess ? PEAK_OK : PEAK_ERR_HIP;
+}
+
+peak_status_t peak_calib_lds_load(const void *src_dev, size_t bytes, int32_t iters, void *out_dev, void *hip_stream,
+                                  double *bytes_per_workgroup, int32_t *workgroups)
+{
+    if (!src_dev || !out_dev || (uintptr_t)src_dev % 16 || (uintptr_t)out_dev % 8 || iters < 1 || iters > (1 << 20)) return PEAK_ERR_INVALID_ARG;
+    int dev = 0, cus = 0;
+    if (hipGetDevice(&dev) != hipSuccess ||
+        hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus < 1)
+        return PEAK_ERR_HIP;
+    if (bytes < (size_t)cus * LDSLOAD_REGION) return PEAK_ERR_INVALID_ARG;
+    hipLaunchKernelGGL(lds_load_kernel, dim3((unsigned)cus), dim3(256), 0, (hipStream_t)hip_stream,
+                       (const char *)src_dev, (uint64_t *)out_dev, iters);
+    if (hipGetLastError() != hipSuccess) return PEAK_ERR_HIP;
+    if (bytes_per_workgroup) *bytes_per_workgroup = (double)iters * 8.0 * 4.0 * 1024.0;
+    if (workgroups) *workgroups = cus;
+    return PEAK_OK;
 }
 
 }  // extern "C"

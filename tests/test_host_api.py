@@ -27,7 +27,7 @@ def test_every_declared_symbol_is_exported():
     header = "\n".join(open(h).read() for h in headers)
     header = re.sub(r"/\*.*?\*/", "", header, flags=re.S)
     names = set(re.findall(r"\b(peak_[a-z_]+)\s*\(", header))
-    assert {"peak_calib_mfma", "peak_calib_read"} <= names
+    assert {"peak_calib_mfma", "peak_calib_read", "peak_calib_lds_load"} <= names
     assert {"peak_gemm_create", "peak_gemm_run", "peak_gemm_destroy", "peak_gemm_workspace_bytes",
             "peak_status_string", "peak_gemm_plan_info"} <= names
     lib = pg.load_library()
@@ -350,6 +350,9 @@ def test_calibration_calls_check_their_arguments():
     assert pg.peak_calib_read(0, 1 << 20, 0x1000) == pg.PEAK_ERR_INVALID_ARG
     assert pg.peak_calib_read(0x1008, 1 << 20, 0x1000) == pg.PEAK_ERR_INVALID_ARG
     assert pg.peak_calib_read(0x1000, 8, 0x1000) == pg.PEAK_ERR_INVALID_ARG
+    assert pg.peak_calib_lds_load(0, 1 << 30, 10, 0x1000)[0] == pg.PEAK_ERR_INVALID_ARG
+    assert pg.peak_calib_lds_load(0x1000, 1 << 30, 0, 0x1000)[0] == pg.PEAK_ERR_INVALID_ARG
+    assert pg.peak_calib_lds_load(0x1000, 1 << 30, 10, 0x1004)[0] == pg.PEAK_ERR_INVALID_ARG
 
 
 def test_hybrid_stream_k_plans():
