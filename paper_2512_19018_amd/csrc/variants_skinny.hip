@@ -88,6 +88,8 @@ static const Variant rows_skinny[] = {
     SKINNY_M("bf16_skinny_m64n128k128s3_nt", DT_BF16, 128, 128, 3, 4, 3),
     SKINNY_M("f16_skinny_m64n128k128s3_nt", DT_F16, 128, 128, 3, 4, 3),
     SKINNY_M("f32_skinny_m64n64k64s3_nt", DT_F32, 64, 64, 3, 4, 2),
+    // (more blocks, M up to 128 or 256, measured no better than the tiled kernels: the M x K operand, re-read by
+    // every workgroup from the L2, then outweighs B: bf16 128x28672x8192 111 us against 114, 256x... behind)
     // B stored K x N: 512 bytes of every k-row per workgroup, 128 bytes of K per stage
     SKINNY_KN("bf16_skinny_m16n256k64s4_nn", DT_BF16, 4, 1, 2),
     SKINNY_KN("f16_skinny_m16n256k64s4_nn", DT_F16, 4, 1, 2),
