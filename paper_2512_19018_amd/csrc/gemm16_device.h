@@ -52,7 +52,7 @@ struct Cfg16 {
     static constexpr int MB = WTM / 16, NB = WTN / 16;      // 16x16 blocks per wave tile
     static constexpr int KS = BK / 32;                      // MFMA k-steps per K tile
     static constexpr int NSA = PF_ + 1, NSB = PF_;
-    static_assert(PF_ >= 2 && A_BYTES_OF(TILE_) * (PF_ + 1) + A_BYTES_OF(TILE_N_) * PF_ <= 160 * 1024, "stages fit the LDS");
+    static_assert(PF_ >= 2 && A_BYTES_OF(TILE_) * NSA + A_BYTES_OF(TILE_N_) * NSB <= 160 * 1024, "stages fit the LDS");
     static constexpr int A_BYTES = BM * RB, B_BYTES = BN * RB;
     static constexpr int LDS_BYTES = A_BYTES * NSA + B_BYTES * NSB;
     // Chunk c of tile row r sits at chunk position c ^ swizzle(r).  The swizzle depends on
@@ -301,8 +301,13 @@ __global__ __launch_bounds__(C::NT, C::WAVES_PER_EU) void gemm16_kernel(const Ge
     // again into a free stage, so the count in flight stays what the waits assume.
     int soa = 0, sob = 0;
     bool tl = false;
+    // K rotation: this workgroup walks its K tiles starting at tile `rot` and wraps round (only the order
+    // of the sum over k changes).  Off (0) unless the plan asks for it: where every tile streams rows of its
+    // own from HBM, workgroups that all read the same k range at once load few memory channels at a time.
+    const int rot = __builtin_amdgcn_readfirstlane((int)(((int64_t)tn * p.rot_n + (int64_t)tm * p.rot_m) % KT));
     auto next_offsets = [&](int kt) {
-        const int kr = kt < KT ? kt : KT - 1;
+        int kr = (kt < KT ? kt : KT - 1) + rot;
+        if (kr >= KT) kr -= KT;
         soa = C::A_KM ? nA.soffset_of(kr) : dA.soffset_of(kr);
         sob = C::B_KN ? nB.soffset_of(kr) : dB.soffset_of(kr);
         tl = kr == tail_tile;

@@ -319,6 +319,9 @@ def test_exact_integers_deep_k_every_direct_variant(gu, oracle, dtype):
                 shapes = [(304, 520, 1024), (264, 264, 2056 if transB else 2051)]
             else:
                 shapes = [(300, 520, 1024), (260, 264, 2056)]
+            if "skinny" not in name:
+                # one row of tiles, several columns: the plans that start each workgroup at another K tile
+                shapes.append((104, 520, 2056 if transB or not transA else 2051))
             for case, (M, N, K) in enumerate(shapes):
                 A, B, C = _stored(7000 + vid * 4 + case, dtype, M, N, K, transA, transB, ints=True, amp=1)
                 ref = oracle.gemm(dtype, transA, transB, M, N, K, 1.0, A, B, 1.0, C)
