@@ -112,6 +112,10 @@ def main():
                          "much of the time is the chip's power limit)")
     ap.add_argument("--no-calibration", action="store_true",
                     help="skip the MFMA-only / read-only calibration legs (profiling runs that want the GEMM kernels only)")
+    ap.add_argument("--alternate-library", type=float, default=None, metavar="SECONDS",
+                    help="instead of the bench: blocks of SECONDS of this library, of torch.matmul and of the MFMA-only "
+                         "loop in turn on the workload's shape, with rocm-smi clock and power sampled during each "
+                         "(box-independent comparison, and the record of the power limit)")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="run a plain 1 GiB device copy instead (to scale FETCH_SIZE / WRITE_SIZE under rocprofv3)")
     args = ap.parse_args()
@@ -142,6 +146,55 @@ def main():
             dst.copy_(src)
         torch.cuda.synchronize()
         print(json.dumps({"copy_calibration_bytes_read": n, "copy_calibration_bytes_written": n, "launches": args.steps}))
+        return
+
+    if args.alternate_library:
+        import threading
+        import time as _time
+        w = pi.WORKLOADS[args.workload]
+        tdt = {pi.F32: torch.float32, pi.F16: torch.float16, pi.BF16: torch.bfloat16}[w.dtype]
+        A = (torch.randn((w.K, w.M) if w.transA else (w.M, w.K), device="cuda") * w.scale).to(tdt)
+        B = (torch.randn((w.N, w.K) if w.transB else (w.K, w.N), device="cuda") * w.scale).to(tdt)
+        C = torch.zeros((w.M, w.N), device="cuda", dtype=tdt)
+        opA, opB, out = (A.t() if w.transA else A), (B.t() if w.transB else B), torch.empty_like(C)
+        calib = torch.zeros(8, dtype=torch.int64, device="cuda")
+        samples, stop = [], [False]
+
+        def sampler():
+            while not stop[0]:
+                samples.append((_time.time(), smi_snapshot()))
+
+        th = threading.Thread(target=sampler, daemon=True)
+        th.start()
+        blocks = []
+
+        def block(label, fn, seconds, flops):
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            t0, rates = _time.time(), []
+            while _time.time() - t0 < seconds:
+                e0.record(stream)
+                for _ in range(20):
+                    fn()
+                e1.record(stream)
+                e1.synchronize()
+                rates.append(flops * 20 / (e0.elapsed_time(e1) * 1e-3) * 1e-12)
+            t1 = _time.time()
+            smi = [x[1] for x in samples if t0 + 0.5 < x[0] < t1]
+            blocks.append({"what": label, "tflops_median": float(np.median(rates)), "tflops_last": rates[-1], "batches": len(rates),
+                           "rocm_smi_last": smi[-1] if smi else None})
+            log("[alternate] %-14s %8.1f TFLOP/s  %s" % (label, blocks[-1]["tflops_median"], blocks[-1]["rocm_smi_last"]))
+
+        with pg.Plan(w.M, w.N, w.K, w.dtype, w.transA, w.transB) as plan:
+            ws = torch.empty(max(plan.workspace_bytes, 256), dtype=torch.uint8, device="cuda")
+            _, mfma_flops = pg.peak_calib_mfma(w.dtype, True, 4096, calib.data_ptr(), stream.cuda_stream)
+            for rnd in range(2):
+                block("mfma_only", lambda: pg.peak_calib_mfma(w.dtype, True, 4096, calib.data_ptr(), stream.cuda_stream), 1.0, mfma_flops)
+                block("this_library", lambda: plan.run(w.alpha, A.data_ptr(), B.data_ptr(), 0.0, C.data_ptr(), ws.data_ptr(),
+                                                       plan.workspace_bytes, stream.cuda_stream), args.alternate_library, w.flops)
+                block("torch_matmul", lambda: torch.matmul(opA, opB, out=out), args.alternate_library, w.flops)
+            info = plan.info()
+        stop[0] = True
+        print(json.dumps({"alternate_library": args.workload, "plan": info, "blocks": blocks}))
         return
 
     def dev(x):
