@@ -484,7 +484,7 @@ def main():
                      "S32_bf16", "S64_f16", "S16_f32", "S16_bf16_kn", "S16_f32_kn"]:
             if name == args.workload:
                 continue
-            small = pi.WORKLOADS[name].flops < 1e10
+            small = pi.WORKLOADS[name].flops < 5e10          # short launches: more of them, or the figure is noise
             r, _ = time_workload(name, max(args.steps, 200) if small else args.steps, args.warmup,
                                  with_torch=not args.no_torch, cpu_seconds=0.0 if args.no_cpu else 1.5)
             log("[bench] %s: %.3f ms  %.1f TFLOP/s  %.0f GB/s  (%s)" % (name, r["event_ms_per_step"], r["tflops_events"],
