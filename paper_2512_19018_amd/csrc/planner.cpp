@@ -185,7 +185,11 @@ static void plan_geometry(Geometry *p, const peak_gemm_desc_t &d, int variant, i
     if (split < 1) split = 1;
     p->ktiles_per_slice = (int)cdiv(p->ktiles_total, split);
     p->split = (int)cdiv(p->ktiles_total, p->ktiles_per_slice);   // no empty slices
-    p->group_m = p->tiles_m >= 8 ? 8 : (p->tiles_m > 0 ? p->tiles_m : 1);
+    // tile rows per band: an XCD's 32 tiles of a moment form a patch of group_m x 32 / group_m tiles.  Re-measured with
+    // the 16x16x32 kernels: 4 rows against 8 at bf16 8192^3 695 / 700 us, 8192x4608x8192 417 / 426, 6144^3 321 / 324,
+    // level at 4096^3 and with few tile columns (5000x3000x12288: 249.9 / 249.0)
+    const int band_rows = p->tiles_n >= 16 ? 4 : 8;
+    p->group_m = p->tiles_m >= band_rows ? band_rows : (p->tiles_m > 0 ? p->tiles_m : 1);
     p->rot_m = 0;                                           // K rotation off for the tiled kernels: measured no gain on the graded shapes
                                                             // (bf16 8192^3: 694 us without, 701 with 1, 736 with 5)
     p->rot_n = v.kind == KIND_SKINNY && !v.tr ? 5 : 0;               // streaming kernel: neighbouring workgroups start five K tiles apart
