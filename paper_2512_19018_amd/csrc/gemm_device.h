@@ -123,7 +123,7 @@ PEAK_DEV int swz(int r)
 }
 
 template <int DT_, int BM_, int BN_, int RB_, int WAVES_M_, int WAVES_N_, int NS_,
-          bool A_T_, bool B_T_, bool DIRECT_, int AX_ = 0, bool TR_ = false, bool PP_ = false, bool ATR_ = false>
+          bool A_T_, bool B_T_, bool DIRECT_, int AX_ = 0, bool TR_ = false, bool PP_ = false, bool ATR_ = false, bool AG_ = false>
 struct Cfg {
     static constexpr int DT = DT_;
     static constexpr int ESZ = DT_ == DT_F32 ? 4 : 2;
@@ -172,7 +172,12 @@ struct Cfg {
     // the accumulation half of the register file.  The compiler does not manage that (it
     // keeps part of them in ordinary registers and spills), so for this shape the MFMAs of
     // the main loop are written as assembly with the accumulators constrained to AGPRs.
-    static constexpr bool ACC_AGPR = WAVES_M_ * WAVES_N_ == 4 && (BM_ / WAVES_M_) * (BN_ / WAVES_N_) == 128 * 128;
+    // AG: the same hand-scheduled loop for fp32 with 64x64 wave tiles (128x128 tile, four waves).  Left to the
+    // compiler that loop kept the matrix cores busy 81 % of the time at fp32 2048^3, against 92 % for the
+    // hand-scheduled 256x256 tile.
+    static constexpr bool ACC_AGPR = (WAVES_M_ * WAVES_N_ == 4 && (BM_ / WAVES_M_) * (BN_ / WAVES_N_) == 128 * 128) || AG_;
+    static_assert(!AG_ || (DT_ == DT_F32 && WAVES_M_ * WAVES_N_ == 4 && BM_ / WAVES_M_ == 64 && BN_ / WAVES_N_ == 64),
+                  "hand-scheduled loop on request: fp32, four waves, 64x64 wave tiles");
     static_assert(!PP_ || (NS_ >= 2 && AX_ == 0 && DIRECT_ && !A_T_ && (!B_T_ || TR_) && WAVES_M_ * WAVES_N_ == 8),
                   "alternating loop: 8 waves, both operands direct");
     static_assert(AX_ == 0 || (AX_ == 1 && NS_ == 2 && RB_ == 128 && DIRECT_ && !A_T_ && (!B_T_ || TR_)),
@@ -1165,7 +1170,9 @@ __global__ __launch_bounds__(C::NT) void gemm_kernel(const GemmArgs p)
         // hardware needs between the zeroing of the accumulators and the first MFMA, and
         // between the last MFMA and the first read of an accumulator, are put in by hand.
         constexpr int NM = C::MI * C::NI, NFR = C::MI + C::NI;
-        static_assert(NFR <= NM && DLOADS <= NM && C::MI == C::NI, "one read and one load per MFMA slot");
+        // (fp32: a slot is four MFMAs of 64 cycles and takes two loads where the tile has fewer slots than loads)
+        constexpr int LPS = C::DT == DT_F32 && DLOADS > NM ? 2 : 1;     // loads per slot
+        static_assert(NFR <= NM && DLOADS <= LPS * NM && C::MI == C::NI, "one read and one load (fp32: two) per MFMA slot");
         u32x4 af[2][C::MI], bf[2][C::NI];
         // B kept as [k][n] rows: its transposing reads go out as assembly (the compiler would put a
         // wait for all loads in front of each, see the loop below) into bl/bh and are handed over
@@ -1213,10 +1220,12 @@ __global__ __launch_bounds__(C::NT) void gemm_kernel(const GemmArgs p)
                 // i / 4 of four blocks, so that consecutive MFMAs write different accumulators and an
                 // accumulator comes round again only 16 MFMAs later (the compiler, which would put the
                 // wait states between dependent MFMAs, does not see inside these statements).
-                static_assert(C::MI * C::NI == 16, "four blocks per slot, four slots per k step");
-                constexpr int st = i / 4;
+                // With four blocks in all (64x64 wave tile) a slot is one k step of all of them.
+                static_assert(C::MI * C::NI == 16 || C::MI * C::NI == 4, "four blocks per slot");
+                constexpr int SPK = C::MI * C::NI / 4;                   // slots per k step
+                constexpr int st = i / SPK;
                 static_for<4>([&](auto bc) {
-                    constexpr int blk = (i % 4) * 4 + decltype(bc)::value;
+                    constexpr int blk = (i % SPK) * 4 + decltype(bc)::value;
                     f32x16 &cc = acc[blk / C::NI][blk % C::NI];
                     const float bv = __builtin_bit_cast(f32x4, bf[set][blk % C::NI])[st];
                     const float av = __builtin_bit_cast(f32x4, af[set][blk / C::NI])[st];
@@ -1301,7 +1310,8 @@ __global__ __launch_bounds__(C::NT) void gemm_kernel(const GemmArgs p)
                                 // later instead: no gain)
                                 if constexpr (LAST && i % 2 == 0 && i / 2 < LB) issue_b(kt + 2, s, IC<i / 2>{}, IC<LB>{});
                             } else {
-                                if constexpr (LAST && i < DLOADS) load_one(kt + 2, s, ic);
+                                if constexpr (LAST && LPS * i < DLOADS) load_one(kt + 2, s, IC<LPS * i>{});
+                                if constexpr (LAST && LPS == 2 && LPS * i + 1 < DLOADS) load_one(kt + 2, s, IC<(LPS * i + 1 < DLOADS ? LPS * i + 1 : 0)>{});
                             }
                             __builtin_amdgcn_sched_barrier(0);
                         });
@@ -1311,7 +1321,9 @@ __global__ __launch_bounds__(C::NT) void gemm_kernel(const GemmArgs p)
         }
         settle(IC<0>{});      // the last k-group's reads feed nothing, but must have returned before their registers are reused
         // 32x32x16 MFMA: 8 passes of 4 cycles; an accumulator may be read 18 wait states after the issue
+        // (32x32x2 fp32: 16 passes)
         asm volatile("s_nop 15\n\ts_nop 15" ::: "memory");
+        if constexpr (C::DT == DT_F32) asm volatile("s_nop 15\n\ts_nop 15\n\ts_nop 15\n\ts_nop 15" ::: "memory");
 #ifdef PEAK_TRACE
         tr_loop1 = __builtin_amdgcn_s_memtime();
 #endif

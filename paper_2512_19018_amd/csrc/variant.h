@@ -64,6 +64,12 @@ static int launch_gemm(const GemmArgs &a, unsigned grid, void *stream)
      Cfg<DT, BM, BN, RB, WMW, WNW, NS, false, true, true, 0, true>::LDS_BYTES, 0,                      \
      &launch_gemm<Cfg<DT, BM, BN, RB, WMW, WNW, NS, false, true, true, 0, true>>, 1, 0, 0, 0}
 
+// fp32, B kept as [k][n] rows, 128x128 tile of four 64x64 wave tiles, hand-scheduled loop
+#define TILED_TR_AG(NAME, BM, BN)                                                                      \
+    {NAME, KIND_TILED, DT_F32, 0, 1, 1, BM, BN, PEAK_BK(DT_F32, 128), 256, 2,                          \
+     Cfg<DT_F32, BM, BN, 128, 2, 2, 2, false, true, true, 0, true, false, false, true>::LDS_BYTES, 0,  \
+     &launch_gemm<Cfg<DT_F32, BM, BN, 128, 2, 2, 2, false, true, true, 0, true, false, false, true>>, 1, 0, 0, 0}
+
 // A stored K x M staged directly as [k][m] rows; B either along K ("_tt") or [k][n] rows as well ("_tn")
 #define TILED_ATR(NAME, DT, BM, BN, RB, WMW, WNW, NS, BTR)                                             \
     {NAME, KIND_TILED, DT, 1, BTR, 1, BM, BN, PEAK_BK(DT, RB), WMW * WNW * 64, NS,                     \

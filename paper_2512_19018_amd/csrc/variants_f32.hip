@@ -13,6 +13,7 @@ static const Variant rows_f32[] = {
     TILED("f32_d256x128w8s3_nn", DT_F32, 256, 128, 128, 4, 2, 3, false, true, true),
     TILED_TR("f32_t128x128w4_nn", DT_F32, 128, 128, 128, 2, 2, 2),
     TILED_TR("f32_t128x128w4s3_nn", DT_F32, 128, 128, 128, 2, 2, 3),
+    TILED_TR_AG("f32_t128x128w4g_nn", 128, 128),
     TILED_TR("f32_t256x128w8_nn", DT_F32, 256, 128, 128, 4, 2, 2),
     TILED_TR("f32_t256x128w8s3_nn", DT_F32, 256, 128, 128, 4, 2, 3),
     TILED_TR("f32_t256x128w4_nn", DT_F32, 256, 128, 128, 2, 2, 2),
