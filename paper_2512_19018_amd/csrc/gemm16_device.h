@@ -25,7 +25,7 @@ namespace peak {
 
 typedef float f32x4v __attribute__((ext_vector_type(4)));
 
-constexpr int A_BYTES_OF(int tile) { return tile * 128; }    // one stage of one operand: tile rows x 64 k x 2 bytes
+constexpr int A_BYTES_OF(int tile, int bk = 64) { return tile * bk * 2; }    // one stage of one operand: tile rows x BK k x 2 bytes
 
 // TILE: 256 (the large problems: one workgroup per CU, one wave per SIMD, 128x128 per wave) or
 // 128 (mid-size problems: 64x64 per wave, 80 KB of LDS and half the registers, so two workgroups
@@ -36,7 +36,9 @@ constexpr int A_BYTES_OF(int tile) { return tile * 128; }    // one stage of one
 // cycles of waiting per K tile at bf16 2048^3 with a distance of 2)
 // TILE_N: columns of the tile when it is not square (256 x 128: problems that fill the chip with neither
 // the 256 x 256 nor the 128 x 128 tile, and whose wave tile of 128 x 64 still spares the LDS)
-template <int DT_, bool A_KM_ = false, bool B_KN_ = false, int TILE_ = 256, int PF_ = 2, int TILE_N_ = TILE_>
+// BK: k per stage, 64 or 128.  128 (the 128 x 128 tile only: 3 + 2 stages of 32 KB) halves the barriers and waits
+// per multiply-add and takes 256 bytes of a row from memory at a time instead of 128.
+template <int DT_, bool A_KM_ = false, bool B_KN_ = false, int TILE_ = 256, int PF_ = 2, int TILE_N_ = TILE_, int BK_ = 64>
 struct Cfg16 {
     static_assert(DT_ == DT_F16 || DT_ == DT_BF16, "16-bit storage");
     static_assert((TILE_ == 256 || TILE_ == 128) && (TILE_N_ == 256 || TILE_N_ == 128), "workgroup tile");
@@ -44,15 +46,16 @@ struct Cfg16 {
     static constexpr bool A_KM = A_KM_;                      // A stored K x M: staged as [k][m] rows
     static constexpr bool B_KN = B_KN_;                      // B stored K x N: staged as [k][n] rows
     static constexpr int ESZ = 2, EPC = 8;
-    static constexpr int BM = TILE_, BN = TILE_N_, RB = 128, CPR = 8, BK = 64;
+    static_assert(BK_ == 64 || BK_ == 128, "k per stage");
+    static constexpr int BM = TILE_, BN = TILE_N_, RB = BK_ * 2, CPR = RB / 16, BK = BK_;
     static constexpr int WAVES_M = 2, WAVES_N = 2, NW = 4, NT = 256;
     static constexpr int PF = PF_;
-    static constexpr int WAVES_PER_EU = PF_ == 2 && TILE_ == 128 && TILE_N_ == 128 ? 2 : 1;   // workgroups per CU the register budget is cut for
+    static constexpr int WAVES_PER_EU = PF_ == 2 && TILE_ == 128 && TILE_N_ == 128 && BK_ == 64 ? 2 : 1;   // workgroups per CU the register budget is cut for
     static constexpr int WTM = BM / 2, WTN = BN / 2;
     static constexpr int MB = WTM / 16, NB = WTN / 16;      // 16x16 blocks per wave tile
     static constexpr int KS = BK / 32;                      // MFMA k-steps per K tile
     static constexpr int NSA = PF_ + 1, NSB = PF_;
-    static_assert(PF_ >= 2 && A_BYTES_OF(TILE_) * NSA + A_BYTES_OF(TILE_N_) * NSB <= 160 * 1024, "stages fit the LDS");
+    static_assert(PF_ >= 2 && A_BYTES_OF(TILE_, BK_) * NSA + A_BYTES_OF(TILE_N_, BK_) * NSB <= 160 * 1024, "stages fit the LDS");
     static constexpr int A_BYTES = BM * RB, B_BYTES = BN * RB;
     static constexpr int LDS_BYTES = A_BYTES * NSA + B_BYTES * NSB;
     // Chunk c of tile row r sits at chunk position c ^ swizzle(r).  The swizzle depends on
@@ -67,7 +70,13 @@ struct Cfg16 {
     // whose partners under "^ 2" are four others: bit 1 of the swizzle is the same for the
     // eight rows of a group (and differs between the two groups of a block, which keeps
     // sixteen consecutive lanes conflict-free as well), bits 0 and 2 count the row pairs.
-    static __device__ __forceinline__ int swizzle(int r) { return ((r >> 1) & 1) | (((r >> 2) & 1) << 2) | (((r >> 3) & 1) << 1); }
+    // With 256-byte rows (BK = 128) all rows start in the same bank and a step's 8 rows x 2 chunks must take all
+    // 16 positions of a row: bits 0, 2 and 3 count the rows of a group, bit 1 again tells the two groups apart.
+    static __device__ __forceinline__ int swizzle(int r)
+    {
+        if constexpr (BK_ == 64) return ((r >> 1) & 1) | (((r >> 2) & 1) << 2) | (((r >> 3) & 1) << 1);
+        else return (r & 1) | (((r >> 1) & 1) << 2) | (((r >> 2) & 1) << 3) | (((r >> 3) & 1) << 1);
+    }
     // Tiles kept as [k][x] rows (512 bytes each, so all rows start in the same bank): chunk c of
     // row k sits at c ^ kn_swizzle(k).  A transposing read has its four groups of 16 lanes on
     // k-rows 8 q .. 8 q + 3 (q = lane / 16), 32 bytes of each.  4 * (k & 3) sends the four rows of
@@ -373,14 +382,17 @@ __global__ __launch_bounds__(C::NT, C::WAVES_PER_EU) void gemm16_kernel(const Ge
     //                         tile kt+2 into the stage tile kt has just left, rest of A's loads
     constexpr int NM = C::MB * C::NB;                        // MFMAs per k-step
     constexpr int NFR = C::MB + C::NB;                       // fragments per k-step
-    static_assert(C::KS == 2 && LA % 2 == 0 && 2 * NFR <= NM && slot_plan_ok(NM, NFR, LA, LB), "slot plan below");
+    static_assert(LA % 2 == 0 && 2 * NFR <= NM, "slot plan below");
+    static_assert(C::KS == 4 || (C::KS == 2 && slot_plan_ok(NM, NFR, LA, LB)), "two k-steps per K tile: the slot plan below");
+    static_assert(C::KS == 2 || (C::KS == 4 && C::PF == 2 && NM == 16 && NFR == 8 && LA == 8 && LB == 8), "four k-steps: 128 x 128 tile");
     // fragment f of a k-step in the order the MFMAs first need them: B0, A0 .. A7, B1 .. B7
-    auto fetch_one = [&](auto sac, auto sbc, auto ksc, auto fc) {
+    auto fetch_one_set = [&](auto sac, auto sbc, auto ksc, auto setc, auto fc) {
         constexpr int f = decltype(fc)::value;
-        if constexpr (f == 0) read_b(sbc, ksc, IC<0>{}, ksc);
-        else if constexpr (f <= C::MB) read_a(sac, ksc, IC<f - 1>{}, ksc);
-        else read_b(sbc, ksc, IC<f - C::MB>{}, ksc);
+        if constexpr (f == 0) read_b(sbc, ksc, IC<0>{}, setc);
+        else if constexpr (f <= C::MB) read_a(sac, ksc, IC<f - 1>{}, setc);
+        else read_b(sbc, ksc, IC<f - C::MB>{}, setc);
     };
+    auto fetch_one = [&](auto sac, auto sbc, auto ksc, auto fc) { fetch_one_set(sac, sbc, ksc, ksc, fc); };   // two k-steps: set = k-step
     auto mfma_one = [&](auto setc, auto jc) {
         constexpr int set = decltype(setc)::value, j = decltype(jc)::value;
         constexpr int nb = j / C::MB, mb = j % C::MB;
@@ -431,7 +443,49 @@ __global__ __launch_bounds__(C::NT, C::WAVES_PER_EU) void gemm16_kernel(const Ge
 #ifdef PEAK_TRACE
     tr_loop0 = __builtin_amdgcn_s_memtime();
 #endif
-    {
+    if constexpr (C::KS == 4) {
+        // Four k-steps of 16 MFMAs per K tile (BK = 128).  Fragments of the next k-step follow the first eight
+        // MFMAs of each; A's eight loads of tile kt+2 are spread over the slots behind them in k-steps 0 to 2
+        // (its stage is free since the barrier of tile kt-1), the tile's barrier stands before k-step 3, and B's
+        // eight loads follow it.  The loads' offsets are worked out at the start of the tile.
+        constexpr auto may_tail = IC<MAY_TAIL ? 1 : 0>{};
+        constexpr int U = C::NSA * C::NSB;
+        for (int kt0 = 0; kt0 < KT; kt0 += U) {
+            static_for<U>([&](auto uc) {
+                constexpr int u = decltype(uc)::value;
+                constexpr int s = u % C::NSB, s1 = (u + 1) % C::NSB, sa = u % C::NSA, sa1 = (sa + 1) % C::NSA, sa2 = (sa + C::PF) % C::NSA;
+                const int kt = kt0 + u;
+                if (kt < KT) {
+                    static_for<4>([&](auto ksc) {
+                        constexpr int ks = decltype(ksc)::value, cur = ks & 1, nxt = cur ^ 1;
+                        if constexpr (ks == 3) {
+                            wait_vmcnt<LA>();                    // own loads of tile kt+1 (A's of tile kt+2 may be under way)
+                            lds_barrier();                       // tile kt+1 complete, tile kt read
+                        }
+                        settle(IC<cur>{});
+                        __builtin_amdgcn_sched_barrier(0);
+                        static_for<NM>([&](auto jc) {
+                            constexpr int j = decltype(jc)::value;
+                            // which load follows MFMA j: A part 3 ks + (j - 8) / 2 in k-steps 0 to 2, B part j - 8 in k-step 3
+                            constexpr int pa = ks < 3 && j >= 8 && j % 2 == 0 && 3 * ks + (j - 8) / 2 < LA && (j - 8) / 2 < 3 ? 3 * ks + (j - 8) / 2 : -1;
+                            constexpr int pb = ks == 3 && j >= 8 ? j - 8 : -1;
+                            if constexpr (ks == 0 && j == 0) next_offsets(kt + C::PF);
+                            if constexpr (pa >= 0) m0_a(sa2, IC<(pa >= 0 ? pa : 0)>{});
+                            if constexpr (pb >= 0) m0_b(s, IC<(pb >= 0 ? pb : 0)>{});
+                            mfma_one(IC<cur>{}, jc);
+                            if constexpr (j < NFR) {
+                                if constexpr (ks < 3) fetch_one_set(IC<sa>{}, IC<s>{}, IC<(ks + 1) % 4>{}, IC<nxt>{}, jc);
+                                else fetch_one_set(IC<sa1>{}, IC<s1>{}, IC<0>{}, IC<nxt>{}, jc);
+                            }
+                            if constexpr (pa >= 0) ld_a(IC<(pa >= 0 ? pa : 0)>{}, may_tail);
+                            if constexpr (pb >= 0) ld_b(IC<(pb >= 0 ? pb : 0)>{}, may_tail);
+                            __builtin_amdgcn_sched_barrier(0);
+                        });
+                    });
+                }
+            });
+        }
+    } else {
         constexpr auto may_tail = IC<MAY_TAIL ? 1 : 0>{};
         constexpr int U = C::NSA * C::NSB;                   // tiles per trip: both stage indices static (NSA and NSB differ by one)
         for (int kt0 = 0; kt0 < KT; kt0 += U) {

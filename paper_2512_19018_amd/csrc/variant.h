@@ -24,6 +24,7 @@ VariantGroup variants_skinny();
 VariantGroup variants_mf16();
 VariantGroup variants_mf16s();
 VariantGroup variants_mf16r();
+VariantGroup variants_mf16k();
 
 template <class C>
 static int launch_gemm(const GemmArgs &a, unsigned grid, void *stream)

@@ -28,4 +28,10 @@ static int launch_gemm16(const GemmArgs &a, unsigned grid, void *stream)
      Cfg16<DT, AKM != 0, BKN != 0, TM, PF, TN>::LDS_BYTES, 0,                                          \
      &launch_gemm16<Cfg16<DT, AKM != 0, BKN != 0, TM, PF, TN>>, BKN, AKM, 0, 0, 1}
 
+// ... with BK k per stage
+#define TILED_MF16_K(NAME, DT, AKM, BKN, TM, TN, PF, BK)                                               \
+    {NAME, KIND_TILED, DT, AKM, BKN, 1, TM, TN, BK, 256, PF,                                           \
+     Cfg16<DT, AKM != 0, BKN != 0, TM, PF, TN, BK>::LDS_BYTES, 0,                                      \
+     &launch_gemm16<Cfg16<DT, AKM != 0, BKN != 0, TM, PF, TN, BK>>, BKN, AKM, 0, 0, 1}
+
 }  // namespace peak
