@@ -48,7 +48,7 @@ MEASURED_TRAFFIC = {
     "C4": ("f16_m256x256w4a3_nn", 1, 7.340e8),
     "S16_bf16_kn": ("bf16_skinny_m16n256k64s4_nn", 2, 4.803e8),
     "S64_f16": ("f16_skinny_m64n128k128s3_nt", 1, 5.401e8),
-    "S16_f32": ("f32_skinny_m16n64k64s3_nt", 1, 1.2517e9),
+    "S16_f32": ("f32_skinny_m16n64k128s3_nt", 1, 1.2091e9),
     "P2k_f16": ("f16_m128x128k128w4a3_nn", 1, 5.90e7),
 }
 
