@@ -21,7 +21,7 @@ static const std::vector<Variant> &variants()
         std::vector<Variant> t;
         const VariantGroup groups[] = {variants_general(), variants_bf16_nt(), variants_f16_nt(), variants_bf16_nn(),
                                        variants_f16_nn(),  variants_f32(),     variants_ta(),     variants_skinny(),
-                                       variants_mf16(),    variants_mf16s(),   variants_mf16r(),
+                                       variants_mf16(),    variants_mf16s(),   variants_mf16d(),   variants_mf16r(),
                                        variants_mf16k()};
         for (const VariantGroup &g : groups) t.insert(t.end(), g.rows, g.rows + g.count);
         return t;

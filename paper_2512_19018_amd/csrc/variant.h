@@ -23,6 +23,7 @@ VariantGroup variants_ta();
 VariantGroup variants_skinny();
 VariantGroup variants_mf16();
 VariantGroup variants_mf16s();
+VariantGroup variants_mf16d();
 VariantGroup variants_mf16r();
 VariantGroup variants_mf16k();
 

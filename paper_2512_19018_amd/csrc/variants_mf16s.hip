@@ -13,16 +13,6 @@ static const Variant rows_mf16s[] = {
     TILED_MF16("f16_m128x128w4a3_tt", DT_F16, 1, 0, 128, 2),
     TILED_MF16("bf16_m128x128w4a3_tn", DT_BF16, 1, 1, 128, 2),
     TILED_MF16("f16_m128x128w4a3_tn", DT_F16, 1, 1, 128, 2),
-    // the same tile with five A stages and four B stages (144 KB: one workgroup per CU), loads four K tiles ahead:
-    // for problems of at most one tile per CU, where nothing else covers a load's latency
-    TILED_MF16("bf16_m128x128w4a5_nt", DT_BF16, 0, 0, 128, 4),
-    TILED_MF16("f16_m128x128w4a5_nt", DT_F16, 0, 0, 128, 4),
-    TILED_MF16("bf16_m128x128w4a5_nn", DT_BF16, 0, 1, 128, 4),
-    TILED_MF16("f16_m128x128w4a5_nn", DT_F16, 0, 1, 128, 4),
-    TILED_MF16("bf16_m128x128w4a5_tt", DT_BF16, 1, 0, 128, 4),
-    TILED_MF16("f16_m128x128w4a5_tt", DT_F16, 1, 0, 128, 4),
-    TILED_MF16("bf16_m128x128w4a5_tn", DT_BF16, 1, 1, 128, 4),
-    TILED_MF16("f16_m128x128w4a5_tn", DT_F16, 1, 1, 128, 4),
 };
 
 PEAK_VARIANT_GROUP(variants_mf16s, rows_mf16s)
