@@ -188,8 +188,8 @@ static void plan_geometry(Geometry *p, const peak_gemm_desc_t &d, int variant, i
     p->ktiles_per_slice = (int)cdiv(p->ktiles_total, split);
     p->split = (int)cdiv(p->ktiles_total, p->ktiles_per_slice);   // no empty slices
     // tile rows per band: an XCD's 32 tiles of a moment form a patch of group_m x 32 / group_m tiles.  Re-measured with
-    // the 16x16x32 kernels: 4 rows against 8 at bf16 8192^3 695 / 700 us, 8192x4608x8192 417 / 426, 6144^3 321 / 324,
-    // level at 4096^3 and with few tile columns (5000x3000x12288: 249.9 / 249.0)
+    // the 16x16x32 kernels, 4 rows against 8 in alternating blocks: bf16 8192x4608x8192 +0.8 %, 6144^3 +0.9 %, 4096^3
+    // +0.5 %, 8192^3 level, and -0.6 % with few tile columns (f16 5000x3000x12288)
     const int band_rows = p->tiles_n >= 16 ? 4 : 8;
     p->group_m = p->tiles_m >= band_rows ? band_rows : (p->tiles_m > 0 ? p->tiles_m : 1);
     p->rot_m = 0;                                           // K rotation off for the tiled kernels: measured no gain on the graded shapes
