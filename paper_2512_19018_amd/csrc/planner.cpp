@@ -489,10 +489,10 @@ int peak_gemm_plan_info(const peak_gemm_plan_t *p, char *buf, size_t n)
     const Variant &v = g_variants[g.variant];
     return snprintf(buf, n,
                     "variant=%d:%s tile=%dx%dx%d threads=%d stages=%d lds=%d split=%d ktiles/slice=%d "
-                    "grid=%lld (tiles %dx%d) group_m=%d workspace=%zu unaligned=%s streamk=%d",
+                    "grid=%lld (tiles %dx%d) group_m=%d workspace=%zu unaligned=%s streamk=%d rot=%d,%d",
                     g.variant, v.name, v.bm, v.bn, v.bk, v.nt, v.ns, v.lds, g.split, g.ktiles_per_slice,
                     (long long)grid_blocks(g), g.tiles_m, g.tiles_n, g.group_m, p->ws_bytes,
-                    p->alt.variant >= 0 ? g_variants[p->alt.variant].name : "same", g.sk_tiles);
+                    p->alt.variant >= 0 ? g_variants[p->alt.variant].name : "same", g.sk_tiles, g.rot_m, g.rot_n);
 }
 
 peak_status_t peak_gemm_destroy(peak_gemm_plan_t *plan)

@@ -406,3 +406,21 @@ def test_streaming_plans_cover_m_up_to_64_fp32_and_b_stored_k_by_n():
     assert "skinny" not in info(16, 28672, 8200, bf, 0, 0)            # K not a whole number of stages
     # A stored K x M: no streaming kernel
     assert "skinny" not in info(16, 28672, 8192, bf, 1, 1) and "skinny" not in info(16, 28672, 8192, bf, 1, 0)
+
+
+def test_tile_order_and_k_rotation_of_the_plans():
+    """Bands of four tile rows where the problem has 16 or more tile columns, eight otherwise; the
+    16x16x32 kernels start their workgroups one K tile apart when there is a single row of tiles
+    (every workgroup then streams rows of B that no other reads), the streaming NT kernel five apart."""
+    def info(M, N, K, dt, tA, tB):
+        with pg.Plan(M, N, K, dt, tA, tB) as p:
+            return p.info()
+    bf, f16 = pg.PEAK_DT_BF16, pg.PEAK_DT_F16
+    c3 = info(8192, 8192, 8192, bf, 0, 1)
+    assert "group_m=4 " in c3 and c3.endswith("rot=0,0")
+    c4 = info(5000, 3000, 12288, f16, 0, 0)
+    assert "group_m=8 " in c4 and c4.endswith("rot=0,0")
+    single = info(128, 28672, 8192, bf, 0, 1)
+    assert "_m128x128" in single and "(tiles 1x224)" in single and single.endswith("rot=0,1")
+    assert info(16, 16384, 16384, bf, 0, 1).endswith("rot=0,5")
+    assert info(16, 28672, 8192, bf, 0, 0).endswith("rot=0,0")        # B stored K x N: contiguous pieces of a k-row
