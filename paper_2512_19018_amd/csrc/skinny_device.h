@@ -132,24 +132,31 @@ __global__ __launch_bounds__(C::NT) void skinny_kernel(const GemmArgs p)
                 for (int kg = 0; kg < C::KSTEP / C::KMMA; ++kg) {
                     const int c = kg * 4 + q;
                     const u32x4 bf = *(const u32x4 *)(st + b_row + (((c & ~15) | ((c & 15) ^ b_sw)) << 4));
+                    u32x4 af[C::MBLK];
 #pragma unroll
-                    for (int mb = 0; mb < C::MBLK; ++mb) {
-                        const u32x4 af = *(const u32x4 *)(st + a_row + mb * 16 * C::RB + (((c & ~15) | ((c & 15) ^ a_sw)) << 4));
-                        if constexpr (C::DT == DT_BF16)
-                            acc[mb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, bf),
-                                                                              __builtin_bit_cast(bf16x8, af), acc[mb], 0, 0, 0);
-                        else if constexpr (C::DT == DT_F16)
-                            acc[mb] = __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(f16x8, bf),
-                                                                             __builtin_bit_cast(f16x8, af), acc[mb], 0, 0, 0);
-                        else {
-                            // fp32: the chunk holds 4 k per lane; MFMA s takes element s of both chunks, so its
-                            // four k are 16 * kg + 4 * (lane / 16) + s over the four lane groups
+                    for (int mb = 0; mb < C::MBLK; ++mb)
+                        af[mb] = *(const u32x4 *)(st + a_row + mb * 16 * C::RB + (((c & ~15) | ((c & 15) ^ a_sw)) << 4));
+                    if constexpr (C::DT == DT_F32) {
+                        // fp32: the chunk holds 4 k per lane; MFMA e takes element e of both chunks, so its four k
+                        // are 16 * kg + 4 * (lane / 16) + e over the four lane groups.  The blocks take turns, so
+                        // that an MFMA does not follow the one whose result it adds to.
 #pragma unroll
-                            for (int e = 0; e < 4; ++e) {
-                                const uint32_t be = bf[e], ae = af[e];      // (a bit cast straight from the vector's element takes element 0)
+                        for (int e = 0; e < 4; ++e)
+#pragma unroll
+                            for (int mb = 0; mb < C::MBLK; ++mb) {
+                                const uint32_t be = bf[e], ae = af[mb][e];      // (a bit cast straight from the vector's element takes element 0)
                                 acc[mb] = __builtin_amdgcn_mfma_f32_16x16x4f32(__builtin_bit_cast(float, be),
                                                                                __builtin_bit_cast(float, ae), acc[mb], 0, 0, 0);
                             }
+                    } else {
+#pragma unroll
+                        for (int mb = 0; mb < C::MBLK; ++mb) {
+                            if constexpr (C::DT == DT_BF16)
+                                acc[mb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, bf),
+                                                                                  __builtin_bit_cast(bf16x8, af[mb]), acc[mb], 0, 0, 0);
+                            else
+                                acc[mb] = __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(f16x8, bf),
+                                                                                 __builtin_bit_cast(f16x8, af[mb]), acc[mb], 0, 0, 0);
                         }
                     }
                 }
