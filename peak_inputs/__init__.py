@@ -236,6 +236,9 @@ WORKLOADS = {
                             "bf16 skinny 16x28672x8192 NN, B stored K x N (HBM bound)"),
     "S16_f32_kn": Workload("S16_f32_kn", F32, 16, 28672, 8192, 0, 0, 1.0, 0.0, "normal", 0.02, 16,
                            "fp32 skinny 16x28672x8192 NN, B stored K x N (HBM bound)"),
+    # one row of 128 x 128 tiles, B streamed from HBM by the tiled kernel (128 k per stage)
+    "D128_bf16": Workload("D128_bf16", BF16, 128, 28672, 8192, 0, 1, 1.0, 0.0, "normal", 0.02, 17,
+                          "bf16 128x28672x8192 NT (one row of tiles, HBM bound)"),
     # the two layouts with A stored K x M, as context for the [k][m] staging path
     "T4k_bf16_tn": Workload("T4k_bf16_tn", BF16, 4096, 4096, 4096, 1, 0, 1.0, 0.0, "normal", 1.0 / math.sqrt(4096.0), 9,
                             "bf16 4096^3 TN (A stored K x M, B stored K x N)"),
