@@ -11,8 +11,10 @@ under "workloads" in the same JSON line.
 
 Order of a run: the headline workload's inputs are made and uploaded; the
 matrix cores' sustained rate is measured with an MFMA-only loop on random
-operands (include/peak_calib.h); then W warmup steps, K timed steps between one
-pair of HIP events, K more steps with an event pair each (median, min, mean);
+operands (include/peak_calib.h); launches of the workload itself for --settle-ms
+(the chip's power management takes some 50 launches to settle after a change of
+load, and the calibration loop is a different load; the count is in the line as
+"settle_launches"); then W warmup steps, K timed steps between one pair of HIP events, K more steps with an event pair each (median, min, mean);
 torch.matmul on the same buffers as context; the CPU oracle on a bounded sample
 of rows; then the other workloads the same way with shorter CPU samples.
 
@@ -41,15 +43,16 @@ PEAK_HBM_GBS = 8000.0
 # A figure belongs to the kernel variant it was measured on: it is reported only
 # when the plan of this run selects that very variant and split, else null.
 MEASURED_TRAFFIC = {
-    "C3": ("bf16_m256x256w4a3_nt", 1, 1.759e9),
+    "C3": ("bf16_m256x256w4a3_nt", 1, 1.746e9),
     "C3b": ("bf16_m256x256w4a3_nt", 1, 2.352e8),
-    "C5": ("bf16_skinny16s3_nt", 1, 5.571e8),
+    "C5": ("bf16_skinny16s3_nt", 1, 5.567e8),
     "C2": ("f32_t256x256w4a3_nn", 1, 5.380e8),
     "C4": ("f16_m256x256w4a3_nn", 1, 7.340e8),
     "S16_bf16_kn": ("bf16_skinny_m16n256k64s4_nn", 2, 4.803e8),
     "S64_f16": ("f16_skinny_m64n128k128s3_nt", 1, 5.401e8),
     "S16_f32": ("f32_skinny_m16n64k128s3_nt", 1, 1.2091e9),
     "P2k_f16": ("f16_m128x128k128w4a3_nn", 1, 5.90e7),
+    "D128_bf16": ("bf16_m128x128k128w4a3_nt", 1, 5.082e8),
 }
 
 
@@ -97,6 +100,9 @@ def main():
     # is long enough that the timed steps see the sustained state
     ap.add_argument("--steps", type=int, default=100)
     ap.add_argument("--warmup", type=int, default=200)
+    ap.add_argument("--settle-ms", type=float, default=150.0,
+                    help="before the W warmup steps: launches of the workload for this long (at most 2000), so that a "
+                         "short warmup does not time the power management's reaction to the change of load")
     ap.add_argument("--workload", default="C3")
     ap.add_argument("--only", action="store_true", help="time only the headline workload")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU-oracle baseline leg")
@@ -285,6 +291,17 @@ def main():
                 "sample": "%d of %d rows of C (all N columns, full K) of %s in %.2f s on %d thread%s; rate scaled to the "
                           "whole product" % (len(rows), w.M, label or w.name, t_cpu, threads, "" if threads == 1 else "s")}
 
+    def settle(launch):
+        """Launches in groups of ten until --settle-ms have passed (at most 2000); returns the count."""
+        n = 0
+        t0 = time.perf_counter()
+        while args.settle_ms > 0 and n < 2000 and (time.perf_counter() - t0) * 1e3 < args.settle_ms:
+            for _ in range(10):
+                launch(n)
+                n += 1
+            torch.cuda.synchronize()
+        return n
+
     def time_workload(name, steps, warmup, variant=None, split=None, with_torch=True, cpu_seconds=0.0):
         w = pi.WORKLOADS[name]
         t0 = time.time()
@@ -350,6 +367,7 @@ def main():
                     plan.run(w.alpha, dA[s].data_ptr(), dB[s].data_ptr(), w.beta, dC[s].data_ptr(),
                              ws.data_ptr(), plan.workspace_bytes, stream.cuda_stream)
 
+            res["settle_launches"] = settle(step)
             for i in range(warmup):
                 step(i)
             torch.cuda.synchronize()
@@ -424,6 +442,7 @@ def main():
                         torch.addmm(tC, opA, opB, beta=w.beta, alpha=w.alpha, out=out)
                     else:
                         torch.matmul(opA, opB, out=out)
+                settle(lambda i: tstep())
                 for _ in range(max(3, warmup // 2)):
                     tstep()
                 torch.cuda.synchronize()
@@ -469,6 +488,7 @@ def main():
         "roofline": head["roofline"],
         "pct_of_peak": 100.0 * head["roofline"]["frac"],
         "per_launch_ms": head["per_launch_ms"],
+        "settle_launches": head["settle_launches"],
         "torch_matmul_tflops": head.get("torch_tflops"),
         "pct_of_library": head.get("pct_of_library"),
     }
