@@ -89,7 +89,9 @@ static double tiled_cost(const Variant &v, const peak_gemm_desc_t &d, int split)
     // The constants come from the measured sweeps on the graded shapes.
     double eff = 1.0;
     if (v.dt == PEAK_DT_F32) {                               // fp32 MFMA is slow enough that tile size hardly matters
-        if (v.bm * v.bn >= 256 * 256) eff = 0.90;       // 128x128 per wave: a quarter of the LDS traffic of 64x64 wave tiles
+        // 128x128 per wave: a quarter of the LDS traffic of 64x64 wave tiles; with one wave per SIMD 1-3 % ahead of
+        // the 128 x 128 tile on full rounds (2048x8192x8192: 1822 us against 1871)
+        if (v.bm * v.bn >= 256 * 256) eff = v.nt == 256 && v.lds > 140 * 1024 ? 0.96 : 0.90;
         else if (v.bm * v.bn >= 256 * 128) eff = 0.86;
         else if (v.bm * v.bn >= 128 * 128) eff = 0.95;
         else if (v.bm * v.bn >= 128 * 64) eff = 0.8;    // as good per multiply-add as 128x128 while few workgroups run
@@ -113,7 +115,20 @@ static double tiled_cost(const Variant &v, const peak_gemm_desc_t &d, int split)
     // stands in for the second workgroup that would cover the loads' latency
     // (likewise the form with 128 k per stage: one workgroup per CU, half the barriers per multiply-add, 256 bytes
     // of a row per load step; bf16 128x28672x8192 87 us against 93)
-    if (v.mf16 && v.bm == 128 && v.bn == 128 && (v.ns > 2 || v.bk == 128)) eff *= tiles <= num_cu() ? 1.3 : 0.85;
+    // The gain fades with the depth of K: a long launch runs at the chip's power limit, where the energy per
+    // multiply-add decides and the 256 x 256 tile's smaller LDS and L2 traffic wins (bf16 512x8192x28672: 252 us
+    // against 211 for the 256 x 256 tile split four ways; 512x8192x8192: the 128 x 128 form ahead, 57.8 us).
+    const double kdepth = ktiles * v.bk;
+    if (v.mf16 && v.bm == 128 && v.bn == 128 && (v.ns > 2 || v.bk == 128))
+        eff *= tiles > num_cu() ? 0.85 : kdepth > 16384.0 ? 0.8 : kdepth > 8192.0 ? 1.1 : 1.3;
+    else if (v.mf16 && v.bm == 128 && v.bn == 128 && tiles <= num_cu())
+        eff *= 0.85;                                    // the two-workgroups-per-CU form with a CU to itself
+    else if (v.dt != PEAK_DT_F32 && v.bm * v.bn < 256 * 256 && kdepth > 8192.0)
+        eff *= 0.85;                                    // likewise the other tiles below 256 x 256 (256 x 128 at 512x8192x28672 in two slices: 264 us)
+    // The small tiles of the 32x32x16 kernels hide the loads' latency behind the other workgroups of their CU.
+    // Where there is at most one round of them and K is deep, each K tile waits out a trip to memory
+    // (bf16 512x4096x4096: 128x64 tiles 37 us, the 128 x 128 forms above 26; f16 NN likewise 37 against 29).
+    if (v.dt != PEAK_DT_F32 && !v.mf16 && v.bm * v.bn < 256 * 128 && tiles <= num_cu() && kdepth >= 2048.0) eff *= 0.6;
     if (v.atr) eff *= 1.5;                              // likewise A; the alternative is the register-staged general tile
     if (v.dt == PEAK_DT_F32 && v.ns == 3) eff *= 0.97;
     const double fixed = 12.0e6;                    // prologue + epilogue of one tile, same units

@@ -95,6 +95,25 @@ def own_choice(dtype, transA, transB, M, N, K):
     return info.split("variant=")[1].split()[0].split(":", 1)[1], int(info.split("split=")[1].split()[0])
 
 
+def time_own(dtype, transA, transB, M, N, K, alpha=1.0, beta=0.0, reps=20, warmup=3):
+    """(us, plan info) of the plan the library makes by itself, timed like the sweep's settings.  A plan with
+    hybrid stream-K (only part of the tiles cut along K) has no forced counterpart in the sweep, and the
+    table's (variant, split) rows cannot ask for it."""
+    import torch
+    tdt = {pg.PEAK_DT_F32: torch.float32, pg.PEAK_DT_F16: torch.float16, pg.PEAK_DT_BF16: torch.bfloat16}[dtype]
+    scale = 1.0 / max(K, 1) ** 0.5
+    dA = (torch.randn((K, M) if transA else (M, K), device="cuda") * scale).to(tdt)
+    dB = (torch.randn((N, K) if transB else (K, N), device="cuda") * scale).to(tdt)
+    dC = torch.zeros((M, N), device="cuda", dtype=tdt)
+    with pg.Plan(M, N, K, dtype, transA, transB) as plan:
+        return time_setting(torch, plan, alpha, beta, dA, dB, dC, reps, warmup), plan.info()
+
+
+def is_streamk(info):
+    """True when the plan description says that part of the tiles are cut into K slices."""
+    return "streamk=" in info and int(info.split("streamk=")[1].split()[0]) > 0
+
+
 def pick(results, own, margin):
     """The row to write for a problem: the library's own choice when it is within `margin` of the
     fastest setting (differences that small are run-to-run noise, and a table that follows them
@@ -142,6 +161,13 @@ def main(argv=None):
     for dtype, ta, tb, M, N, K, alpha, beta in problems:
         log("%s transA=%d transB=%d %dx%dx%d" % (DT_OF[dtype], ta, tb, M, N, K))
         res = sweep(dtype, ta, tb, M, N, K, alpha, beta, args.reps, args.warmup, log=log)
+        own_us, own_info = time_own(dtype, ta, tb, M, N, K, alpha, beta, args.reps, args.warmup)
+        if is_streamk(own_info) and own_us <= res[0][0] * (1.0 + args.margin):
+            # a row would switch the stream-K plan off: leave the problem to the library's own choice
+            log("  own stream-K plan %.1f us, fastest forced setting %.1f us: no row" % (own_us, res[0][0]))
+            lines.append("# %s %d %d %d %d %d: the library's own stream-K plan (%.1f us) is left in place"
+                         % (DT_OF[dtype], ta, tb, M, N, K, own_us))
+            continue
         us, name, split = pick(res, own_choice(dtype, ta, tb, M, N, K), args.margin)
         log("  best: %s split=%d %.1f us (of %d settings; fastest %s split=%d %.1f us)" % ((name, split, us, len(res)) + (res[0][1], res[0][2], res[0][0])))
         lines.append(table_line(dtype, ta, tb, M, N, K, name, split, us))

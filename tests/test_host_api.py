@@ -217,6 +217,7 @@ def test_tuner_enumerates_only_accepted_settings():
     assert tune.pick(res, ("zz", 1), 0.015) == (10.0, "a", 1)
     own = tune.own_choice(pg.PEAK_DT_BF16, 0, 1, 8192, 8192, 8192)
     assert own == ("bf16_m256x256w4a3_nt", 1)
+    assert tune.is_streamk("variant=1:x split=4 grid=8 streamk=64 rot=0,0") and not tune.is_streamk("split=1 streamk=0 rot=0,0")
     line = tune.table_line(pg.PEAK_DT_BF16, 0, 1, 256, 512, 1024, "bf16_d256x256w8_nt", 4, 12.5)
     assert line.split()[:8] == ["bf16", "0", "1", "256", "512", "1024", "bf16_d256x256w8_nt", "4"]
 
