@@ -501,7 +501,7 @@ def main():
     if not args.only:
         others = []
         for name in ["C1", "C2", "C3b", "C4", "C5", "P2k_f32", "P4k_f32", "P2k_f16", "P4k_f16", "T4k_bf16_tn", "T4k_bf16_tt", "SK_bf16",
-                     "S32_bf16", "S64_f16", "S16_f32", "S16_bf16_kn", "S16_f32_kn", "D128_bf16"]:
+                     "S32_bf16", "S64_f16", "S16_f32", "S16_bf16_kn", "S16_f32_kn", "S32_f16_tn", "S16_bf16_tt", "D128_bf16"]:
             if name == args.workload:
                 continue
             small = pi.WORKLOADS[name].flops < 5e10          # short launches: more of them, or the figure is noise

@@ -104,9 +104,11 @@ typedef struct {
  */
 peak_status_t peak_gemm_create(const peak_gemm_desc_t *desc, peak_gemm_plan_t **out_plan);
 
-/* Bytes of device workspace peak_gemm_run needs for this plan (0 when K is not
- * split).  The workspace holds fp32 partial tiles of the Split-K step (Section
- * 4.1, Table 2). */
+/* Bytes of device workspace peak_gemm_run needs for this plan (0 for most
+ * plans that do not split K).  The workspace holds fp32 partial tiles of the
+ * Split-K step (Section 4.1, Table 2) and, for a streaming plan on an A stored
+ * K x M, the copy of A with rows along K that the run writes first (Section
+ * 4.1, Table 2, Transpose). */
 size_t peak_gemm_workspace_bytes(const peak_gemm_plan_t *plan);
 
 /*

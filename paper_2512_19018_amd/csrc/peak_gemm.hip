@@ -50,6 +50,25 @@ int planner_device_cu_count()
 using namespace peak;
 #define g_variants (variants())
 
+// A stored K x M (at most 64 columns) written out as M rows of K elements, for the streaming kernels,
+// which read their small operand along K.  One workgroup turns 64 k-rows around in LDS: reads run along
+// the rows of A, writes along K.
+template <class T>
+__global__ __launch_bounds__(256) void stage_a_kernel(const T *A, int64_t lda, T *dst, int M, int64_t K)
+{
+    __shared__ T tile[64][65];
+    const int64_t k0 = (int64_t)blockIdx.x * 64;
+    for (int idx = threadIdx.x; idx < 64 * M; idx += 256) {
+        const int k = idx / M, m = idx % M;
+        if (k0 + k < K) tile[k][m] = A[(k0 + k) * lda + m];
+    }
+    __syncthreads();
+    for (int idx = threadIdx.x; idx < 64 * M; idx += 256) {
+        const int m = idx / 64, k = idx % 64;
+        if (k0 + k < K) dst[(int64_t)m * K + k0 + k] = tile[k][m];
+    }
+}
+
 static int esize_of(int dt) { return dt == PEAK_DT_F32 ? 4 : 2; }
 static int64_t cdiv(int64_t a, int64_t b) { return (a + b - 1) / b; }
 
@@ -96,24 +115,38 @@ static peak_status_t run_plan(peak_gemm_plan_t *p, float alpha, const void *A, c
     if ((uintptr_t)A % es || (uintptr_t)B % es) return PEAK_ERR_INVALID_ARG;
     if (p->g.variant < 0) return PEAK_ERR_UNSUPPORTED;
 
-    const bool a_al = (uintptr_t)A % 16 == 0 && (d.lda * es) % 16 == 0;
+    // (a plan that stages A reads its own aligned copy, whatever the base and rows of A)
+    bool a_al = (uintptr_t)A % 16 == 0 && (d.lda * es) % 16 == 0;
     const bool b_al = (uintptr_t)B % 16 == 0 && (d.ldb * es) % 16 == 0;
-    if (a_al) a.flags |= GF_A_VEC;
-    if (b_al) a.flags |= GF_B_VEC;
     // the selected variant, or its stand-in when it copies 16-byte chunks and a base is off that alignment
     const Geometry *g = &p->g;
-    if (g_variants[g->variant].direct && !(a_al && b_al)) {
+    if (g_variants[g->variant].direct && !((a_al || g->a_copy) && b_al)) {
         if (p->alt.variant < 0) return PEAK_ERR_UNSUPPORTED;
         g = &p->alt;
     }
     const Variant &v = g_variants[g->variant];
 
-    if (g->split > 1) {
+    if (g->split > 1 || g->a_copy) {
         if (!workspace || workspace_bytes < g->ws_bytes) return PEAK_ERR_WORKSPACE;
         if ((uintptr_t)workspace % 256) return PEAK_ERR_INVALID_ARG;
+    }
+    if (g->split > 1) {
         a.ws = (float *)workspace;
         if (d.N % 4 == 0) a.flags |= GF_WS_VEC;
     }
+    if (g->a_copy) {
+        if (d.M > 64) return PEAK_ERR_UNSUPPORTED;          // (the planner admits no such plan)
+        void *copy = (char *)workspace + g->a_copy_off;
+        dim3 sgrid((unsigned)cdiv(d.K, 64));
+        if (es == 4) hipLaunchKernelGGL(stage_a_kernel<uint32_t>, sgrid, dim3(256), 0, stream, (const uint32_t *)A, d.lda, (uint32_t *)copy, (int)d.M, d.K);
+        else hipLaunchKernelGGL(stage_a_kernel<uint16_t>, sgrid, dim3(256), 0, stream, (const uint16_t *)A, d.lda, (uint16_t *)copy, (int)d.M, d.K);
+        if (hipGetLastError() != hipSuccess) return PEAK_ERR_HIP;
+        a.A = copy;
+        a.lda = d.K;
+        a_al = true;
+    }
+    if (a_al) a.flags |= GF_A_VEC;
+    if (b_al) a.flags |= GF_B_VEC;
 #ifdef PEAK_TRACE
     // diagnostic build: an unsplit run writes 64 bytes of time stamps per wave into the workspace, if one that large is given
     if (g->split == 1 && workspace && workspace_bytes >= (size_t)g->tiles_m * g->tiles_n * (v.nt / 64) * 64) a.ws = (float *)workspace;

@@ -49,10 +49,13 @@ static bool variant_fits(const Variant &v, const peak_gemm_desc_t &d)
     // layouts: kernel's A_T means A does not run along K, i.e. transA == 1;
     // kernel's B_T means B stored K x N, i.e. transB == 0
     const int a_t = d.transA ? 1 : 0, b_t = d.transB ? 0 : 1;
-    if (v.a_t != a_t || v.b_t != b_t) return false;
+    const bool a_copy = stages_a(v, d.transA);              // the kernel then reads a copy of A with rows of K elements
+    if ((v.a_t != a_t && !a_copy) || v.b_t != b_t) return false;
     if (v.kind != KIND_TILED && d.M > v.max_m) return false;
+    if (a_copy && (!v.direct || d.M > 64)) return false;
     if (v.direct) {
         const int es = esize_of(d.dtype);
+        const int64_t lda = a_copy ? d.K : d.lda;
         const bool a_along_k = !v.a_t, b_along_k = !v.b_t;      // copied in 16-byte chunks along K
         if (v.kind == KIND_TILED) {
             // K may stop inside the last K tile: at a 16-byte chunk boundary for an operand that
@@ -64,10 +67,10 @@ static bool variant_fits(const Variant &v, const peak_gemm_desc_t &d)
             if (d.K % v.bk != 0 || d.K < v.bk) return false;
             if (v.tr && (d.N * es) % 16 != 0) return false;
         }
-        if ((d.lda * es) % 16 != 0 || (d.ldb * es) % 16 != 0) return false;
+        if ((lda * es) % 16 != 0 || (d.ldb * es) % 16 != 0) return false;
         // a workgroup's operand panel is addressed with 32-bit byte offsets
         const int64_t lim = (int64_t)1 << 31;
-        if (v.atr ? ((d.K - 1) * d.lda + d.M) * es >= lim : a_along_k && ((int64_t)(v.bm - 1) * d.lda + d.K) * es >= lim) return false;
+        if (v.atr ? ((d.K - 1) * lda + d.M) * es >= lim : a_along_k && ((int64_t)(v.bm - 1) * lda + d.K) * es >= lim) return false;
         if (v.tr ? ((d.K - 1) * d.ldb + d.N) * es >= lim : b_along_k && ((int64_t)(v.bn - 1) * d.ldb + d.K) * es >= lim) return false;
     }
     return true;
@@ -223,6 +226,12 @@ static void plan_geometry(Geometry *p, const peak_gemm_desc_t &d, int variant, i
         if (sscanf(e, "%d,%d", &a, &b) == 2 && a >= 0 && b >= 0) { p->rot_m = a; p->rot_n = b; }
     }
     p->ws_bytes = p->split > 1 ? (size_t)p->split * (size_t)d.M * (size_t)d.N * sizeof(float) : 0;
+    p->a_copy = stages_a(v, d.transA) ? 1 : 0;
+    p->a_copy_off = 0;
+    if (p->a_copy) {                                        // behind the partials, on a 256-byte boundary
+        p->a_copy_off = (p->ws_bytes + 255) & ~(size_t)255;
+        p->ws_bytes = p->a_copy_off + (((size_t)d.M * (size_t)d.K * esize_of(d.dtype) + 255) & ~(size_t)255);
+    }
     // hybrid stream-K where nothing forces a K split: PEAK_GEMM_STREAMK_ON / _OFF decide, else the cost model
     if (forced_split <= 0 && p->split == 1 && streamk >= 0) {
         int sk_tiles = 0;
@@ -247,6 +256,7 @@ static int select_variant(const peak_gemm_desc_t &d, bool staged_only)
     for (int i = 0; i < NUM_VARIANTS; ++i) {
         const Variant &v = g_variants[i];
         if (v.kind == KIND_TILED || v.sweep_only || (staged_only && v.direct) || !variant_fits(v, d)) continue;
+        if (stages_a(v, d.transA) && d.N * d.K * esize_of(d.dtype) < ((int64_t)8 << 20)) continue;
         if (stream_bm == 0 || v.bm < stream_bm) stream_bm = v.bm;
     }
     for (int i = 0; i < NUM_VARIANTS; ++i) {
@@ -254,6 +264,8 @@ static int select_variant(const peak_gemm_desc_t &d, bool staged_only)
         if (v.sweep_only || (staged_only && v.direct) || !variant_fits(v, d)) continue;
         if (v.kind != KIND_TILED) {
             if (v.bm != stream_bm) continue;
+            // the transposition of A is one more launch: worth it once the streamed operand has some MB
+            if (stages_a(v, d.transA) && d.N * d.K * esize_of(d.dtype) < ((int64_t)8 << 20)) continue;
             // rank 3 only where one workgroup per tile of its (larger) BN fills four fifths of the chip, or where
             // the M x K operand is tall enough for its re-reads to matter (every workgroup reads its K slice of
             // all of it: bf16 64x8192x28672 takes 101.9 us with 128 rows per workgroup, 126.4 us with 64)
@@ -504,10 +516,10 @@ int peak_gemm_plan_info(const peak_gemm_plan_t *p, char *buf, size_t n)
     const Variant &v = g_variants[g.variant];
     return snprintf(buf, n,
                     "variant=%d:%s tile=%dx%dx%d threads=%d stages=%d lds=%d split=%d ktiles/slice=%d "
-                    "grid=%lld (tiles %dx%d) group_m=%d workspace=%zu unaligned=%s streamk=%d rot=%d,%d",
+                    "grid=%lld (tiles %dx%d) group_m=%d workspace=%zu unaligned=%s streamk=%d rot=%d,%d acopy=%d",
                     g.variant, v.name, v.bm, v.bn, v.bk, v.nt, v.ns, v.lds, g.split, g.ktiles_per_slice,
                     (long long)grid_blocks(g), g.tiles_m, g.tiles_n, g.group_m, p->ws_bytes,
-                    p->alt.variant >= 0 ? g_variants[p->alt.variant].name : "same", g.sk_tiles, g.rot_m, g.rot_n);
+                    p->alt.variant >= 0 ? g_variants[p->alt.variant].name : "same", g.sk_tiles, g.rot_m, g.rot_n, g.a_copy);
 }
 
 peak_status_t peak_gemm_destroy(peak_gemm_plan_t *plan)

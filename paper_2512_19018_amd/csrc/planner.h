@@ -50,8 +50,15 @@ struct Geometry {
     int variant;          // index into the variant table, -1: nothing to launch
     int tiles_m, tiles_n, split, ktiles_total, ktiles_per_slice, group_m, rot_m, rot_n;
     int sk_tiles;         // hybrid stream-K: tiles of the last, partial round that are cut into `split` K slices; 0: off
+    int a_copy;           // streaming kernel on an A stored K x M: A is first written out along K (M rows of K
+                          // elements) at a_copy_off of the workspace, and the kernel reads that
+    size_t a_copy_off;
     size_t ws_bytes;
 };
+
+// A streaming kernel built for A along K also serves an A stored K x M (at most 64 columns): the run
+// transposes A into the workspace first, a few MB against the K x N operand the kernel then streams.
+static inline bool stages_a(const Variant &v, int transA) { return v.kind == KIND_SKINNY && !v.a_t && transA; }
 
 // workgroups of the GEMM launch
 int64_t grid_blocks(const Geometry &g);

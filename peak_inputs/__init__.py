@@ -236,6 +236,11 @@ WORKLOADS = {
                             "bf16 skinny 16x28672x8192 NN, B stored K x N (HBM bound)"),
     "S16_f32_kn": Workload("S16_f32_kn", F32, 16, 28672, 8192, 0, 0, 1.0, 0.0, "normal", 0.02, 16,
                            "fp32 skinny 16x28672x8192 NN, B stored K x N (HBM bound)"),
+    # ... and with the small operand stored K x M (the streaming kernels read a copy written out along K)
+    "S32_f16_tn": Workload("S32_f16_tn", F16, 32, 28672, 8192, 1, 0, 1.0, 0.0, "normal", 0.02, 18,
+                           "f16 skinny 32x28672x8192 TN, A stored K x M, B stored K x N (HBM bound)"),
+    "S16_bf16_tt": Workload("S16_bf16_tt", BF16, 16, 16384, 16384, 1, 1, 1.0, 0.0, "normal", 0.02, 19,
+                            "bf16 skinny 16x16384x16384 TT, A stored K x M (HBM bound)"),
     # one row of 128 x 128 tiles, B streamed from HBM by the tiled kernel (128 k per stage)
     "D128_bf16": Workload("D128_bf16", BF16, 128, 28672, 8192, 0, 1, 1.0, 0.0, "normal", 0.02, 17,
                           "bf16 128x28672x8192 NT (one row of tiles, HBM bound)"),

@@ -368,3 +368,68 @@ def test_operand_base_off_16_bytes_with_aligned_rows(gu, oracle, dtype):
                     got = pi.to_f64(np.ascontiguousarray(raw[:M, :N]), dtype)
                     gu.check_against_oracle(oracle, got, dtype, transA, transB, M, N, K, 0.5, A, B, 2.0, C,
                                             what=(info, transA, transB, off_a, off_b))
+
+
+@pytest.mark.parametrize("dtype", DTYPES)
+@pytest.mark.parametrize("transB", [0, 1])
+def test_streaming_variants_with_a_stored_k_by_m(gu, oracle, dtype, transB):
+    """Every streaming variant on an A stored K x M: the run first writes A out along K
+    into the workspace (behind the Split-K partials) and the kernel reads that copy.
+    Exact integers over many K tiles, split and unsplit, odd leading dimension of A (the
+    copy is aligned whatever A's rows are), A's base one element into its allocation, a K
+    that is not a whole number of 64-row blocks of the transposition; then random data
+    against the per-element bound.  Padding of C must stay untouched."""
+    limit = {pi.F32: 2 ** 24, pi.F16: 2048, pi.BF16: 256}[dtype]
+    es = pi.DTYPE_SIZE[dtype]
+    for vid, name in gu.variants_for(dtype, 0, transB):
+        if "skinny" not in name or "skinnyreg" in name:
+            continue
+        m = re.search(r"k(\d+)s", name)
+        ks = int(m.group(1)) if m else 128
+        mm = _skinny_max_m(name)
+        n2 = 1000 if transB else 1032                       # B as [k][n] rows: N a whole number of 16-byte chunks
+        for case, (M, N, K, pad_a, a_off) in enumerate([(mm, 264, min(16 * ks, 4096), 0, 0), (mm - 3, n2, 4096 + ks, 3, 0),
+                                                        (1, 264, 8 * ks, 5, 1)]):
+            A, B, C = _stored(9000 + vid * 4 + case, dtype, M, N, K, 1, transB, pad=(pad_a, 0, 7), ints=True, amp=1)
+            ref = oracle.gemm(dtype, 1, transB, M, N, K, 1.0, A, B, 1.0, C)
+            assert np.abs(ref).max() <= limit
+            # a base one element in: the same values, shifted by one element in a longer allocation
+            Adev = A if not a_off else np.concatenate([np.zeros(1, A.dtype), A.reshape(-1)]).reshape(1, -1)
+            for split in (None, 3):
+                if a_off:
+                    # run_gemm takes the leading dimension from the array's row length: hand it the flat copy by hand
+                    import torch
+                    dA, dB, dC = gu.to_dev(Adev), gu.to_dev(B), gu.to_dev(C)
+                    with gu.pg.Plan(M, N, K, dtype, 1, transB, A.shape[1], B.shape[1], C.shape[1],
+                                    gu.pg.force_flags(variant=vid, split=split)) as plan:
+                        info = plan.info()
+                        ws = torch.empty(max(plan.workspace_bytes, 256), dtype=torch.uint8, device="cuda")
+                        plan.run(1.0, dA.data_ptr() + es, dB.data_ptr(), 1.0, dC.data_ptr(), ws.data_ptr(),
+                                 plan.workspace_bytes, torch.cuda.current_stream().cuda_stream)
+                        torch.cuda.synchronize()
+                    raw = gu.from_dev(dC, dtype)
+                    got = pi.to_f64(np.ascontiguousarray(raw[:M, :N]), dtype)
+                else:
+                    got, raw, info = gu.run_gemm(dtype, 1, transB, M, N, K, 1.0, 1.0, A, B, C,
+                                                 flags=gu.pg.force_flags(variant=vid, split=split))
+                assert name in info and info.endswith("acopy=1"), info
+                assert np.array_equal(got, ref), (info, M, N, K, int((got != ref).sum()))
+                _check_padding(raw, C, M, N)
+        M, N, K = mm - 5 if mm > 16 else 13, n2, 2048
+        A, B, C = _stored(9500 + vid, dtype, M, N, K, 1, transB, pad=(1, 0, 0))
+        got, raw, info = gu.run_gemm(dtype, 1, transB, M, N, K, 0.5, -0.75, A, B, C, flags=gu.pg.force_flags(variant=vid))
+        assert info.endswith("acopy=1"), info
+        gu.check_against_oracle(oracle, got, dtype, 1, transB, M, N, K, 0.5, A, B, -0.75, C, what=(info, M, N, K))
+    # the selector's own plan for a streamed operand of some MB, and the workspace check of the run
+    M, N, K = 24, 4104 if transB else 4096, 2048
+    A, B, C = _stored(9900, dtype, M, N, K, 1, transB)
+    got, raw, info = gu.run_gemm(dtype, 1, transB, M, N, K, 1.0, 0.0, A, B, gu.nan_fill(M, N, dtype))
+    assert "skinny" in info and info.endswith("acopy=1"), info
+    gu.check_against_oracle(oracle, got, dtype, 1, transB, M, N, K, 1.0, A, B, 0.0, C, what=(info, M, N, K))
+    import torch
+    with gu.pg.Plan(M, N, K, dtype, 1, transB) as plan:
+        assert plan.workspace_bytes >= M * K * es
+        dA, dB, dC = gu.to_dev(A), gu.to_dev(B), gu.to_dev(C)
+        with pytest.raises(gu.pg.PeakError) as e:
+            plan.run(1.0, dA.data_ptr(), dB.data_ptr(), 0.0, dC.data_ptr(), 0, 0, torch.cuda.current_stream().cuda_stream)
+        assert e.value.status == gu.pg.PEAK_ERR_WORKSPACE

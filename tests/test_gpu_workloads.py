@@ -42,6 +42,8 @@ CASES = [("C1", 256, None), ("C2", 2, None), ("C3", 3, None), ("C3b", 3, None), 
          # the streaming path beyond M <= 16 / 16 bits / B along K: every row
          ("S32_bf16", 32, None), ("S64_f16", 64, None), ("S16_f32", 16, None), ("S16_bf16_kn", 16, None),
          ("S16_f32_kn", 16, None),
+         # ... and with A stored K x M: the run writes A out along K first
+         ("S32_f16_tn", 32, None), ("S16_bf16_tt", 16, None),
          # one row of tiles of the 16x16x32 kernels: workgroups start at different K tiles
          ("D128_bf16", 24, None)]
 
@@ -56,8 +58,10 @@ def test_workload_against_oracle(gu, oracle, name, per_tile_row, split):
     print(name, info)
     if name.startswith("S") and name != "SK_bf16":
         assert "skinny" in info, info
+    if name in ("S32_f16_tn", "S16_bf16_tt"):
+        assert info.endswith("acopy=1"), info
     if name == "D128_bf16":
-        assert "_m128x128" in info and info.endswith("rot=0,1"), info
+        assert "_m128x128" in info and " rot=0,1 " in info, info
     if split is not None:
         assert "split=%d" % split in info, info
     rows = _sample_rows(w.M, info, per_tile_row, 7)

@@ -405,8 +405,15 @@ def test_streaming_plans_cover_m_up_to_64_fp32_and_b_stored_k_by_n():
     assert "f32_skinny_m32n128k32s6_nn" in info(20, 16384, 8192, f32, 0, 0)
     assert "skinny" not in info(16, 28668, 8192, bf, 0, 0)            # N not a whole number of 16-byte chunks
     assert "skinny" not in info(16, 28672, 8200, bf, 0, 0)            # K not a whole number of stages
-    # A stored K x M: no streaming kernel
-    assert "skinny" not in info(16, 28672, 8192, bf, 1, 1) and "skinny" not in info(16, 28672, 8192, bf, 1, 0)
+    # A stored K x M: the same kernels on a copy of A written out along K, which the workspace holds
+    # behind the Split-K partials (256-byte boundary); not for a streamed operand of a few MB
+    tt, tn = info(16, 28672, 8192, bf, 1, 1), info(40, 28672, 8192, f32, 1, 0)
+    assert "bf16_skinny" in tt and tt.endswith("acopy=1") and "f32_skinny_m64n128k32s6_nn" in tn and tn.endswith("acopy=1")
+    assert info(16, 28672, 8192, bf, 0, 1).endswith("acopy=0")
+    with pg.Plan(16, 28672, 8192, bf, 1, 1, flags=pg.force_flags(split=2)) as p:
+        assert p.info().endswith("acopy=1") and p.workspace_bytes >= 2 * 16 * 28672 * 4 + 16 * 8192 * 2
+    assert "skinny" not in info(16, 1024, 1024, bf, 1, 1) and "skinny" not in info(65, 28672, 8192, bf, 1, 1)
+    assert "skinny" not in info(16, 28672, 8200, bf, 1, 1)
 
 
 def test_tile_order_and_k_rotation_of_the_plans():
@@ -418,10 +425,10 @@ def test_tile_order_and_k_rotation_of_the_plans():
             return p.info()
     bf, f16 = pg.PEAK_DT_BF16, pg.PEAK_DT_F16
     c3 = info(8192, 8192, 8192, bf, 0, 1)
-    assert "group_m=4 " in c3 and c3.endswith("rot=0,0")
+    assert "group_m=4 " in c3 and " rot=0,0 " in c3
     c4 = info(5000, 3000, 12288, f16, 0, 0)
-    assert "group_m=8 " in c4 and c4.endswith("rot=0,0")
+    assert "group_m=8 " in c4 and " rot=0,0 " in c4
     single = info(128, 28672, 8192, bf, 0, 1)
-    assert "_m128x128" in single and "(tiles 1x224)" in single and single.endswith("rot=0,1")
-    assert info(16, 16384, 16384, bf, 0, 1).endswith("rot=0,5")
-    assert info(16, 28672, 8192, bf, 0, 0).endswith("rot=0,0")        # B stored K x N: contiguous pieces of a k-row
+    assert "_m128x128" in single and "(tiles 1x224)" in single and " rot=0,1 " in single
+    assert " rot=0,5 " in info(16, 16384, 16384, bf, 0, 1)
+    assert " rot=0,0 " in info(16, 28672, 8192, bf, 0, 0)        # B stored K x N: contiguous pieces of a k-row
