@@ -193,7 +193,7 @@ peak_status_t peak_gemm_run_fused(peak_gemm_plan_t *plan, float alpha,
  * peak_gemm_run for callers that cannot allocate device memory or pass a
  * workspace: code under HIP graph capture, tight serving loops, harnesses that
  * forbid hipMalloc.  Same plan, same kernels, same result bits as peak_gemm_run;
- * the Split-K partials go to an array of PEAK_GEMM_STATIC_WORKSPACE_BYTES that
+ * what the workspace would hold goes to an array of PEAK_GEMM_STATIC_WORKSPACE_BYTES that
  * is part of the library's device code (every GPU the library runs on holds
  * its own copy until the process ends).  The call allocates nothing.
  *

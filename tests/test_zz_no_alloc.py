@@ -1,6 +1,6 @@
 """peak_gemm_run_static: the entry point for callers that cannot allocate or pass
-a workspace (the K-split partials go to an array inside the library's device
-code).  Its output must equal peak_gemm_run's bit for bit (same plan, same
+a workspace (the K-split partials, and the copy of an A stored K x M that a
+streaming plan makes, go to an array inside the library's device code).  Its output must equal peak_gemm_run's bit for bit (same plan, same
 kernels), on two calls in a row, the second on a smaller problem, so that what
 the first call left in the shared array is still there when the second runs."""
 import numpy as np
@@ -19,18 +19,19 @@ def gu():
     return gpu_util
 
 
-def _case(gu, oracle, dtype, M, N, K, split, seed):
+def _case(gu, oracle, dtype, M, N, K, split, seed, transA=0):
     import torch
     pg = gu.pg
     la = pi.logical_matrix(seed, 0, M, K, "normal", 1.0 / np.sqrt(K), dtype)
     lb = pi.logical_matrix(seed, 1, K, N, "normal", 1.0, dtype)
     lc = pi.logical_matrix(seed, 2, M, N, "uniform", 1.0, dtype)
-    A, B = pi.store(la, False), pi.store(lb, True)
+    A, B = pi.store(la, bool(transA)), pi.store(lb, True)
     stream = torch.cuda.current_stream().cuda_stream
     dA, dB = gu.to_dev(A), gu.to_dev(B)
-    with pg.Plan(M, N, K, dtype, 0, 1, flags=pg.force_flags(split=split)) as plan:
+    with pg.Plan(M, N, K, dtype, transA, 1, flags=pg.force_flags(split=split)) as plan:
         info = plan.info()
         assert "split=%d " % split in info, info
+        assert info.endswith("acopy=%d" % transA), info
         assert 0 < plan.workspace_bytes <= pg.PEAK_GEMM_STATIC_WORKSPACE_BYTES
         # the existing entry point, workspace from the caller
         dC1 = gu.to_dev(lc)
@@ -45,7 +46,7 @@ def _case(gu, oracle, dtype, M, N, K, split, seed):
     r1, r2 = gu.from_dev(dC1, dtype), gu.from_dev(dC2, dtype)
     assert np.array_equal(r1.view(np.uint8), r2.view(np.uint8)), info
     got = pi.to_f64(np.ascontiguousarray(r2[:M, :N]), dtype)
-    gu.check_against_oracle(oracle, got, dtype, 0, 1, M, N, K, 0.75, A, B, -0.5, lc, what=info)
+    gu.check_against_oracle(oracle, got, dtype, transA, 1, M, N, K, 0.75, A, B, -0.5, lc, what=info)
 
 
 def test_static_workspace_entry_point_two_calls_in_a_row(gu, oracle):
@@ -54,6 +55,7 @@ def test_static_workspace_entry_point_two_calls_in_a_row(gu, oracle):
     _case(gu, oracle, pi.BF16, 200, 136, 2048, 3, 32)
     _case(gu, oracle, pi.F32, 130, 264, 1024, 4, 33)
     _case(gu, oracle, pi.BF16, 16, 520, 4096, 2, 34)            # streaming kernel with a K split
+    _case(gu, oracle, pi.F16, 24, 4104, 2048, 2, 35, transA=1)  # ... on an A stored K x M: partials and the copy of A
 
 
 def test_static_workspace_entry_point_limits(gu):
