@@ -15,17 +15,26 @@ namespace peak {
 
 // MBLK: 16-row blocks of the M x K operand (M <= 16 * MBLK); each wave multiplies all of them
 // with its 16 rows of the other operand.
-template <int DT_, int BN_, int KSTEP_, int NS_, int MBLK_ = 1>
+// KW: waves per 16 rows of the N x K operand.  With 2, the two take the even and the odd rounds of
+// fragment reads of every stage and their sums are added in LDS at the end (even rounds first): where
+// the MFMAs are the bound (fp32 with several blocks) a SIMD then has a second wave to issue from while
+// the first waits for its fragments.
+// PIPE: the loop is software-pipelined across the stage's barrier (see the kernel).
+template <int DT_, int BN_, int KSTEP_, int NS_, int MBLK_ = 1, int KW_ = 1, int PIPE_ = 0>
 struct SkinnyCfg {
     static constexpr int DT = DT_;
+    static constexpr bool PIPE = PIPE_ != 0;
     static constexpr int ESZ = DT_ == DT_F32 ? 4 : 2, EPC = 16 / ESZ;
-    static constexpr int MBLK = MBLK_;
+    static constexpr int MBLK = MBLK_, KW = KW_;
     static constexpr int KMMA = 4 * EPC;                  // k per round of fragment reads: 4 chunks of 16 bytes
     static constexpr int BM = 16 * MBLK_, BN = BN_, KSTEP = KSTEP_, NS = NS_;
     static constexpr int RB = KSTEP_ * ESZ;               // bytes per tile row and stage
     static constexpr int CPR = RB / 16;                   // 16-byte chunks per tile row
-    static constexpr int NW = BN_ / 16;                   // one wave per 16 rows of the N x K operand
+    static constexpr int NWC = BN_ / 16;                  // wave columns: one per 16 rows of the N x K operand
+    static constexpr int NW = NWC * KW_;
     static constexpr int NT = NW * 64;
+    static_assert(KW_ == 1 || (KW_ == 2 && (KSTEP_ / KMMA) % 2 == 0), "one or two waves per 16 rows; an even number of rounds per stage");
+    static_assert(KW_ == 1 || NWC * MBLK_ * 1024 <= (BM + BN_) * RB, "the odd waves' sums fit the first stage");
     static constexpr int A_BYTES = BM * RB, B_BYTES = BN_ * RB;
     static constexpr int STAGE_BYTES = A_BYTES + B_BYTES;
     static constexpr int LDS_BYTES = STAGE_BYTES * NS_;
@@ -106,15 +115,97 @@ __global__ __launch_bounds__(C::NT) void skinny_kernel(const GemmArgs p)
 
     // fragment addresses: lane reads tile row (lane % 16), chunk 4*kg + lane/16
     const int r16 = lane & 15, q = lane >> 4;
+    const int wcol = C::KW == 1 ? wave : wave % C::NWC;        // which 16 rows of the N x K operand
+    const int kpar = C::KW == 1 ? 0 : wave / C::NWC;           // which rounds of a stage: kg = KW * i + kpar
     const int a_row = r16 * C::RB;
-    const int b_row = C::A_BYTES + (wave * 16 + r16) * C::RB;
-    const int a_sw = r16, b_sw = (wave * 16 + r16) & 15;       // both equal r16; kept apart for clarity
+    const int b_row = C::A_BYTES + (wcol * 16 + r16) * C::RB;
+    const int a_sw = r16, b_sw = (wcol * 16 + r16) & 15;       // both equal r16; kept apart for clarity
 
     typedef float f32x4v __attribute__((ext_vector_type(4)));
     f32x4v acc[C::MBLK];
 #pragma unroll
     for (int mb = 0; mb < C::MBLK; ++mb) acc[mb] = f32x4v{0.0f, 0.0f, 0.0f, 0.0f};
 
+    if constexpr (C::PIPE) {
+        // Where the MFMAs are the bound, the stage's barrier must not drain the matrix pipe: the fragments of a
+        // stage's last round are read before the barrier, and that round's MFMAs are issued after it, one between
+        // each two of what the barrier releases - the loads that refill this very stage (every wave has its last
+        // fragments in registers, so the stage is free) and the reads of the next stage's first fragments.
+        constexpr int G = C::KSTEP / C::KMMA / C::KW;       // rounds per stage and wave
+        static_assert(G % 2 == 0, "two fragment sets take turns: an even number of rounds per stage");
+        constexpr int NFR = 1 + C::MBLK;                     // fragment reads per round
+        constexpr int NMF = C::DT == DT_F32 ? 4 * C::MBLK : C::MBLK;   // MFMAs per round
+        u32x4 bfr[2], afr[2][C::MBLK];
+        auto read_one = [&](const char *st, int kg, int f, u32x4 &bf, u32x4 (&af)[C::MBLK]) {
+            const int c = (kg * C::KW + kpar) * 4 + q;
+            if (f == 0) bf = *(const u32x4 *)(st + b_row + (((c & ~15) | ((c & 15) ^ b_sw)) << 4));
+            else af[f - 1] = *(const u32x4 *)(st + a_row + (f - 1) * 16 * C::RB + (((c & ~15) | ((c & 15) ^ a_sw)) << 4));
+        };
+        auto mfma_one = [&](int j, const u32x4 &bf, const u32x4 (&af)[C::MBLK]) {
+            if constexpr (C::DT == DT_F32) {
+                const int e = j / C::MBLK, mb = j % C::MBLK;          // the blocks take turns
+                const uint32_t be = bf[e], ae = af[mb][e];
+                acc[mb] = __builtin_amdgcn_mfma_f32_16x16x4f32(__builtin_bit_cast(float, be), __builtin_bit_cast(float, ae), acc[mb], 0, 0, 0);
+            } else if constexpr (C::DT == DT_BF16) {
+                acc[j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, bf), __builtin_bit_cast(bf16x8, af[j]), acc[j], 0, 0, 0);
+            } else {
+                acc[j] = __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(f16x8, bf), __builtin_bit_cast(f16x8, af[j]), acc[j], 0, 0, 0);
+            }
+        };
+        auto issue_one = [&](int kc, int stage, int i) {
+            char *st = lds + stage * C::STAGE_BYTES;
+            if (i < C::A_PER_WAVE)
+                __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)(ga[i] + (int64_t)kc * C::RB),
+                                                 (__attribute__((address_space(3))) void *)(st + ja[i] * 1024), 16, 0, 0);
+            else
+                __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)(gb[i - C::A_PER_WAVE] + (int64_t)kc * C::RB),
+                                                 (__attribute__((address_space(3))) void *)(st + C::A_BYTES + jb[i - C::A_PER_WAVE] * 1024), 16, 0, 0);
+        };
+#pragma unroll
+        for (int s = 0; s < C::NS; ++s) issue(s, s);       // every stage of the ring
+        wait_vmcnt<(C::NS - 1) * C::DLOADS>();
+        lds_barrier();
+#pragma unroll
+        for (int f = 0; f < NFR; ++f) read_one(lds, 0, f, bfr[0], afr[0]);
+        for (int kt0 = 0; kt0 < KT; kt0 += C::NS) {
+#pragma unroll
+            for (int s = 0; s < C::NS; ++s) {
+                const int kt = kt0 + s;
+                if (kt < KT) {
+                    const char *st = lds + s * C::STAGE_BYTES;
+#pragma unroll
+                    for (int kg = 0; kg + 1 < G; ++kg) {
+                        // the next round's fragments behind this round's first MFMAs, so that nothing waits for them
+                        constexpr int NS1 = NMF > NFR ? NMF : NFR;
+                        __builtin_amdgcn_sched_barrier(0);       // (... or lift one above the wait for this round's)
+#pragma unroll
+                        for (int j = 0; j < NS1; ++j) {
+                            if (j < NMF) mfma_one(j, bfr[kg & 1], afr[kg & 1]);
+                            if (j < NFR) {
+                                read_one(st, kg + 1, j, bfr[(kg + 1) & 1], afr[(kg + 1) & 1]);
+                                __builtin_amdgcn_sched_barrier(0);   // (the compiler would sink the reads to the round's end)
+                            }
+                        }
+                    }
+                    __builtin_amdgcn_sched_barrier(0);       // (this round's MFMAs stay ahead of the barrier: they cover its reads)
+                    wait_vmcnt<(C::NS - 2) * C::DLOADS>();   // tile kt + 1 has landed (this wave's part)
+                    lds_barrier();                           // ... everybody's, and nobody reads this stage any more
+                    int kc = (kt + C::NS < KT ? kt + C::NS : KT - 1) + rot;   // past the end: refetch the last tile
+                    if (kc >= KT) kc -= KT;
+                    const char *stn = lds + ((s + 1) % C::NS) * C::STAGE_BYTES;
+                    constexpr int NSLOT = NMF > C::DLOADS + NFR ? NMF : C::DLOADS + NFR;
+                    __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+                    for (int j = 0; j < NSLOT; ++j) {
+                        if (j < NMF) mfma_one(j, bfr[(G - 1) & 1], afr[(G - 1) & 1]);
+                        if (j < NFR) read_one(stn, 0, j, bfr[0], afr[0]);
+                        else if (j - NFR < C::DLOADS) issue_one(kc, s, j - NFR);
+                        if (j < NFR + C::DLOADS) __builtin_amdgcn_sched_barrier(0);
+                    }
+                }
+            }
+        }
+    } else {
     constexpr int P = C::NS - 1;
 #pragma unroll
     for (int s = 0; s < P; ++s) issue(s, s);
@@ -129,8 +220,8 @@ __global__ __launch_bounds__(C::NT) void skinny_kernel(const GemmArgs p)
                 issue(kt + P, (s + P) % C::NS);
                 const char *st = lds + s * C::STAGE_BYTES;
 #pragma unroll
-                for (int kg = 0; kg < C::KSTEP / C::KMMA; ++kg) {
-                    const int c = kg * 4 + q;
+                for (int kg = 0; kg < C::KSTEP / C::KMMA / C::KW; ++kg) {
+                    const int c = (kg * C::KW + kpar) * 4 + q;
                     const u32x4 bf = *(const u32x4 *)(st + b_row + (((c & ~15) | ((c & 15) ^ b_sw)) << 4));
                     u32x4 af[C::MBLK];
 #pragma unroll
@@ -163,10 +254,25 @@ __global__ __launch_bounds__(C::NT) void skinny_kernel(const GemmArgs p)
             }
         }
     }
+    }
     wait_vmcnt<0>();        // the refetches past the end must land before this workgroup's LDS is given away
 
-    // acc[mb][v] <-> m = 16*mb + lane % 16, n = n0 + wave*16 + 4*(lane/16) + v
-    const int64_t n = n0 + wave * 16 + q * 4;
+    if constexpr (C::KW == 2) {
+        // the odd rounds' sums go through LDS to the wave that holds the even rounds' and stores
+        lds_barrier();                                      // every wave is through its last stage, no load is under way
+        f32x4v *red = (f32x4v *)lds + (wcol * C::MBLK) * 64 + lane;
+        if (kpar == 1) {
+#pragma unroll
+            for (int mb = 0; mb < C::MBLK; ++mb) red[mb * 64] = acc[mb];
+        }
+        lds_barrier();
+        if (kpar == 1) return;
+#pragma unroll
+        for (int mb = 0; mb < C::MBLK; ++mb) acc[mb] += red[mb * 64];
+    }
+
+    // acc[mb][v] <-> m = 16*mb + lane % 16, n = n0 + wcol*16 + 4*(lane/16) + v
+    const int64_t n = n0 + wcol * 16 + q * 4;
     const int64_t left = p.N - n;
 #pragma unroll
     for (int mb = 0; mb < C::MBLK; ++mb) {

@@ -41,6 +41,12 @@ static int launch_skinny_kn(const GemmArgs &a, unsigned grid, void *stream)
      SkinnyCfg<DT, BN, KSTEP, NS, MBLK>::LDS_BYTES, 16 * MBLK,                                         \
      &launch_skinny<SkinnyCfg<DT, BN, KSTEP, NS, MBLK>>, 0, 0, RANK == 0, RANK}
 
+// ... with the loop pipelined across the stage's barrier (KW waves per 16 rows)
+#define SKINNY_MP(NAME, DT, BN, KSTEP, NS, MBLK, KW, RANK)                                             \
+    {NAME, KIND_SKINNY, DT, 0, 0, 1, 16 * MBLK, BN, KSTEP, SkinnyCfg<DT, BN, KSTEP, NS, MBLK, KW, 1>::NT, NS, \
+     SkinnyCfg<DT, BN, KSTEP, NS, MBLK, KW, 1>::LDS_BYTES, 16 * MBLK,                                  \
+     &launch_skinny<SkinnyCfg<DT, BN, KSTEP, NS, MBLK, KW, 1>>, 0, 0, RANK == 0, RANK}
+
 #define SKINNY_REG(NAME, DT, DEPTH, WAVES, RANK)                                                       \
     {NAME, KIND_SKINNY_REG, DT, 0, 0, 1, 16, 16, 64, WAVES * 64, DEPTH, 0, 16,                         \
      &launch_skinny_reg<SkinnyRegCfg<DT, DEPTH, WAVES>>, 0, 0, RANK == 0, RANK}
@@ -50,6 +56,7 @@ static const Variant rows_skinny[] = {
     // 64 rows x 128 k, three stages: the selector's usual choice (K a multiple of 128)
     SKINNY("bf16_skinny16s3_nt", DT_BF16, 64, 128, 3, 2),
     SKINNY("f16_skinny16s3_nt", DT_F16, 64, 128, 3, 2),
+    // (the loop pipelined across the barrier, as for fp32 below, changes nothing here: 86.0 us against 85.9)
     SKINNY("bf16_skinny32k512s3_nt", DT_BF16, 32, 512, 3, 0),
     SKINNY("f16_skinny32k512s3_nt", DT_F16, 32, 512, 3, 0),
     SKINNY("bf16_skinny64k256s3_nt", DT_BF16, 64, 256, 3, 0),
@@ -82,12 +89,18 @@ static const Variant rows_skinny[] = {
     SKINNY_M("f16_skinny_m32n64k128s3_nt", DT_F16, 64, 128, 3, 2, 2),
     SKINNY_M("bf16_skinny_m32n128k128s3_nt", DT_BF16, 128, 128, 3, 2, 3),
     SKINNY_M("f16_skinny_m32n128k128s3_nt", DT_F16, 128, 128, 3, 2, 3),
-    SKINNY_M("f32_skinny_m32n64k64s3_nt", DT_F32, 64, 64, 3, 2, 2),
+    // fp32 with several blocks is bound by the MFMAs: two waves per 16 rows and the loop pipelined across the stage's
+    // barrier (64x16384x8192: 154.6 us against 174; 48x28672x8192: 275 against 314; 32x16384x8192: 93.9 against 104.7)
+    SKINNY_MP("f32_skinny_m32n64k64s3w8p_nt", DT_F32, 64, 64, 3, 2, 2, 2),
+    SKINNY_MP("f32_skinny_m32n64k64s3p_nt", DT_F32, 64, 64, 3, 2, 1, 0),
+    SKINNY_M("f32_skinny_m32n64k64s3_nt", DT_F32, 64, 64, 3, 2, 0),
     SKINNY_M("bf16_skinny_m64n64k128s3_nt", DT_BF16, 64, 128, 3, 4, 2),
     SKINNY_M("f16_skinny_m64n64k128s3_nt", DT_F16, 64, 128, 3, 4, 2),
     SKINNY_M("bf16_skinny_m64n128k128s3_nt", DT_BF16, 128, 128, 3, 4, 3),
     SKINNY_M("f16_skinny_m64n128k128s3_nt", DT_F16, 128, 128, 3, 4, 3),
-    SKINNY_M("f32_skinny_m64n64k64s3_nt", DT_F32, 64, 64, 3, 4, 2),
+    SKINNY_MP("f32_skinny_m64n64k64s3w8p_nt", DT_F32, 64, 64, 3, 4, 2, 2),
+    SKINNY_MP("f32_skinny_m64n64k64s3p_nt", DT_F32, 64, 64, 3, 4, 1, 0),
+    SKINNY_M("f32_skinny_m64n64k64s3_nt", DT_F32, 64, 64, 3, 4, 0),
     // (more blocks, M up to 128 or 256, measured no better than the tiled kernels: the M x K operand, re-read by
     // every workgroup from the L2, then outweighs B: bf16 128x28672x8192 111 us against 114, 256x... behind)
     // B stored K x N: 512 bytes of every k-row per workgroup, 128 bytes of K per stage

@@ -398,7 +398,8 @@ def test_streaming_plans_cover_m_up_to_64_fp32_and_b_stored_k_by_n():
     assert "skinny_m64n128" in info(64, 28672, 8192, f16, 0, 1)
     assert "skinny" not in info(65, 28672, 8192, bf, 0, 1)
     assert "f32_skinny_m16" in info(16, 16384, 16384, f32, 0, 1)
-    assert "f32_skinny_m64n64k64s3_nt" in info(64, 16384, 8192, f32, 0, 1)
+    assert "f32_skinny_m64n64k64s3w8p_nt" in info(64, 16384, 8192, f32, 0, 1)    # MFMA bound: two waves per 16 rows, pipelined loop
+    assert "f32_skinny_m32n64k64s3w8p_nt" in info(24, 16384, 8192, f32, 0, 1)
     # B stored K x N
     assert "bf16_skinny_m16n256k64s4_nn" in info(16, 28672, 8192, bf, 0, 0)
     assert "f16_skinny_m64n256k64s4_nn" in info(48, 28672, 8192, f16, 0, 0)
