@@ -45,14 +45,14 @@ PEAK_HBM_GBS = 8000.0
 MEASURED_TRAFFIC = {
     "C3": ("bf16_m256x256w4a3_nt", 1, 1.746e9),
     "C3b": ("bf16_m256x256w4a3_nt", 1, 2.352e8),
-    "C5": ("bf16_skinny16s3_nt", 1, 5.567e8),
+    "C5": ("bf16_skinny16s3_nt", 1, 5.569e8),
     "C2": ("f32_t256x256w4a3_nn", 1, 5.380e8),
     "C4": ("f16_m256x256w4a3_nn", 1, 7.340e8),
     "S16_bf16_kn": ("bf16_skinny_m16n256k64s4_nn", 2, 4.803e8),
     "S64_f16": ("f16_skinny_m64n128k128s3_nt", 1, 5.401e8),
     "S16_f32": ("f32_skinny_m16n64k128s3_nt", 1, 1.2091e9),
     "P2k_f16": ("f16_m128x128k128w4a3_nn", 1, 5.90e7),
-    "D128_bf16": ("bf16_m128x128k128w4a3_nt", 1, 5.082e8),
+    "D128_bf16": ("bf16_m128x128k128w4a3_nt", 1, 5.088e8),
 }
 
 
