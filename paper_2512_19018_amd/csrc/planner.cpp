@@ -125,14 +125,17 @@ static double tiled_cost(const Variant &v, const peak_gemm_desc_t &d, int split)
     if (v.mf16 && v.bm == 128 && v.bn == 128 && (v.ns > 2 || v.bk == 128))
         eff *= tiles > num_cu() ? 0.85 : kdepth > 16384.0 ? 0.8 : kdepth > 8192.0 ? 1.1 : 1.3;
     else if (v.mf16 && v.bm == 128 && v.bn == 128 && tiles <= num_cu())
-        eff *= 0.85;                                    // the two-workgroups-per-CU form with a CU to itself
+        eff *= kdepth > 8192.0 ? 0.72 : 0.85;           // the two-workgroups-per-CU form with a CU to itself
     else if (v.dt != PEAK_DT_F32 && v.bm * v.bn < 256 * 256 && kdepth > 8192.0)
         eff *= 0.85;                                    // likewise the other tiles below 256 x 256 (256 x 128 at 512x8192x28672 in two slices: 264 us)
     // The small tiles of the 32x32x16 kernels hide the loads' latency behind the other workgroups of their CU.
     // Where there is at most one round of them and K is deep, each K tile waits out a trip to memory
     // (bf16 512x4096x4096: 128x64 tiles 37 us, the 128 x 128 forms above 26; f16 NN likewise 37 against 29).
     if (v.dt != PEAK_DT_F32 && !v.mf16 && v.bm * v.bn < 256 * 128 && tiles <= num_cu() && kdepth >= 2048.0) eff *= 0.6;
-    if (v.atr) eff *= 1.5;                              // likewise A; the alternative is the register-staged general tile
+    // (A staged as [k][m] rows gets no factor of its own: every direct kernel for an A stored K x M stages it that
+    // way, the register-staged general tile is marked down above, and a factor here would only shrink the tile work
+    // against the cost of a K split's reduction - bf16 512x8192x28672 TN: 128x128 tiles unsplit 347 us, the
+    // 256x256 tile in four slices 206)
     if (v.dt == PEAK_DT_F32 && v.ns == 3) eff *= 0.97;
     const double fixed = 12.0e6;                    // prologue + epilogue of one tile, same units
     // K slices write and re-read fp32 partials: about 9 units per element and slice when they go
