@@ -53,6 +53,7 @@ MEASURED_TRAFFIC = {
     "S16_f32": ("f32_skinny_m16n64k128s3_nt", 1, 1.2091e9),
     "P2k_f16": ("f16_m128x128k128w4a3_nn", 1, 5.90e7),
     "D128_bf16": ("bf16_m128x128k128w4a3_nt", 1, 5.088e8),
+    "S64_f32": ("f32_skinny_m64n64k64s3w8p_nt", 1, 8.088e8),
 }
 
 
@@ -501,7 +502,7 @@ def main():
     if not args.only:
         others = []
         for name in ["C1", "C2", "C3b", "C4", "C5", "P2k_f32", "P4k_f32", "P2k_f16", "P4k_f16", "T4k_bf16_tn", "T4k_bf16_tt", "SK_bf16",
-                     "S32_bf16", "S64_f16", "S16_f32", "S16_bf16_kn", "S16_f32_kn", "S32_f16_tn", "S16_bf16_tt", "D128_bf16"]:
+                     "S32_bf16", "S64_f16", "S16_f32", "S16_bf16_kn", "S16_f32_kn", "S64_f32", "S32_f16_tn", "S16_bf16_tt", "D128_bf16"]:
             if name == args.workload:
                 continue
             small = pi.WORKLOADS[name].flops < 5e10          # short launches: more of them, or the figure is noise

@@ -236,6 +236,9 @@ WORKLOADS = {
                             "bf16 skinny 16x28672x8192 NN, B stored K x N (HBM bound)"),
     "S16_f32_kn": Workload("S16_f32_kn", F32, 16, 28672, 8192, 0, 0, 1.0, 0.0, "normal", 0.02, 16,
                            "fp32 skinny 16x28672x8192 NN, B stored K x N (HBM bound)"),
+    # fp32 with four 16-row blocks: bound by the fp32 MFMA rate, not by HBM
+    "S64_f32": Workload("S64_f32", F32, 64, 16384, 8192, 0, 1, 1.0, 0.0, "normal", 0.02, 20,
+                        "fp32 skinny 64x16384x8192 NT (fp32 MFMA bound)"),
     # ... and with the small operand stored K x M (the streaming kernels read a copy written out along K)
     "S32_f16_tn": Workload("S32_f16_tn", F16, 32, 28672, 8192, 1, 0, 1.0, 0.0, "normal", 0.02, 18,
                            "f16 skinny 32x28672x8192 TN, A stored K x M, B stored K x N (HBM bound)"),

@@ -41,7 +41,7 @@ CASES = [("C1", 256, None), ("C2", 2, None), ("C3", 3, None), ("C3b", 3, None), 
          ("T4k_bf16_tn", 3, None), ("T4k_bf16_tt", 3, None), ("SK_bf16", 2, None),
          # the streaming path beyond M <= 16 / 16 bits / B along K: every row
          ("S32_bf16", 32, None), ("S64_f16", 64, None), ("S16_f32", 16, None), ("S16_bf16_kn", 16, None),
-         ("S16_f32_kn", 16, None),
+         ("S16_f32_kn", 16, None), ("S64_f32", 64, None),
          # ... and with A stored K x M: the run writes A out along K first
          ("S32_f16_tn", 32, None), ("S16_bf16_tt", 16, None),
          # one row of tiles of the 16x16x32 kernels: workgroups start at different K tiles
