@@ -426,7 +426,18 @@ def test_streaming_variants_with_a_stored_k_by_m(gu, oracle, dtype, transB):
     got, raw, info = gu.run_gemm(dtype, 1, transB, M, N, K, 1.0, 0.0, A, B, gu.nan_fill(M, N, dtype))
     assert "skinny" in info and info.endswith("acopy=1"), info
     gu.check_against_oracle(oracle, got, dtype, 1, transB, M, N, K, 1.0, A, B, 0.0, C, what=(info, M, N, K))
+    # B one element into its allocation: the run takes the plan's register-staged stand-in, which reads A as it lies
+    Bflat = np.concatenate([np.zeros(1, B.dtype), B.reshape(-1)]).reshape(1, -1)
     import torch
+    dA, dB, dC = gu.to_dev(A), gu.to_dev(Bflat), gu.to_dev(gu.nan_fill(M, N, dtype))
+    with gu.pg.Plan(M, N, K, dtype, 1, transB, A.shape[1], B.shape[1], N) as plan:
+        ws = torch.empty(max(plan.workspace_bytes, 256), dtype=torch.uint8, device="cuda")
+        plan.run(1.0, dA.data_ptr(), dB.data_ptr() + es, 0.0, dC.data_ptr(), ws.data_ptr(), plan.workspace_bytes,
+                 torch.cuda.current_stream().cuda_stream)
+        torch.cuda.synchronize()
+        info2 = plan.info()
+    got = pi.to_f64(np.ascontiguousarray(gu.from_dev(dC, dtype)[:M, :N]), dtype)
+    gu.check_against_oracle(oracle, got, dtype, 1, transB, M, N, K, 1.0, A, B, 0.0, C, what=(info2, "B base off 16 bytes"))
     with gu.pg.Plan(M, N, K, dtype, 1, transB) as plan:
         assert plan.workspace_bytes >= M * K * es
         dA, dB, dC = gu.to_dev(A), gu.to_dev(B), gu.to_dev(C)
