@@ -319,6 +319,30 @@ def test_shipped_selector_table_is_loaded_by_default():
     assert _plan_info_in_fresh_process({}, (777, 512, 1024)) == _plan_info_in_fresh_process({"PEAK_GEMM_TUNING": ""}, (777, 512, 1024))
 
 
+def test_every_row_of_the_shipped_table_is_honoured():
+    """A row the library cannot follow (a variant that does not fit the row's shape, a split it would
+    clamp) is silently ignored at create: every shipped row must come back as the plan of its shape."""
+    import subprocess
+    import sys
+    code = (
+        "import sys; sys.path.insert(0, %r); import paper_2512_19018_amd as pg\n"
+        "dts = {'f32': pg.PEAK_DT_F32, 'f16': pg.PEAK_DT_F16, 'bf16': pg.PEAK_DT_BF16}\n"
+        "bad = []\n"
+        "for l in open(%r):\n"
+        "    r = l.split('#')[0].split()\n"
+        "    if not r: continue\n"
+        "    with pg.Plan(int(r[3]), int(r[4]), int(r[5]), dts[r[0]], int(r[1]), int(r[2])) as p:\n"
+        "        i = p.info()\n"
+        "    if (':%%s ' %% r[6]) not in i or ('split=%%s ' %% r[7]) not in i or ' streamk=0 ' not in i: bad.append((r, i))\n"
+        "print(len(bad)); [print(b) for b in bad[:5]]\n"
+        % (ROOT, os.path.join(ROOT, "paper_2512_19018_amd", "peak_gemm_tuning.txt")))
+    env = dict(os.environ)
+    env.pop("PEAK_GEMM_TUNING", None)
+    r = subprocess.run([sys.executable, "-c", code], capture_output=True, text=True, timeout=300, env=env)
+    assert r.returncode == 0, r.stderr
+    assert r.stdout.split()[0] == "0", r.stdout
+
+
 def test_plans_keep_a_stand_in_for_unaligned_operand_bases():
     # rows suit the 16-byte copies: a direct variant, with a register-staged stand-in for odd base addresses
     with pg.Plan(512, 512, 1024, pg.PEAK_DT_BF16, 0, 1) as p:
